@@ -1,0 +1,193 @@
+/*
+ * cq.h -- C ABI of the MI355X (gfx950) library for the forward pass of a low-precision
+ * Mixture-of-Experts expert layer in the CodeQuant deployment format.
+ *
+ * The layer (paper: Methodology, "Activation-Oriented Outlier Smoothing", "Adaptive Weight
+ * Clustering and Centroid Finetuning", "CodeQuant Kernel and System Implementation"):
+ *   X_R = X R                      rotation by the orthogonal matrix R         (AOS section)
+ *   q, s = Q(X_R)                  integer quantization, symmetric per token    (AOS objective)
+ *   Pi   = top-k of X_R Wr^T       the router is a linear layer                 (AOS section)
+ *   X_t  = tokens of each expert   grouping by expert                           (AOS section)
+ *   W_c[i,j] = sum_k C[i,k] A[i,j,k]   weights exist only as a 4-bit index per weight into a
+ *                                  16-entry centroid table per output row       (Eq. W_c)
+ *   o    = (SiLU(a Wg_c^T) . a Wu_c^T) Wd_c^T,  a = s q                          (invariance eq.)
+ *   Y    = sum_j Pi_j o_j + shared experts                                      (MoE case of Eq. L)
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; the library neither allocates
+ *     nor frees device memory inside these calls and never synchronises the host.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream).
+ *   - Buffers must be 16-byte aligned.  Matrices are row-major.
+ *   - Arguments are validated BEFORE any HIP call; on a bad argument nothing is launched.
+ *   - Return value: CQ_OK or one of the error codes below; cq_status_string() names them.
+ *   - Weight matrices are in [out, in] layout: row n holds the K input weights of output n.
+ */
+#ifndef CQ_H_
+#define CQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int cq_status;
+enum {
+  CQ_OK = 0,
+  CQ_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+  CQ_ERR_SHAPE = 2,       /* non-positive size, top_k > E, H or I not a multiple of 64 ... */
+  CQ_ERR_UNSUPPORTED = 3, /* act_bits not in {4,8}, unknown enum value                     */
+  CQ_ERR_WORKSPACE = 4,   /* workspace NULL or smaller than the *_workspace_bytes() figure */
+  CQ_ERR_HIP = 5          /* a HIP runtime call failed (launch error, no device)           */
+};
+
+typedef void* cq_stream; /* hipStream_t */
+
+#define CQ_N_CENTROIDS 16
+
+/* kinds of the activation operand of cq_codebook_grouped_gemm */
+enum { CQ_A_INT8_CODES = 0, /* int8 container holding integer codes (|q| <= 127)          */
+       CQ_A_F16 = 1,        /* IEEE half                                                    */
+       CQ_A_F32 = 2 };      /* float; rounded to half (RNE, saturating) when staged         */
+/* epilogues */
+enum { CQ_EPI_NONE = 0,     /* out[m, n] = scale[m] * sum_k W_c[n,k] a[m,k]                 */
+       CQ_EPI_SWIGLU = 1 }; /* N = 2I rows interleaved (2i = gate i, 2i+1 = up i):
+                               out[m, i] = SiLU(g) * u                                      */
+/* kinds of the output */
+enum { CQ_OUT_F32 = 0, CQ_OUT_F16 = 1 };
+
+/*
+ * A group (expert) array of clustered weight matrices (Eq. W_c; 16 centroids, paper's W4 budget).
+ *   idx       [G, N, K/2] bytes, canonical: byte j of a row = index of weight 2j in bits 0-3 and
+ *             of weight 2j+1 in bits 4-7.  May be NULL if `prepacked` is given.
+ *   cent      [G, N, 16] bf16 bit patterns: row n's centroid table.
+ *   prepacked optional kernel-native copy of idx written by cq_prepack() (same byte count):
+ *             rows are taken 32 at a time and K 64 weights at a time; the 1 KiB tile of row block
+ *             rb and K step s is at ((rb*(K/64) + s) * 1024) and holds, for l = 0..63, the 16
+ *             canonical bytes of row rb*32 + l%32, byte columns s*32 + (l/32)*16 .. +15, at l*16.
+ *   K must be a multiple of 64 and N a multiple of 64.
+ */
+typedef struct {
+  const uint8_t* idx;
+  const uint16_t* cent;
+  const void* prepacked;
+  int G, N, K;
+} cq_codebook_weights;
+
+/* One MoE expert layer.  Groups 0..E-1 are routed experts, E..E+S-1 always-on shared experts. */
+typedef struct {
+  int H, I, E, top_k, S, act_bits;
+  const float* R;     /* [H, H] orthogonal, X_R = X R                                   */
+  const float* Wr;    /* [E, H] router weight in the rotated basis                      */
+  const float* bias;  /* [E] or NULL                                                    */
+  cq_codebook_weights gate_up; /* G = E+S, N = 2I (gate/up interleaved), K = H          */
+  cq_codebook_weights down;    /* G = E+S, N = H, K = I                                 */
+} cq_layer;
+
+const char* cq_status_string(cq_status st);
+
+/*
+ * a1 + a2: X_R = X R (AOS section) and per-token symmetric integer quantization Q(X_R).
+ *   X [T,H] f32, R [H,H] f32  ->  XR_out [T,H] f32 (the router reads it), Q_out [T,H] int8
+ *   codes in [-qmax, qmax] with qmax = 2^(act_bits-1)-1, scale_out [T] f32 = max|X_R[t,:]|/qmax
+ *   (1 for an all-zero row).  Rounding is to nearest, ties to even.  The product is accumulated
+ *   in fp32 on fp32 matrix cores so that codes differ from an exact evaluation only at ties.
+ *   H % 64 == 0.  workspace: cq_rotate_quant_workspace_bytes(T, H) bytes.
+ */
+size_t cq_rotate_quant_workspace_bytes(int T, int H);
+cq_status cq_rotate_quant(const float* X, const float* R, int T, int H, int act_bits,
+                          float* XR_out, int8_t* Q_out, float* scale_out,
+                          void* workspace, size_t workspace_bytes, cq_stream stream);
+
+/*
+ * a3 + a4 + a5: router logits L = X_R Wr^T (+bias) in fp32, top-k by descending logit (equal
+ * logits -> lower expert id), weights = softmax over the k selected logits, and the stable
+ * grouping of assignments a = t*k + j by expert ("tokens assigned to that expert", AOS section).
+ *   XR [T,H] or NULL; if NULL, logits_in [T,E] is used as the logits (bias is then ignored).
+ *   Outputs: logits_out [T,E] or NULL; topk_ids [T,k] i32; topk_w [T,k] f32;
+ *   expert_offsets [E+S+1] i32; perm [T*k] (sorted position -> a); inv_perm [T*k] (a -> position);
+ *   src_token [T*(k+S)] or NULL: token whose activations feed each sorted row.
+ *   n_shared = S appends S always-on groups E..E+S-1, each holding all T tokens in order
+ *   (rows T*k + s*T + t); they are not part of the softmax.
+ *   1 <= top_k <= min(E, 64), E <= 1024, H % 64 == 0.
+ *   workspace: cq_route_permute_workspace_bytes(T, H, E, top_k) bytes.
+ */
+size_t cq_route_permute_workspace_bytes(int T, int H, int E, int top_k);
+cq_status cq_route_permute(const float* XR, const float* Wr, const float* bias, const float* logits_in,
+                           int T, int H, int E, int top_k, int n_shared,
+                           float* logits_out, int32_t* topk_ids, float* topk_w,
+                           int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm, int32_t* src_token,
+                           void* workspace, size_t workspace_bytes, cq_stream stream);
+
+/*
+ * a6 / a7: grouped product with clustered weights (Eq. W_c): for every group g and every sorted
+ * row m in [group_offsets[g], group_offsets[g+1]):
+ *     acc[m, n] = sum_k W_c^{(g)}[n, k] * A[src(m), k],  src(m) = row_gather ? row_gather[m] : m
+ *     out[m, n] = (row_scale ? row_scale[src(m)] : 1) * acc[m, n]          (CQ_EPI_NONE, N outputs)
+ *     out[m, i] = SiLU(sc*acc[m,2i]) * (sc*acc[m,2i+1])                    (CQ_EPI_SWIGLU, N/2 outputs)
+ *   Weights are never materialised: packed indices stream from HBM, are turned into centroid
+ *   values through a table staged in LDS, and feed the matrix cores directly.  Integer codes and
+ *   bf16 centroids are exact operands (bf16 MFMA, fp32 accumulation); CQ_A_F16 / CQ_A_F32 rows
+ *   use f16 MFMA with centroids converted bf16 -> f16.
+ *   A: [rows, K] of a_kind.  out: [M_total, N or N/2] of out_kind (CQ_OUT_F16 saturates).
+ *   group_offsets [G+1] device i32, non-decreasing, group_offsets[G] <= M_total.  Empty groups ok.
+ *   workspace: cq_grouped_gemm_workspace_bytes(W, M_total) bytes (may be 0 -> NULL allowed).
+ */
+size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, int M_total);
+cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W,
+                                   const void* A, int a_kind,
+                                   const float* row_scale, const int32_t* row_gather,
+                                   const int32_t* group_offsets, int M_total,
+                                   int epilogue, void* out, int out_kind,
+                                   void* workspace, size_t workspace_bytes, cq_stream stream);
+
+/*
+ * a8: weighted combine (MoE weighted sum; shared expert per the appendix on DeepSeek-V2-Lite):
+ *   Y[t,:] = sum_{j<k} topk_w[t,j] * O[inv_perm[t*k+j], :] + sum_{s<S} O[T*k + s*T + t, :]
+ * summed in the fixed order j = 0..k-1, then s = 0..S-1 (deterministic).  O [T*(k+S), H] f32.
+ */
+cq_status cq_combine(const float* O, const float* topk_w, const int32_t* inv_perm,
+                     int T, int H, int top_k, int n_shared, float* Y, cq_stream stream);
+
+/*
+ * The whole layer, a1..a8, on one stream with no host synchronisation:
+ *   X [T,H] f32 -> Y [T,H] f32 (in the rotated basis; no R^T is applied).
+ * workspace: cq_moe_workspace_bytes(L, T) bytes.  Intermediates live in the workspace; their
+ * locations are reported by cq_moe_workspace_layout() for inspection by tests.
+ */
+typedef struct {
+  size_t total;
+  size_t XR, Q, scale, logits, topk_ids, topk_w, offsets, perm, inv_perm, src_token, Hbuf, Obuf, scratch;
+} cq_moe_layout;
+size_t cq_moe_workspace_bytes(const cq_layer* L, int T);
+cq_status cq_moe_workspace_layout(const cq_layer* L, int T, cq_moe_layout* out);
+cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y,
+                         void* workspace, size_t workspace_bytes, cq_stream stream);
+
+/*
+ * Offline, one-time re-layout of canonical indices into the kernel-native tile order described at
+ * cq_codebook_weights (the paper's pipeline is fully offline, so the stored order is free; the
+ * byte count streamed is unchanged).  dst must hold cq_prepack_bytes(W) bytes.
+ */
+size_t cq_prepack_bytes(const cq_codebook_weights* W);
+cq_status cq_prepack(const cq_codebook_weights* W, void* dst, size_t dst_bytes, cq_stream stream);
+
+/*
+ * Test hook for the bit-exact decode check: writes W_c of group g as bf16 bit patterns [N, K],
+ * reading `prepacked` if present, else `idx` (Eq. W_c).
+ */
+cq_status cq_decode_dense(const cq_codebook_weights* W, int g, uint16_t* Wc_bf16, cq_stream stream);
+
+/* Device facts used for rooflines: writes CU count, max clock (kHz), memory clock (kHz), memory
+ * bus width (bits), LDS bytes per workgroup. Returns CQ_ERR_HIP when no device is present. */
+cq_status cq_device_info(int* cu_count, int* clock_khz, int* mem_clock_khz, int* bus_bits, int* lds_bytes);
+
+/* Plain streaming read of `bytes` bytes (16-byte multiples) used to measure the achievable HBM
+ * read ceiling next to the nominal one; the 16-byte XOR of everything read lands in sink[0..3]. */
+cq_status cq_stream_read(const void* src, size_t bytes, uint32_t* sink, cq_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CQ_H_ */

@@ -1,0 +1,347 @@
+"""Thin ctypes binding of libcq.so: argument marshalling only.
+
+Every step of the layer runs in the HIP kernels behind the C ABI declared in include/cq.h; the
+functions here carry the same names, allocate outputs and workspaces as torch tensors (device
+memory and streams are all torch is used for) and pass raw device pointers through.  There is no
+CPU fallback: if the library has not been built, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libcq.so")
+
+CQ_OK = 0
+CQ_A_INT8_CODES, CQ_A_F16, CQ_A_F32 = 0, 1, 2
+CQ_EPI_NONE, CQ_EPI_SWIGLU = 0, 1
+CQ_OUT_F32, CQ_OUT_F16 = 0, 1
+
+EXPORTS = [
+    "cq_status_string", "cq_rotate_quant_workspace_bytes", "cq_rotate_quant",
+    "cq_route_permute_workspace_bytes", "cq_route_permute", "cq_grouped_gemm_workspace_bytes",
+    "cq_codebook_grouped_gemm", "cq_combine", "cq_moe_workspace_bytes", "cq_moe_workspace_layout",
+    "cq_moe_forward", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
+    "cq_stream_read",
+]
+
+
+class CodebookWeights(ctypes.Structure):
+    _fields_ = [("idx", ctypes.c_void_p), ("cent", ctypes.c_void_p), ("prepacked", ctypes.c_void_p),
+                ("G", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int)]
+
+
+class Layer(ctypes.Structure):
+    _fields_ = [("H", ctypes.c_int), ("I", ctypes.c_int), ("E", ctypes.c_int), ("top_k", ctypes.c_int),
+                ("S", ctypes.c_int), ("act_bits", ctypes.c_int),
+                ("R", ctypes.c_void_p), ("Wr", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+                ("gate_up", CodebookWeights), ("down", CodebookWeights)]
+
+
+class MoeLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in
+                ("total", "XR", "Q", "scale", "logits", "topk_ids", "topk_w", "offsets", "perm", "inv_perm",
+                 "src_token", "Hbuf", "Obuf", "scratch")]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libcq.so (after torch when torch is importable, so both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_10496_amd.build` "
+                           "(there is no fallback path)")
+    try:
+        import torch  # noqa: F401  (maps torch's libamdhip64 first)
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.cq_status_string.restype = ctypes.c_char_p
+    lib.cq_status_string.argtypes = [ci]
+    lib.cq_rotate_quant_workspace_bytes.restype = sz
+    lib.cq_rotate_quant_workspace_bytes.argtypes = [ci, ci]
+    lib.cq_rotate_quant.restype = ci
+    lib.cq_rotate_quant.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.cq_route_permute_workspace_bytes.restype = sz
+    lib.cq_route_permute_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.cq_route_permute.restype = ci
+    lib.cq_route_permute.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cq_grouped_gemm_workspace_bytes.restype = sz
+    lib.cq_grouped_gemm_workspace_bytes.argtypes = [ctypes.POINTER(CodebookWeights), ci]
+    lib.cq_codebook_grouped_gemm.restype = ci
+    lib.cq_codebook_grouped_gemm.argtypes = [ctypes.POINTER(CodebookWeights), vp, ci, vp, vp, vp, ci, ci, vp, ci,
+                                             vp, sz, vp]
+    lib.cq_combine.restype = ci
+    lib.cq_combine.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+    lib.cq_moe_workspace_bytes.restype = sz
+    lib.cq_moe_workspace_bytes.argtypes = [ctypes.POINTER(Layer), ci]
+    lib.cq_moe_workspace_layout.restype = ci
+    lib.cq_moe_workspace_layout.argtypes = [ctypes.POINTER(Layer), ci, ctypes.POINTER(MoeLayout)]
+    lib.cq_moe_forward.restype = ci
+    lib.cq_moe_forward.argtypes = [ctypes.POINTER(Layer), vp, ci, vp, vp, sz, vp]
+    lib.cq_prepack_bytes.restype = sz
+    lib.cq_prepack_bytes.argtypes = [ctypes.POINTER(CodebookWeights)]
+    lib.cq_prepack.restype = ci
+    lib.cq_prepack.argtypes = [ctypes.POINTER(CodebookWeights), vp, sz, vp]
+    lib.cq_decode_dense.restype = ci
+    lib.cq_decode_dense.argtypes = [ctypes.POINTER(CodebookWeights), ci, vp, vp]
+    lib.cq_device_info.restype = ci
+    lib.cq_device_info.argtypes = [ctypes.POINTER(ci)] * 5
+    lib.cq_stream_read.restype = ci
+    lib.cq_stream_read.argtypes = [vp, sz, vp, vp]
+    _lib = lib
+    return lib
+
+
+class CqError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(load_library().cq_status_string(status).decode())
+
+
+def _check(st: int) -> None:
+    if st != CQ_OK:
+        raise CqError(st)
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("libcq needs a GPU: torch.cuda.is_available() is False and there is no CPU path")
+    return torch
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(nbytes: int):
+    torch = _torch()
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+# ------------------------------------------------------------------------------------------------
+# weights
+# ------------------------------------------------------------------------------------------------
+class DeviceCodebook:
+    """Device-resident [G, N, K/2] indices + [G, N, 16] bf16 tables, optionally prepacked."""
+
+    def __init__(self, idx, cent, prepack: bool = True, keep_canonical: bool = True):
+        torch = _torch()
+        import numpy as np
+        if isinstance(idx, np.ndarray):
+            idx = torch.from_numpy(np.ascontiguousarray(idx))
+        if isinstance(cent, np.ndarray):
+            cent = torch.from_numpy(np.ascontiguousarray(cent).view(np.int16))
+        assert idx.dtype == torch.uint8 and idx.dim() == 3 and cent.dtype == torch.int16
+        self.G, self.N, self.K = int(idx.shape[0]), int(idx.shape[1]), int(idx.shape[2]) * 2
+        assert tuple(cent.shape) == (self.G, self.N, 16)
+        self.cent = cent.to("cuda").contiguous()
+        self.idx = idx.to("cuda").contiguous()
+        self.prepacked = None
+        if prepack:
+            self.prepacked = cq_prepack(self)
+            if not keep_canonical:
+                self.idx = None
+
+    def struct(self, use_prepacked: bool = True) -> CodebookWeights:
+        pre = self.prepacked if use_prepacked else None
+        return CodebookWeights(_ptr(self.idx), _ptr(self.cent), _ptr(pre), self.G, self.N, self.K)
+
+
+def cq_prepack(W: DeviceCodebook):
+    torch = _torch()
+    lib = load_library()
+    s = W.struct(use_prepacked=False)
+    n = lib.cq_prepack_bytes(ctypes.byref(s))
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    _check(lib.cq_prepack(ctypes.byref(s), _ptr(dst), n, _stream()))
+    return dst
+
+
+def cq_decode_dense(W: DeviceCodebook, g: int, use_prepacked: bool = True):
+    torch = _torch()
+    lib = load_library()
+    out = torch.empty((W.N, W.K), dtype=torch.int16, device="cuda")
+    s = W.struct(use_prepacked)
+    _check(lib.cq_decode_dense(ctypes.byref(s), g, _ptr(out), _stream()))
+    return out
+
+
+# ------------------------------------------------------------------------------------------------
+# steps
+# ------------------------------------------------------------------------------------------------
+def cq_rotate_quant(X, R, act_bits: int) -> Dict[str, object]:
+    torch = _torch()
+    lib = load_library()
+    T, H = X.shape
+    XR = torch.empty((T, H), dtype=torch.float32, device="cuda")
+    Q = torch.empty((T, H), dtype=torch.int8, device="cuda")
+    scale = torch.empty((T,), dtype=torch.float32, device="cuda")
+    n = lib.cq_rotate_quant_workspace_bytes(T, H)
+    ws = _ws(n)
+    _check(lib.cq_rotate_quant(_ptr(X), _ptr(R), T, H, act_bits, _ptr(XR), _ptr(Q), _ptr(scale), _ptr(ws), ws.numel(),
+                               _stream()))
+    return {"XR": XR, "Q": Q, "scale": scale}
+
+
+def cq_route_permute(XR, Wr, bias, top_k: int, n_shared: int = 0, logits_in=None) -> Dict[str, object]:
+    torch = _torch()
+    lib = load_library()
+    if XR is not None:
+        T, H = XR.shape
+        E = Wr.shape[0]
+    else:
+        T, E = logits_in.shape
+        H = 64
+    A = T * top_k
+    i32 = dict(dtype=torch.int32, device="cuda")
+    out = {
+        "logits": torch.empty((T, E), dtype=torch.float32, device="cuda"),
+        "ids": torch.empty((T, top_k), **i32),
+        "w": torch.empty((T, top_k), dtype=torch.float32, device="cuda"),
+        "offsets": torch.empty((E + n_shared + 1,), **i32),
+        "perm": torch.empty((A,), **i32),
+        "inv_perm": torch.empty((A,), **i32),
+        "src_token": torch.empty((T * (top_k + n_shared),), **i32),
+    }
+    n = lib.cq_route_permute_workspace_bytes(T, H, E, top_k)
+    ws = _ws(n)
+    _check(lib.cq_route_permute(_ptr(XR), _ptr(Wr), _ptr(bias), _ptr(logits_in), T, H, E, top_k, n_shared,
+                                _ptr(out["logits"]), _ptr(out["ids"]), _ptr(out["w"]), _ptr(out["offsets"]),
+                                _ptr(out["perm"]), _ptr(out["inv_perm"]), _ptr(out["src_token"]), _ptr(ws),
+                                ws.numel(), _stream()))
+    return out
+
+
+def cq_codebook_grouped_gemm(W: DeviceCodebook, A, a_kind: int, row_scale, row_gather, group_offsets, M_total: int,
+                             epilogue: int, out_kind: int, use_prepacked: bool = True):
+    torch = _torch()
+    lib = load_library()
+    n_out = W.N // 2 if epilogue == CQ_EPI_SWIGLU else W.N
+    out = torch.empty((M_total, n_out), dtype=torch.float16 if out_kind == CQ_OUT_F16 else torch.float32,
+                      device="cuda")
+    s = W.struct(use_prepacked)
+    n = lib.cq_grouped_gemm_workspace_bytes(ctypes.byref(s), M_total)
+    ws = _ws(n)
+    _check(lib.cq_codebook_grouped_gemm(ctypes.byref(s), _ptr(A), a_kind, _ptr(row_scale), _ptr(row_gather),
+                                        _ptr(group_offsets), M_total, epilogue, _ptr(out), out_kind, _ptr(ws),
+                                        ws.numel(), _stream()))
+    return out
+
+
+def cq_combine(O, topk_w, inv_perm, T: int, H: int, top_k: int, n_shared: int = 0):
+    torch = _torch()
+    lib = load_library()
+    Y = torch.empty((T, H), dtype=torch.float32, device="cuda")
+    _check(lib.cq_combine(_ptr(O), _ptr(topk_w), _ptr(inv_perm), T, H, top_k, n_shared, _ptr(Y), _stream()))
+    return Y
+
+
+class DeviceLayer:
+    """All constant inputs of one layer on the device, plus a reusable workspace."""
+
+    def __init__(self, cfg, R, Wr, bias, gate_up: DeviceCodebook, down: DeviceCodebook, use_prepacked: bool = True):
+        torch = _torch()
+        self.cfg = cfg
+        self.R = torch.as_tensor(R).to("cuda").contiguous()
+        self.Wr = torch.as_tensor(Wr).to("cuda").contiguous()
+        self.bias = None if bias is None else torch.as_tensor(bias).to("cuda").contiguous()
+        self.gate_up, self.down = gate_up, down
+        self.use_prepacked = use_prepacked
+        self._ws = None
+        self._ws_T = -1
+
+    def struct(self) -> Layer:
+        c = self.cfg
+        return Layer(c.H, c.I, c.E, c.top_k, c.S, c.act_bits, _ptr(self.R), _ptr(self.Wr), _ptr(self.bias),
+                     self.gate_up.struct(self.use_prepacked), self.down.struct(self.use_prepacked))
+
+    def workspace(self, T: int):
+        if self._ws is None or self._ws_T != T:
+            lib = load_library()
+            s = self.struct()
+            n = lib.cq_moe_workspace_bytes(ctypes.byref(s), T)
+            if n == 0:
+                raise CqError(2)
+            self._ws = _ws(n)
+            self._ws_T = T
+        return self._ws
+
+
+def cq_moe_forward(layer: DeviceLayer, X, Y=None):
+    torch = _torch()
+    lib = load_library()
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, layer.cfg.H), dtype=torch.float32, device="cuda")
+    ws = layer.workspace(T)
+    s = layer.struct()
+    _check(lib.cq_moe_forward(ctypes.byref(s), _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream()))
+    return Y
+
+
+def moe_intermediates(layer: DeviceLayer, T: int) -> Dict[str, object]:
+    """Views of the intermediates the last cq_moe_forward(layer, X[T]) left in the workspace."""
+    torch = _torch()
+    lib = load_library()
+    lay = MoeLayout()
+    s = layer.struct()
+    _check(lib.cq_moe_workspace_layout(ctypes.byref(s), T, ctypes.byref(lay)))
+    ws = layer.workspace(T)
+    c = layer.cfg
+    A, M = T * c.top_k, T * (c.top_k + c.S)
+
+    def view(off, nbytes, dtype, shape):
+        return ws[off:off + nbytes].view(dtype).view(shape)
+    return {
+        "XR": view(lay.XR, T * c.H * 4, torch.float32, (T, c.H)),
+        "Q": view(lay.Q, T * c.H, torch.int8, (T, c.H)),
+        "scale": view(lay.scale, T * 4, torch.float32, (T,)),
+        "logits": view(lay.logits, T * c.E * 4, torch.float32, (T, c.E)),
+        "ids": view(lay.topk_ids, A * 4, torch.int32, (T, c.top_k)),
+        "w": view(lay.topk_w, A * 4, torch.float32, (T, c.top_k)),
+        "offsets": view(lay.offsets, (c.E + c.S + 1) * 4, torch.int32, (c.E + c.S + 1,)),
+        "perm": view(lay.perm, A * 4, torch.int32, (A,)),
+        "inv_perm": view(lay.inv_perm, A * 4, torch.int32, (A,)),
+        "src_token": view(lay.src_token, M * 4, torch.int32, (M,)),
+        "h": view(lay.Hbuf, M * c.I * 2, torch.float16, (M, c.I)),
+        "o": view(lay.Obuf, M * c.H * 4, torch.float32, (M, c.H)),
+    }
+
+
+def device_layer_from_inputs(inputs, use_prepacked: bool = True) -> DeviceLayer:
+    """Upload a synth.LayerInputs (layout work only: stacking experts, interleaving gate/up rows)."""
+    from . import synth
+    st = synth.stack_experts(inputs)
+    gu = DeviceCodebook(st["gate_up_idx"], st["gate_up_cent"], prepack=use_prepacked)
+    dn = DeviceCodebook(st["down_idx"], st["down_cent"], prepack=use_prepacked)
+    return DeviceLayer(inputs.cfg, inputs.R, inputs.Wr, inputs.bias, gu, dn, use_prepacked)
+
+
+def cq_device_info() -> Dict[str, int]:
+    lib = load_library()
+    vals = [ctypes.c_int(0) for _ in range(5)]
+    _check(lib.cq_device_info(*[ctypes.byref(v) for v in vals]))
+    keys = ["cu_count", "clock_khz", "mem_clock_khz", "bus_bits", "lds_bytes"]
+    return {k: v.value for k, v in zip(keys, vals)}
+
+
+def cq_stream_read(buf):
+    torch = _torch()
+    lib = load_library()
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    _check(lib.cq_stream_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()))
+    return sink

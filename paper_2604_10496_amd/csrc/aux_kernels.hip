@@ -1,0 +1,160 @@
+// a8 (weighted combine) and the small helpers: offline prepack of the index bytes, the dense-decode
+// test hook, the streaming-read probe and device facts.
+#include "cq_internal.h"
+
+namespace {
+
+// Y[t,:] = sum_j w[t,j] * O[inv_perm[t*k+j], :] + sum_s O[T*k + s*T + t, :], fixed order.
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ O, const float* __restrict__ w,
+                                                      const int32_t* __restrict__ inv_perm, int T, int H, int k,
+                                                      int S, float* __restrict__ Y) {
+  const int t = blockIdx.x;
+  for (int c = threadIdx.x * 4; c < H; c += 256 * 4) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < k; ++j) {
+      const float wt = w[(size_t)t * k + j];
+      const size_t row = (size_t)inv_perm[(size_t)t * k + j];
+      const float4 o = *reinterpret_cast<const float4*>(O + row * H + c);
+      acc.x += wt * o.x; acc.y += wt * o.y; acc.z += wt * o.z; acc.w += wt * o.w;
+    }
+    for (int s = 0; s < S; ++s) {
+      const size_t row = (size_t)T * k + (size_t)s * T + t;
+      const float4 o = *reinterpret_cast<const float4*>(O + row * H + c);
+      acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+    }
+    *reinterpret_cast<float4*>(Y + (size_t)t * H + c) = acc;
+  }
+}
+
+// canonical [rows, K/2] -> tiles of 32 rows x 64 weights (1 KiB): lane l of a tile owns the 16 bytes
+// of row l%32, byte columns s*32 + (l/32)*16.
+__global__ __launch_bounds__(256) void prepack_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                      size_t n_rows, int K) {
+  const size_t n16 = n_rows * (size_t)(K / 32);  // 16-byte pieces in total
+  const int steps = K / 64;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+    const size_t tile = i >> 6;
+    const int l = (int)(i & 63);
+    const size_t rb = tile / steps;
+    const int s = (int)(tile - rb * steps);
+    const size_t row = rb * 32 + (l & 31);
+    const size_t piece = (size_t)s * 2 + (l >> 5);  // 16-byte piece inside the row
+    dst[i] = src[row * (size_t)(K / 32) + piece];
+  }
+}
+
+__global__ __launch_bounds__(256) void decode_dense_kernel(const uint8_t* __restrict__ idx, int prepacked,
+                                                           const uint16_t* __restrict__ cent, int N, int K,
+                                                           uint16_t* __restrict__ out) {
+  const size_t total = (size_t)N * (K / 2);
+  const int steps = K / 64;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t n = i / (K / 2);
+    const int bc = (int)(i - n * (K / 2));  // canonical byte column
+    size_t src = i;
+    if (prepacked) {
+      const int s = bc >> 5, g = (bc >> 4) & 1, within = bc & 15;
+      src = (((n >> 5) * steps + s) * 64 + g * 32 + (n & 31)) * 16 + within;
+    }
+    const uint32_t b = idx[src];
+    const uint16_t* c = cent + n * CQ_N_CENTROIDS;
+    out[n * K + 2 * bc] = c[b & 15u];
+    out[n * K + 2 * bc + 1] = c[b >> 4];
+  }
+}
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
+                                                          uint32_t* __restrict__ sink) {
+  uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc.x ^= a.x ^ b.x ^ c.x ^ d.x; acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
+    acc.z ^= a.z ^ b.z ^ c.z ^ d.z; acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 a = src[i];
+    acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
+  }
+  // keeps the loads alive; the branch is practically never taken
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) {
+    sink[0] = acc.x; sink[1] = acc.y; sink[2] = acc.z; sink[3] = acc.w;
+  }
+}
+
+}  // namespace
+
+extern "C" const char* cq_status_string(cq_status st) {
+  switch (st) {
+    case CQ_OK: return "CQ_OK";
+    case CQ_ERR_NULL: return "CQ_ERR_NULL: a required pointer is NULL";
+    case CQ_ERR_SHAPE: return "CQ_ERR_SHAPE: size out of range or not a multiple of the tile";
+    case CQ_ERR_UNSUPPORTED: return "CQ_ERR_UNSUPPORTED: unsupported bit width or enum value";
+    case CQ_ERR_WORKSPACE: return "CQ_ERR_WORKSPACE: workspace missing or too small";
+    case CQ_ERR_HIP: return "CQ_ERR_HIP: HIP runtime error";
+    default: return "unknown cq_status";
+  }
+}
+
+extern "C" cq_status cq_combine(const float* O, const float* topk_w, const int32_t* inv_perm, int T, int H,
+                                int top_k, int n_shared, float* Y, cq_stream stream) {
+  if (!O || !topk_w || !inv_perm || !Y) return CQ_ERR_NULL;
+  if (T <= 0 || H <= 0 || H % 4 != 0 || top_k <= 0 || n_shared < 0) return CQ_ERR_SHAPE;
+  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, (hipStream_t)stream, O, topk_w, inv_perm, T, H, top_k,
+                     n_shared, Y);
+  return cq_check_launch();
+}
+
+extern "C" size_t cq_prepack_bytes(const cq_codebook_weights* W) {
+  if (!W || W->G <= 0 || W->N <= 0 || W->K <= 0) return 0;
+  return (size_t)W->G * W->N * (W->K / 2);
+}
+
+extern "C" cq_status cq_prepack(const cq_codebook_weights* W, void* dst, size_t dst_bytes, cq_stream stream) {
+  if (!W || !W->idx || !dst) return CQ_ERR_NULL;
+  if (W->G <= 0 || W->N <= 0 || W->K <= 0 || W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;
+  if (dst_bytes < cq_prepack_bytes(W)) return CQ_ERR_WORKSPACE;
+  const size_t rows = (size_t)W->G * W->N;
+  const size_t n16 = rows * (W->K / 32);
+  const unsigned grid = (unsigned)((n16 + 255) / 256 < 65536 ? (n16 + 255) / 256 : 65536);
+  hipLaunchKernelGGL(prepack_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)W->idx,
+                     (uint4*)dst, rows, W->K);
+  return cq_check_launch();
+}
+
+extern "C" cq_status cq_decode_dense(const cq_codebook_weights* W, int g, uint16_t* Wc_bf16, cq_stream stream) {
+  if (!W || (!W->idx && !W->prepacked) || !W->cent || !Wc_bf16) return CQ_ERR_NULL;
+  if (W->G <= 0 || W->N <= 0 || W->K <= 0 || W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;
+  if (g < 0 || g >= W->G) return CQ_ERR_SHAPE;
+  const size_t gbytes = (size_t)W->N * (W->K / 2);
+  const uint8_t* src = (W->prepacked ? (const uint8_t*)W->prepacked : W->idx) + (size_t)g * gbytes;
+  const unsigned grid = (unsigned)((gbytes + 255) / 256 < 65536 ? (gbytes + 255) / 256 : 65536);
+  hipLaunchKernelGGL(decode_dense_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, src,
+                     W->prepacked ? 1 : 0, W->cent + (size_t)g * W->N * CQ_N_CENTROIDS, W->N, W->K, Wc_bf16);
+  return cq_check_launch();
+}
+
+extern "C" cq_status cq_device_info(int* cu_count, int* clock_khz, int* mem_clock_khz, int* bus_bits,
+                                    int* lds_bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return CQ_ERR_HIP;
+  struct { int* dst; hipDeviceAttribute_t attr; } q[] = {
+      {cu_count, hipDeviceAttributeMultiprocessorCount}, {clock_khz, hipDeviceAttributeClockRate},
+      {mem_clock_khz, hipDeviceAttributeMemoryClockRate}, {bus_bits, hipDeviceAttributeMemoryBusWidth},
+      {lds_bytes, hipDeviceAttributeMaxSharedMemoryPerBlock}};
+  for (auto& e : q) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, e.attr, dev) != hipSuccess) return CQ_ERR_HIP;
+    if (e.dst) *e.dst = v;
+  }
+  return CQ_OK;
+}
+
+extern "C" cq_status cq_stream_read(const void* src, size_t bytes, uint32_t* sink, cq_stream stream) {
+  if (!src || !sink) return CQ_ERR_NULL;
+  if (bytes == 0 || bytes % 16 != 0) return CQ_ERR_SHAPE;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+                     bytes / 16, sink);
+  return cq_check_launch();
+}

@@ -1,0 +1,370 @@
+// a6 / a7: grouped product with clustered weights (W_c[n,k] = C[n, idx[n,k]], Eq. W_c) for
+// token blocks of up to 32 rows per pass -- the decode (GEMV-like) regime, where the kernel is
+// bound by streaming the packed 4-bit indices from HBM.
+//
+// Design (gfx950), one workgroup of 4 wavefronts per (expert, 64 weight rows):
+//   * Table.  A weight row has 16 centroids, so a BYTE of packed indices (two weights) has only 256
+//     possible decoded values.  The workgroup builds, for each of its 64 rows, the 256-entry table of
+//     decoded PAIRS (two 16-bit operands in one dword) in LDS, entry-major: entry b of row slot r is
+//     the dword at b*256 + r*4.  A wavefront's 32-lane LDS pass then touches 32 different banks
+//     whatever the indices are (bank = row slot), which removes the bank conflicts that random table
+//     indexing causes -- the paper's stated obstacle for LUT kernels -- without replicating tables.
+//     One v_perm_b32 builds the LDS address of a pair, one ds_read_b32 returns two MFMA operands.
+//   * Stream.  Indices are read with 16-byte loads per lane, 8 steps ahead, straight into registers;
+//     lane (r = lane%32, g = lane/32) reads the 32 weights [64 s + 32 g, +32) of row r in K step s,
+//     which are four 8-wide MFMA A fragments.  With prepacked storage a wavefront load covers 1 KiB
+//     of contiguous memory.  The four wavefronts split K (step s goes to wavefront s%4).
+//   * Math.  v_mfma_f32_32x32x16 with the decoded weights as A (32 rows x 16 k) and the activations
+//     as B (16 k x 32 tokens): integer codes and bf16 centroids are exact bf16 operands; f16
+//     activations (the down projection) use f16 MFMA with centroids converted to f16.  Both operands
+//     number K identically, so the sum over K is the plain dot product.
+//   * Activations of the block's tokens are staged in LDS one K slab at a time, already in fragment
+//     order (16 bytes = 8 consecutive k of one token); token columns past the block are never stored,
+//     and an MFMA output column depends only on its own B column.
+//   * Epilogue.  The four partial accumulators are summed through LDS in a fixed order (deterministic),
+//     scaled per token, optionally passed through SiLU(gate)*up (gate/up rows interleaved so both sit in
+//     one lane), and stored.
+#include "cq_internal.h"
+
+namespace {
+
+constexpr int kTableBytes = 65536;   // 256 entries x 64 row slots x 4 bytes
+constexpr int kSlabBytes = 65536;    // activation slab / reduction buffer
+constexpr int kRing = 8;             // K steps prefetched per wavefront
+
+struct GemmArgs {
+  const uint8_t* idx;       // canonical or prepacked index bytes, group-major
+  const uint16_t* cent;
+  int prepacked;
+  int N, K;
+  const void* A;
+  const float* row_scale;
+  const int32_t* row_gather;
+  const int32_t* group_offsets;
+  void* out;
+  int out_ld;
+};
+
+__device__ __forceinline__ uint32_t f32_to_f16_bits_sat(float x) {
+  x = fminf(fmaxf(x, -65504.f), 65504.f);
+  const _Float16 h = (_Float16)x;
+  return (uint32_t) __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ uint32_t bf16_bits_to_f16_bits(uint32_t b) {
+  const _Float16 h = (_Float16)__uint_as_float(b << 16);
+  return (uint32_t) __builtin_bit_cast(uint16_t, h);
+}
+
+// integer code -> bf16 bits: a float holding a small integer has zero low mantissa bits.
+__device__ __forceinline__ uint32_t code_to_bf16_bits(int c) { return __float_as_uint((float)c) >> 16; }
+
+template <bool F16>
+__device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f c) {
+  cq_v4u bv = {b.x, b.y, b.z, b.w};
+  if constexpr (F16) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(cq_v8f16, a), __builtin_bit_cast(cq_v8f16, bv),
+                                                  c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(cq_v8bf16, a),
+                                                   __builtin_bit_cast(cq_v8bf16, bv), c, 0, 0, 0);
+  }
+}
+
+template <int AK, int EPI, int OUTK>
+__global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
+  constexpr bool F16 = (AK != CQ_A_INT8_CODES);
+  extern __shared__ uint4 smem[];
+  char* lds = reinterpret_cast<char*>(smem);
+  uint32_t* tbl = reinterpret_cast<uint32_t*>(lds);
+  uint4* slab = reinterpret_cast<uint4*>(lds + kTableBytes);
+  float* red = reinterpret_cast<float*>(lds + kTableBytes);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = blockIdx.y;
+  const int m0 = p.group_offsets[grp];
+  const int Me = p.group_offsets[grp + 1] - m0;
+  if (Me <= 0) return;
+  const int N = p.N, K = p.K;
+  const int n0 = blockIdx.x * 64;
+  const size_t rowbytes = (size_t)K >> 1;
+  const uint8_t* wbase = p.idx + ((size_t)grp * N + n0) * rowbytes;
+  const int r32 = lane & 31, g2 = lane >> 5;
+  size_t lane_off[2];
+  int sstride;
+  if (p.prepacked) {
+    lane_off[0] = (size_t)lane * 16;
+    lane_off[1] = 32 * rowbytes + (size_t)lane * 16;
+    sstride = 1024;
+  } else {
+    lane_off[0] = (size_t)r32 * rowbytes + g2 * 16;
+    lane_off[1] = (size_t)(32 + r32) * rowbytes + g2 * 16;
+    sstride = 32;
+  }
+  const int nS = K >> 6;                 // K steps of 64
+  const int Qmax = (nS + 3) >> 2;        // steps per wavefront (upper bound)
+
+  // ---- pair table for the 64 rows: wavefront w writes the entries whose high nibble is 4w..4w+3 ----
+  {
+    const uint16_t* crow = p.cent + ((size_t)grp * N + n0 + lane) * CQ_N_CENTROIDS;
+    const uint4 c0 = reinterpret_cast<const uint4*>(crow)[0];
+    const uint4 c1 = reinterpret_cast<const uint4*>(crow)[1];
+    const uint32_t cp[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+    uint32_t lo[16];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      lo[2 * i] = cp[i] & 0xffffu;
+      lo[2 * i + 1] = cp[i] >> 16;
+    }
+    if constexpr (F16) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) lo[i] = bf16_bits_to_f16_bits(lo[i]);
+    }
+    const uint2 hraw = *reinterpret_cast<const uint2*>(crow + 4 * wave);
+    uint32_t hv[4] = {hraw.x & 0xffffu, hraw.x >> 16, hraw.y & 0xffffu, hraw.y >> 16};
+    if constexpr (F16) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) hv[i] = bf16_bits_to_f16_bits(hv[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int hi = 4 * wave + i;
+      const uint32_t hs = hv[i] << 16;
+#pragma unroll
+      for (int l = 0; l < 16; ++l) tbl[(hi * 16 + l) * 64 + lane] = lo[l] | hs;
+    }
+  }
+
+  const uint32_t lanebase0 = (uint32_t)(r32 * 4);
+  const uint32_t lanebase1 = (uint32_t)((32 + r32) * 4);
+  const int n_tb = (Me + 31) >> 5;
+
+  for (int tb = 0; tb < n_tb; ++tb) {
+    const int Mb = min(32, Me - 32 * tb);
+    const int Mpad = (Mb + 7) & ~7;
+    // K values per slab: Mpad * KS * 2 bytes <= slab size, KS a multiple of 256 * kRing / ... see below
+    int KS = (kSlabBytes / 2 / Mpad) / 256 * 256;
+    if (KS > K) KS = K;
+    const int qPerSlab = max(1, KS >> 8);  // wavefront steps per slab (KS/64 steps shared by 4 wavefronts)
+    const int tj = r32 < Mpad ? r32 : 0;   // token column this lane feeds to the B operand
+
+    cq_v16f acc0, acc1;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
+
+    uint4 ring[kRing][2];
+#pragma unroll
+    for (int j = 0; j < kRing; ++j) {
+      const int gs = wave + 4 * j;
+      if (gs < nS) {
+        ring[j][0] = *reinterpret_cast<const uint4*>(wbase + lane_off[0] + (size_t)gs * sstride);
+        ring[j][1] = *reinterpret_cast<const uint4*>(wbase + lane_off[1] + (size_t)gs * sstride);
+      }
+    }
+
+    for (int q0 = 0; q0 < Qmax; q0 += kRing) {
+#pragma unroll
+      for (int j = 0; j < kRing; ++j) {
+        const int q = q0 + j;
+        if (q < Qmax) {
+          if (q % qPerSlab == 0) {
+            // ---- stage the activations of K range [k0, k0 + KSc) for this block's tokens ----
+            __syncthreads();
+            const int k0 = (q / qPerSlab) * (qPerSlab << 8);
+            const int KSc = min(qPerSlab << 8, K - k0);
+            const int items = (KSc >> 3) * Mpad;
+            for (int it = tid; it < items; it += 256) {
+              const int c = it / Mpad, t = it - c * Mpad;
+              uint4 v = make_uint4(0u, 0u, 0u, 0u);
+              if (t < Mb) {
+                const int m = m0 + 32 * tb + t;
+                const size_t src = p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
+                const size_t e0 = src * K + k0 + c * 8;
+                if constexpr (AK == CQ_A_INT8_CODES) {
+                  const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0);
+                  const uint32_t rw[2] = {raw.x, raw.y};
+                  uint32_t o[4];
+#pragma unroll
+                  for (int h = 0; h < 2; ++h) {
+                    const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
+                    const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
+                    o[2 * h] = code_to_bf16_bits(b0) | (code_to_bf16_bits(b1) << 16);
+                    o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
+                  }
+                  v = make_uint4(o[0], o[1], o[2], o[3]);
+                } else if constexpr (AK == CQ_A_F16) {
+                  v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0);
+                } else {
+                  const float4 f0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0);
+                  const float4 f1 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0 + 4);
+                  v.x = f32_to_f16_bits_sat(f0.x) | (f32_to_f16_bits_sat(f0.y) << 16);
+                  v.y = f32_to_f16_bits_sat(f0.z) | (f32_to_f16_bits_sat(f0.w) << 16);
+                  v.z = f32_to_f16_bits_sat(f1.x) | (f32_to_f16_bits_sat(f1.y) << 16);
+                  v.w = f32_to_f16_bits_sat(f1.z) | (f32_to_f16_bits_sat(f1.w) << 16);
+                }
+              }
+              slab[it] = v;
+            }
+            __syncthreads();
+          }
+          const int gs = wave + 4 * q;
+          if (gs < nS) {
+            const uint4 w0 = ring[j][0], w1 = ring[j][1];
+            const int gn = gs + 4 * kRing;
+            if (gn < nS) {
+              ring[j][0] = *reinterpret_cast<const uint4*>(wbase + lane_off[0] + (size_t)gn * sstride);
+              ring[j][1] = *reinterpret_cast<const uint4*>(wbase + lane_off[1] + (size_t)gn * sstride);
+            }
+            // chunk (8 k) index inside the slab of this lane's first fragment
+            const int ls = gs - (q / qPerSlab) * (qPerSlab << 2);
+            const uint4* bsrc = slab + (size_t)(ls * 8 + g2 * 4) * Mpad + tj;
+            const uint32_t wd0[4] = {w0.x, w0.y, w0.z, w0.w};
+            const uint32_t wd1[4] = {w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+              const uint4 bf = bsrc[(size_t)jj * Mpad];
+              cq_v4u a0, a1;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const uint32_t o0 = __builtin_amdgcn_perm(wd0[jj], lanebase0, 0x0c0c0400u + (i << 8));
+                const uint32_t o1 = __builtin_amdgcn_perm(wd1[jj], lanebase1, 0x0c0c0400u + (i << 8));
+                a0[i] = *reinterpret_cast<const uint32_t*>(lds + o0);
+                a1[i] = *reinterpret_cast<const uint32_t*>(lds + o1);
+              }
+              acc0 = mfma32<F16>(a0, bf, acc0);
+              acc1 = mfma32<F16>(a1, bf, acc1);
+            }
+          }
+        }
+      }
+    }
+
+    // ---- reduce the four K partials (fixed order) and finish ----
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      red[(wave * 32 + i) * 64 + lane] = acc0[i];
+      red[(wave * 32 + 16 + i) * 64 + lane] = acc1[i];
+    }
+    __syncthreads();
+    // wavefront w finishes accumulator registers 8w..8w+7 of the 32 (row block w/2, v = 8(w%2)..+7)
+    float val[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = wave * 8 + i;
+      float s = red[(0 * 32 + r) * 64 + lane];
+      s += red[(1 * 32 + r) * 64 + lane];
+      s += red[(2 * 32 + r) * 64 + lane];
+      s += red[(3 * 32 + r) * 64 + lane];
+      val[i] = s;
+    }
+    if (r32 < Mb) {
+      const int m = m0 + 32 * tb + r32;
+      float sc = 1.f;
+      if (p.row_scale) sc = p.row_scale[p.row_gather ? p.row_gather[m] : m];
+      const int rb = wave >> 1;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        // MFMA 32x32 output: register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+        const int vb = (wave & 1) * 2 + h;
+        const int row = n0 + rb * 32 + vb * 8 + g2 * 4;
+        const float x0 = sc * val[4 * h], x1 = sc * val[4 * h + 1], x2 = sc * val[4 * h + 2],
+                    x3 = sc * val[4 * h + 3];
+        if constexpr (EPI == CQ_EPI_SWIGLU) {
+          const float h0 = x0 / (1.f + __expf(-x0)) * x1;
+          const float h1 = x2 / (1.f + __expf(-x2)) * x3;
+          const size_t o = (size_t)m * p.out_ld + (row >> 1);
+          if constexpr (OUTK == CQ_OUT_F16) {
+            *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + o) =
+                f32_to_f16_bits_sat(h0) | (f32_to_f16_bits_sat(h1) << 16);
+          } else {
+            *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + o) = make_float2(h0, h1);
+          }
+        } else {
+          const size_t o = (size_t)m * p.out_ld + row;
+          if constexpr (OUTK == CQ_OUT_F16) {
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + o) =
+                make_uint2(f32_to_f16_bits_sat(x0) | (f32_to_f16_bits_sat(x1) << 16),
+                           f32_to_f16_bits_sat(x2) | (f32_to_f16_bits_sat(x3) << 16));
+          } else {
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + o) = make_float4(x0, x1, x2, x3);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int AK, int EPI, int OUTK>
+cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
+  auto kern = gemm_small_kernel<AK, EPI, OUTK>;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kTableBytes + kSlabBytes) != hipSuccess)
+      return CQ_ERR_HIP;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(a.N / 64, G), dim3(256), kTableBytes + kSlabBytes, s, a);
+  return cq_check_launch();
+}
+
+template <int AK>
+cq_status dispatch_epi(const GemmArgs& a, int G, int epilogue, int out_kind, hipStream_t s) {
+  if (epilogue == CQ_EPI_SWIGLU) {
+    return out_kind == CQ_OUT_F16 ? launch_small<AK, CQ_EPI_SWIGLU, CQ_OUT_F16>(a, G, s)
+                                  : launch_small<AK, CQ_EPI_SWIGLU, CQ_OUT_F32>(a, G, s);
+  }
+  return out_kind == CQ_OUT_F16 ? launch_small<AK, CQ_EPI_NONE, CQ_OUT_F16>(a, G, s)
+                                : launch_small<AK, CQ_EPI_NONE, CQ_OUT_F32>(a, G, s);
+}
+
+}  // namespace
+
+cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
+                                  const int32_t* row_gather, const int32_t* group_offsets, int M_total,
+                                  int epilogue, void* out, int out_kind, void* workspace, hipStream_t s) {
+  (void)workspace;
+  (void)M_total;
+  GemmArgs a;
+  a.idx = W->prepacked ? (const uint8_t*)W->prepacked : W->idx;
+  a.cent = W->cent;
+  a.prepacked = W->prepacked ? 1 : 0;
+  a.N = W->N;
+  a.K = W->K;
+  a.A = A;
+  a.row_scale = row_scale;
+  a.row_gather = row_gather;
+  a.group_offsets = group_offsets;
+  a.out = out;
+  a.out_ld = epilogue == CQ_EPI_SWIGLU ? W->N / 2 : W->N;
+  switch (a_kind) {
+    case CQ_A_INT8_CODES: return dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s);
+    case CQ_A_F16: return dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s);
+    default: return dispatch_epi<CQ_A_F32>(a, W->G, epilogue, out_kind, s);
+  }
+}
+
+extern "C" size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, int M_total) {
+  (void)W;
+  (void)M_total;
+  return 0;
+}
+
+extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, const void* A, int a_kind,
+                                              const float* row_scale, const int32_t* row_gather,
+                                              const int32_t* group_offsets, int M_total, int epilogue, void* out,
+                                              int out_kind, void* workspace, size_t workspace_bytes,
+                                              cq_stream stream) {
+  (void)workspace_bytes;
+  if (!W || !A || !group_offsets || !out) return CQ_ERR_NULL;
+  if ((!W->idx && !W->prepacked) || !W->cent) return CQ_ERR_NULL;
+  if (W->G <= 0 || W->N <= 0 || W->K <= 0 || M_total < 0) return CQ_ERR_SHAPE;
+  if (W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;
+  if (a_kind != CQ_A_INT8_CODES && a_kind != CQ_A_F16 && a_kind != CQ_A_F32) return CQ_ERR_UNSUPPORTED;
+  if (epilogue != CQ_EPI_NONE && epilogue != CQ_EPI_SWIGLU) return CQ_ERR_UNSUPPORTED;
+  if (out_kind != CQ_OUT_F32 && out_kind != CQ_OUT_F16) return CQ_ERR_UNSUPPORTED;
+  if (M_total == 0) return CQ_OK;
+  return cq_gemm_codebook_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, epilogue, out,
+                                 out_kind, workspace, (hipStream_t)stream);
+}

@@ -1,0 +1,51 @@
+// Internal declarations shared by the HIP translation units of libcq (gfx950 only).
+#ifndef CQ_INTERNAL_H_
+#define CQ_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cq.h"
+
+#define CQ_WAVE 64
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 cq_v8bf16;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 cq_v8f16;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float cq_v16f;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float cq_v4f;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t cq_v4u;
+
+static inline cq_status cq_check_launch() {
+  return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
+
+static inline size_t cq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- internal launchers (arguments already validated) -------------------------------------
+// C[T,N] (or partials [ksplit][T][N]) = A[T,K] * B, with B given row-major [K,N] (b_transposed = 0)
+// or as its transpose [N,K] (b_transposed = 1); fp32 MFMA, fp32 accumulation.
+struct cq_gemm_f32_plan {
+  int mb;      // 16-token blocks per wave (1 or 4)
+  int ksplit;  // number of K chunks
+  int kchunk;  // K values per chunk (a multiple of 16)
+};
+cq_gemm_f32_plan cq_gemm_f32_make_plan(int T, int N, int K);
+cq_status cq_gemm_f32_launch(const float* A, const float* B, int b_transposed, int T, int N, int K,
+                             const cq_gemm_f32_plan& plan, float* C_or_partials, hipStream_t s);
+
+cq_status cq_quantize_launch(const float* partials, int ksplit, int T, int H, int act_bits,
+                             float* XR_out, int8_t* Q_out, float* scale_out, hipStream_t s);
+
+cq_status cq_topk_launch(const float* logit_partials, int ksplit, const float* bias, int T, int E, int top_k,
+                         float* logits_out, int32_t* topk_ids, float* topk_w, hipStream_t s);
+size_t cq_permute_workspace_bytes(int T, int E, int top_k);
+cq_status cq_permute_launch(const int32_t* topk_ids, int T, int E, int top_k, int n_shared,
+                            int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm, int32_t* src_token,
+                            void* workspace, hipStream_t s);
+
+cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, int a_kind,
+                                  const float* row_scale, const int32_t* row_gather,
+                                  const int32_t* group_offsets, int M_total, int epilogue,
+                                  void* out, int out_kind, void* workspace, hipStream_t s);
+
+#endif  // CQ_INTERNAL_H_

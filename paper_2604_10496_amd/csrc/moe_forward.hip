@@ -1,0 +1,106 @@
+// The whole layer a1..a8 on one stream: rotate + quantize, route + permute, gate/up codebook product
+// with the SiLU-gated epilogue, down codebook product, weighted combine.  Host code only enqueues.
+#include "cq_internal.h"
+
+namespace {
+
+cq_status validate_layer(const cq_layer* L, int T) {
+  if (!L) return CQ_ERR_NULL;
+  if (!L->R || !L->Wr || !L->gate_up.cent || !L->down.cent) return CQ_ERR_NULL;
+  if ((!L->gate_up.idx && !L->gate_up.prepacked) || (!L->down.idx && !L->down.prepacked)) return CQ_ERR_NULL;
+  if (T <= 0 || L->H <= 0 || L->I <= 0 || L->E <= 0 || L->top_k <= 0 || L->S < 0) return CQ_ERR_SHAPE;
+  if (L->H % 64 != 0 || L->I % 64 != 0 || L->top_k > L->E || L->top_k > 64 || L->E > 1024) return CQ_ERR_SHAPE;
+  if ((long)T * (L->top_k + L->S) > 0x7fffffffL) return CQ_ERR_SHAPE;
+  if (L->act_bits != 4 && L->act_bits != 8) return CQ_ERR_UNSUPPORTED;
+  const int G = L->E + L->S;
+  if (L->gate_up.G != G || L->gate_up.N != 2 * L->I || L->gate_up.K != L->H) return CQ_ERR_SHAPE;
+  if (L->down.G != G || L->down.N != L->H || L->down.K != L->I) return CQ_ERR_SHAPE;
+  return CQ_OK;
+}
+
+void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
+  const size_t M = (size_t)T * (L->top_k + L->S), A = (size_t)T * L->top_k;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += cq_align_up(bytes, 256);
+    return at;
+  };
+  o->XR = take((size_t)T * L->H * 4);
+  o->Q = take((size_t)T * L->H);
+  o->scale = take((size_t)T * 4);
+  o->logits = take((size_t)T * L->E * 4);
+  o->topk_ids = take(A * 4);
+  o->topk_w = take(A * 4);
+  o->offsets = take((size_t)(L->E + L->S + 1) * 4);
+  o->perm = take(A * 4);
+  o->inv_perm = take(A * 4);
+  o->src_token = take(M * 4);
+  o->Hbuf = take(M * L->I * 2);
+  o->Obuf = take(M * L->H * 4);
+  size_t scratch = cq_rotate_quant_workspace_bytes(T, L->H);
+  const size_t r = cq_route_permute_workspace_bytes(T, L->H, L->E, L->top_k);
+  if (r > scratch) scratch = r;
+  const size_t g1 = cq_grouped_gemm_workspace_bytes(&L->gate_up, (int)M);
+  if (g1 > scratch) scratch = g1;
+  const size_t g2 = cq_grouped_gemm_workspace_bytes(&L->down, (int)M);
+  if (g2 > scratch) scratch = g2;
+  o->scratch = take(scratch);
+  o->total = off;
+}
+
+}  // namespace
+
+extern "C" size_t cq_moe_workspace_bytes(const cq_layer* L, int T) {
+  if (validate_layer(L, T) != CQ_OK) return 0;
+  cq_moe_layout lay;
+  make_layout(L, T, &lay);
+  return lay.total;
+}
+
+extern "C" cq_status cq_moe_workspace_layout(const cq_layer* L, int T, cq_moe_layout* out) {
+  if (!out) return CQ_ERR_NULL;
+  const cq_status st = validate_layer(L, T);
+  if (st != CQ_OK) return st;
+  make_layout(L, T, out);
+  return CQ_OK;
+}
+
+extern "C" cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y, void* workspace,
+                                    size_t workspace_bytes, cq_stream stream) {
+  cq_status st = validate_layer(L, T);
+  if (st != CQ_OK) return st;
+  if (!X || !Y) return CQ_ERR_NULL;
+  cq_moe_layout lay;
+  make_layout(L, T, &lay);
+  if (!workspace || workspace_bytes < lay.total) return CQ_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  float* XR = (float*)(ws + lay.XR);
+  int8_t* Q = (int8_t*)(ws + lay.Q);
+  float* scale = (float*)(ws + lay.scale);
+  float* logits = (float*)(ws + lay.logits);
+  int32_t* ids = (int32_t*)(ws + lay.topk_ids);
+  float* tw = (float*)(ws + lay.topk_w);
+  int32_t* offsets = (int32_t*)(ws + lay.offsets);
+  int32_t* perm = (int32_t*)(ws + lay.perm);
+  int32_t* inv_perm = (int32_t*)(ws + lay.inv_perm);
+  int32_t* src_token = (int32_t*)(ws + lay.src_token);
+  void* Hbuf = ws + lay.Hbuf;
+  float* Obuf = (float*)(ws + lay.Obuf);
+  void* scratch = ws + lay.scratch;
+  const size_t scratch_bytes = lay.total - lay.scratch;
+  const int M = T * (L->top_k + L->S);
+
+  st = cq_rotate_quant(X, L->R, T, L->H, L->act_bits, XR, Q, scale, scratch, scratch_bytes, stream);
+  if (st != CQ_OK) return st;
+  st = cq_route_permute(XR, L->Wr, L->bias, nullptr, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets, perm,
+                        inv_perm, src_token, scratch, scratch_bytes, stream);
+  if (st != CQ_OK) return st;
+  st = cq_codebook_grouped_gemm(&L->gate_up, Q, CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU, Hbuf,
+                                CQ_OUT_F16, scratch, scratch_bytes, stream);
+  if (st != CQ_OK) return st;
+  st = cq_codebook_grouped_gemm(&L->down, Hbuf, CQ_A_F16, nullptr, nullptr, offsets, M, CQ_EPI_NONE, Obuf,
+                                CQ_OUT_F32, scratch, scratch_bytes, stream);
+  if (st != CQ_OK) return st;
+  return cq_combine(Obuf, tw, inv_perm, T, L->H, L->top_k, L->S, Y, stream);
+}

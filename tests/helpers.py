@@ -1,0 +1,62 @@
+"""Shared test helpers: seeded inputs with a routing margin, oracle runs, comparison rules."""
+import numpy as np
+
+from oracle import cq_oracle as O
+from paper_2604_10496_amd import synth
+
+
+def enforce_routing_margin(inputs, delta_rel=1e-3, max_iter=20):
+    """Redraw token rows whose top-(k+1) router logits have an adjacent gap below delta.
+
+    Single-precision logits cannot be asked to order logits that an exact evaluation separates by
+    less than their own rounding error; the margin makes the bit-exact routing comparison well posed.
+    Returns (number of redrawn rows, final minimum gap, delta).
+    """
+    cfg = inputs.cfg
+    kk = min(cfg.top_k + 1, cfg.E)
+    delta = None
+    min_gap = None
+    for attempt in range(max_iter):
+        L = O.router_logits(O.rotate(inputs.X, inputs.R), inputs.Wr, inputs.bias)
+        top = -np.sort(-L, axis=1)[:, :kk]
+        gaps = top[:, :-1] - top[:, 1:]
+        delta = delta_rel * max(1.0, float(L.std()))
+        min_gap = gaps.min(axis=1) if gaps.size else np.full(L.shape[0], np.inf)
+        bad = np.nonzero(min_gap < delta)[0]
+        if bad.size == 0:
+            break
+        synth.redraw_rows(inputs, bad, attempt)
+    else:
+        raise AssertionError("routing margin not reached")
+    return inputs.redrawn_rows, float(np.min(min_gap)), delta
+
+
+def make_inputs(cfg, with_experts=True):
+    inputs = synth.make_layer(cfg, with_experts=with_experts)
+    enforce_routing_margin(inputs)
+    return inputs
+
+
+def oracle_forward(inputs, **kw):
+    c = inputs.cfg
+    return O.moe_forward(inputs.X, inputs.R, inputs.Wr, inputs.bias, inputs.experts, c.E, c.top_k, c.act_bits, **kw)
+
+
+def check_codes(q_gpu, q_ref, XR_ref, scale_ref, tie_window=1e-3):
+    """Codes must be equal except +-1 where the exact x/s is within tie_window of a rounding tie."""
+    diff = q_gpu.astype(np.int64) - q_ref.astype(np.int64)
+    bad = diff != 0
+    n_bad = int(bad.sum())
+    if n_bad:
+        assert np.all(np.abs(diff[bad]) == 1), "a code differs by more than one step"
+        d = O.tie_distance(XR_ref, scale_ref)
+        assert np.all(d[bad] <= tie_window), f"code differs away from a tie (max distance {d[bad].max():.3e})"
+    return n_bad
+
+
+def row_rel_l2(a, ref):
+    a = np.asarray(a, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    num = np.linalg.norm(a - ref, axis=1)
+    den = np.linalg.norm(ref, axis=1)
+    return num / np.where(den == 0, 1.0, den)

@@ -1,0 +1,99 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header declares,
+and validates its arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_10496_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "cq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree():
+    if not os.path.exists(B.LIB_PATH):
+        pytest.fail("libcq.so is not built: run `python -m paper_2604_10496_amd.build`")
+    lib = B.load_library()
+    declared = _declared_functions()
+    assert len(declared) >= 14
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in cq.h but not exported"
+    assert sorted(B.EXPORTS) == declared
+
+
+def test_status_strings():
+    lib = B.load_library()
+    seen = {lib.cq_status_string(i) for i in range(6)}
+    assert len(seen) == 6 and lib.cq_status_string(0) == b"CQ_OK"
+
+
+def test_argument_validation_happens_before_any_device_call():
+    lib = B.load_library()
+    one = ctypes.c_void_p(256)   # a non-null dummy that must never be dereferenced
+    # rotate_quant
+    assert lib.cq_rotate_quant(None, one, 4, 64, 8, one, one, one, one, 1 << 20, None) == 1
+    assert lib.cq_rotate_quant(one, one, 0, 64, 8, one, one, one, one, 1 << 20, None) == 2
+    assert lib.cq_rotate_quant(one, one, 4, 100, 8, one, one, one, one, 1 << 20, None) == 2
+    assert lib.cq_rotate_quant(one, one, 4, 64, 5, one, one, one, one, 1 << 20, None) == 3
+    assert lib.cq_rotate_quant(one, one, 16, 4096, 8, one, one, one, None, 0, None) == 4
+    # route_permute
+    args = lambda **k: [k.get("XR", one), one, None, None, k.get("T", 8), 64, k.get("E", 8), k.get("k", 2), 0,
+                        None, one, one, one, one, one, None, k.get("ws", one), k.get("wsb", 1 << 24), None]
+    assert lib.cq_route_permute(*args(k=9)) == 2
+    assert lib.cq_route_permute(*args(E=2000)) == 2
+    assert lib.cq_route_permute(*args(XR=None)) == 1
+    assert lib.cq_route_permute(*args(wsb=8)) == 4
+    # grouped gemm
+    W = B.CodebookWeights(256, 256, None, 2, 128, 128)
+    g = lambda W, a_kind=0, epi=0, outk=0: lib.cq_codebook_grouped_gemm(ctypes.byref(W), one, a_kind, None, None,
+                                                                        one, 4, epi, one, outk, None, 0, None)
+    assert g(B.CodebookWeights(None, 256, None, 2, 128, 128)) == 1
+    assert g(B.CodebookWeights(256, 256, None, 2, 100, 128)) == 2
+    assert g(B.CodebookWeights(256, 256, None, 2, 128, 96)) == 2
+    assert g(W, a_kind=7) == 3 and g(W, epi=5) == 3 and g(W, outk=9) == 3
+    # moe_forward: shape mismatch between layer and weights, bad bits
+    gu = B.CodebookWeights(256, 256, None, 4, 256, 128)
+    dn = B.CodebookWeights(256, 256, None, 4, 128, 128)
+    L = B.Layer(128, 128, 4, 2, 0, 8, 256, 256, None, gu, dn)
+    assert lib.cq_moe_workspace_bytes(ctypes.byref(L), 16) > 0
+    assert lib.cq_moe_forward(ctypes.byref(L), one, 16, one, None, 0, None) == 4
+    Lbad = B.Layer(128, 128, 4, 2, 0, 6, 256, 256, None, gu, dn)
+    assert lib.cq_moe_forward(ctypes.byref(Lbad), one, 16, one, one, 1 << 30, None) == 3
+    Lbad2 = B.Layer(128, 128, 4, 5, 0, 8, 256, 256, None, gu, dn)
+    assert lib.cq_moe_forward(ctypes.byref(Lbad2), one, 16, one, one, 1 << 30, None) == 2
+    Lbad3 = B.Layer(128, 64, 4, 2, 0, 8, 256, 256, None, gu, dn)
+    assert lib.cq_moe_forward(ctypes.byref(Lbad3), one, 16, one, one, 1 << 30, None) == 2
+    # prepack / decode
+    assert lib.cq_prepack(ctypes.byref(W), one, 8, None) == 4
+    assert lib.cq_decode_dense(ctypes.byref(W), 5, one, None) == 2
+    assert lib.cq_stream_read(one, 24, one, None) == 2
+
+
+def test_workspace_sizes_are_pure_and_monotone():
+    lib = B.load_library()
+    a = lib.cq_rotate_quant_workspace_bytes(16, 4096)
+    assert a == lib.cq_rotate_quant_workspace_bytes(16, 4096) and a >= 16 * 4096 * 4
+    assert lib.cq_rotate_quant_workspace_bytes(4096, 4096) == 0       # enough tiles: no K split
+    assert lib.cq_route_permute_workspace_bytes(2048, 2048, 128, 8) >= (2048 * 8 // 256) * 128 * 4
+
+
+def test_prepack_layout_documented_in_header_matches_numpy_model():
+    """The tile order stated in cq.h, modelled in numpy, is a permutation of the canonical bytes."""
+    N, K = 64, 128
+    canon = np.arange(N * K // 2, dtype=np.int64).reshape(N, K // 2)
+    packed = np.empty(N * K // 2, dtype=np.int64)
+    for rb in range(N // 32):
+        for s in range(K // 64):
+            base = (rb * (K // 64) + s) * 1024
+            for l in range(64):
+                row, col = rb * 32 + l % 32, s * 32 + (l // 32) * 16
+                packed[base + l * 16: base + l * 16 + 16] = canon[row, col:col + 16]
+    assert sorted(packed.tolist()) == list(range(N * K // 2))
