@@ -166,6 +166,17 @@ cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y,
                          void* workspace, size_t workspace_bytes, cq_stream stream);
 
 /*
+ * Measurement variant of cq_moe_forward: same launches, with HIP events recorded on `stream` at the
+ * stage boundaries.  It waits for the last event (so, unlike cq_moe_forward, it synchronises the
+ * host) and writes the elapsed milliseconds of the CQ_N_STAGES stages to stage_ms (host memory):
+ * [0] rotate+quantize, [1] route+permute, [2] gate/up product, [3] down product, [4] combine.
+ */
+#define CQ_N_STAGES 5
+cq_status cq_moe_forward_timed(const cq_layer* L, const float* X, int T, float* Y,
+                               void* workspace, size_t workspace_bytes, cq_stream stream,
+                               float* stage_ms);
+
+/*
  * Offline, one-time re-layout of canonical indices into the kernel-native tile order described at
  * cq_codebook_weights (the paper's pipeline is fully offline, so the stored order is free; the
  * byte count streamed is unchanged).  dst must hold cq_prepack_bytes(W) bytes.

@@ -23,7 +23,7 @@ EXPORTS = [
     "cq_status_string", "cq_rotate_quant_workspace_bytes", "cq_rotate_quant",
     "cq_route_permute_workspace_bytes", "cq_route_permute", "cq_grouped_gemm_workspace_bytes",
     "cq_codebook_grouped_gemm", "cq_combine", "cq_moe_workspace_bytes", "cq_moe_workspace_layout",
-    "cq_moe_forward", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
+    "cq_moe_forward", "cq_moe_forward_timed", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
     "cq_stream_read",
 ]
 
@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
     lib.cq_moe_workspace_layout.argtypes = [ctypes.POINTER(Layer), ci, ctypes.POINTER(MoeLayout)]
     lib.cq_moe_forward.restype = ci
     lib.cq_moe_forward.argtypes = [ctypes.POINTER(Layer), vp, ci, vp, vp, sz, vp]
+    lib.cq_moe_forward_timed.restype = ci
+    lib.cq_moe_forward_timed.argtypes = [ctypes.POINTER(Layer), vp, ci, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]
     lib.cq_prepack_bytes.restype = sz
     lib.cq_prepack_bytes.argtypes = [ctypes.POINTER(CodebookWeights)]
     lib.cq_prepack.restype = ci
@@ -291,6 +293,23 @@ def cq_moe_forward(layer: DeviceLayer, X, Y=None):
     s = layer.struct()
     _check(lib.cq_moe_forward(ctypes.byref(s), _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream()))
     return Y
+
+
+STAGES = ("rotate_quant", "route_permute", "gate_up", "down", "combine")
+
+
+def cq_moe_forward_timed(layer: DeviceLayer, X, Y=None):
+    """Same launches as cq_moe_forward plus stage-boundary events; returns (Y, {stage: ms})."""
+    torch = _torch()
+    lib = load_library()
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, layer.cfg.H), dtype=torch.float32, device="cuda")
+    ws = layer.workspace(T)
+    s = layer.struct()
+    ms = (ctypes.c_float * len(STAGES))()
+    _check(lib.cq_moe_forward_timed(ctypes.byref(s), _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream(), ms))
+    return Y, dict(zip(STAGES, [float(v) for v in ms]))
 
 
 def moe_intermediates(layer: DeviceLayer, T: int) -> Dict[str, object]:

@@ -43,6 +43,7 @@ struct GemmArgs {
   const int32_t* group_offsets;
   void* out;
   int out_ld;
+  int upw;                  // 64-row units per workgroup (consecutive, same expert)
 };
 
 __device__ __forceinline__ uint32_t f32_to_f16_bits_sat(float x) {
@@ -77,8 +78,8 @@ __global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
   extern __shared__ uint4 smem[];
   char* lds = reinterpret_cast<char*>(smem);
   uint32_t* tbl = reinterpret_cast<uint32_t*>(lds);
+  float* red = reinterpret_cast<float*>(lds);  // aliases the table between units
   uint4* slab = reinterpret_cast<uint4*>(lds + kTableBytes);
-  float* red = reinterpret_cast<float*>(lds + kTableBytes);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = blockIdx.y;
@@ -86,9 +87,12 @@ __global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
   const int Me = p.group_offsets[grp + 1] - m0;
   if (Me <= 0) return;
   const int N = p.N, K = p.K;
-  const int n0 = blockIdx.x * 64;
+  const int nUnits = N >> 6;
+  const int u0 = blockIdx.x * p.upw;
+  const int u1 = min(nUnits, u0 + p.upw);
+  if (u0 >= u1) return;
   const size_t rowbytes = (size_t)K >> 1;
-  const uint8_t* wbase = p.idx + ((size_t)grp * N + n0) * rowbytes;
+  const uint8_t* gbase = p.idx + (size_t)grp * N * rowbytes;
   const int r32 = lane & 31, g2 = lane >> 5;
   size_t lane_off[2];
   int sstride;
@@ -101,120 +105,178 @@ __global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
     lane_off[1] = (size_t)(32 + r32) * rowbytes + g2 * 16;
     sstride = 32;
   }
-  const int nS = K >> 6;                 // K steps of 64
-  const int Qmax = (nS + 3) >> 2;        // steps per wavefront (upper bound)
-
-  // ---- pair table for the 64 rows: wavefront w writes the entries whose high nibble is 4w..4w+3 ----
-  {
-    const uint16_t* crow = p.cent + ((size_t)grp * N + n0 + lane) * CQ_N_CENTROIDS;
-    const uint4 c0 = reinterpret_cast<const uint4*>(crow)[0];
-    const uint4 c1 = reinterpret_cast<const uint4*>(crow)[1];
-    const uint32_t cp[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-    uint32_t lo[16];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      lo[2 * i] = cp[i] & 0xffffu;
-      lo[2 * i + 1] = cp[i] >> 16;
-    }
-    if constexpr (F16) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) lo[i] = bf16_bits_to_f16_bits(lo[i]);
-    }
-    const uint2 hraw = *reinterpret_cast<const uint2*>(crow + 4 * wave);
-    uint32_t hv[4] = {hraw.x & 0xffffu, hraw.x >> 16, hraw.y & 0xffffu, hraw.y >> 16};
-    if constexpr (F16) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) hv[i] = bf16_bits_to_f16_bits(hv[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int hi = 4 * wave + i;
-      const uint32_t hs = hv[i] << 16;
-#pragma unroll
-      for (int l = 0; l < 16; ++l) tbl[(hi * 16 + l) * 64 + lane] = lo[l] | hs;
-    }
-  }
-
+  const int nS = K >> 6;                            // K steps of 64
+  const int Qmax = (nS + 3) >> 2;                   // steps per wavefront (upper bound)
+  const int Qpad = (Qmax + kRing - 1) / kRing * kRing;
   const uint32_t lanebase0 = (uint32_t)(r32 * 4);
   const uint32_t lanebase1 = (uint32_t)((32 + r32) * 4);
   const int n_tb = (Me + 31) >> 5;
 
   for (int tb = 0; tb < n_tb; ++tb) {
     const int Mb = min(32, Me - 32 * tb);
-    const int Mpad = (Mb + 7) & ~7;
-    // K values per slab: Mpad * KS * 2 bytes <= slab size, KS a multiple of 256 * kRing / ... see below
-    int KS = (kSlabBytes / 2 / Mpad) / 256 * 256;
-    if (KS > K) KS = K;
-    const int qPerSlab = max(1, KS >> 8);  // wavefront steps per slab (KS/64 steps shared by 4 wavefronts)
-    const int tj = r32 < Mpad ? r32 : 0;   // token column this lane feeds to the B operand
+    const int Mpad = Mb <= 8 ? 8 : Mb <= 16 ? 16 : 32;      // divides 256: a thread stages one token
+    const int qPerSlab = Mpad == 8 ? 16 : Mpad == 16 ? 8 : 4;  // wavefront steps per slab (x256 k)
+    const int KSfull = qPerSlab << 8;
+    const bool multi = KSfull < K;                          // activations do not fit: restage per slab
+    const int nSlab = multi ? (K + KSfull - 1) / KSfull : 1;
+    const int tj = r32 < Mpad ? r32 : 0;                    // token column this lane feeds to the B operand
 
-    cq_v16f acc0, acc1;
+    // ---- this thread's staging duty: token st, chunks sc0 + i * cstep ----
+    const int st = tid & (Mpad - 1);
+    const int sc0 = tid / Mpad, cstep = 256 / Mpad;
+    const bool svalid = st < Mb;
+    size_t srow = 0;
+    if (svalid) {
+      const int m = m0 + 32 * tb + st;
+      srow = (p.row_gather ? (size_t)p.row_gather[m] : (size_t)m) * K;
+    }
+    uint4 sreg[16];
+    auto stage_load = [&](int sl) {
+      const int k0 = sl * KSfull;
+      const int nC = min(KSfull, K - k0) >> 3;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
+      for (int i = 0; i < 16; ++i) {
+        const int c = sc0 + i * cstep;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (svalid && c < nC) {
+          const size_t e0 = srow + k0 + c * 8;
+          if constexpr (AK == CQ_A_INT8_CODES) {
+            const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0);
+            v.x = raw.x;
+            v.y = raw.y;
+          } else if constexpr (AK == CQ_A_F16) {
+            v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0);
+          } else {
+            const float4 f0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0);
+            const float4 f1 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0 + 4);
+            v.x = f32_to_f16_bits_sat(f0.x) | (f32_to_f16_bits_sat(f0.y) << 16);
+            v.y = f32_to_f16_bits_sat(f0.z) | (f32_to_f16_bits_sat(f0.w) << 16);
+            v.z = f32_to_f16_bits_sat(f1.x) | (f32_to_f16_bits_sat(f1.y) << 16);
+            v.w = f32_to_f16_bits_sat(f1.z) | (f32_to_f16_bits_sat(f1.w) << 16);
+          }
+        }
+        sreg[i] = v;
+      }
+    };
+    auto stage_store = [&](int sl) {
+      const int k0 = sl * KSfull;
+      const int nC = min(KSfull, K - k0) >> 3;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int c = sc0 + i * cstep;
+        if (c < nC) {
+          uint4 v = sreg[i];
+          if constexpr (AK == CQ_A_INT8_CODES) {
+            const uint32_t rw[2] = {v.x, v.y};
+            uint32_t o[4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
+              const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
+              o[2 * h] = code_to_bf16_bits(b0) | (code_to_bf16_bits(b1) << 16);
+              o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
+            }
+            v = make_uint4(o[0], o[1], o[2], o[3]);
+          }
+          slab[c * Mpad + st] = v;
+        }
+      }
+    };
 
+    // ---- centroid rows of a unit, held raw in registers one unit ahead ----
+    uint4 craw0, craw1;
+    uint2 chraw;
+    auto cent_load = [&](int u) {
+      const uint16_t* crow = p.cent + ((size_t)grp * N + (size_t)u * 64 + lane) * CQ_N_CENTROIDS;
+      craw0 = reinterpret_cast<const uint4*>(crow)[0];
+      craw1 = reinterpret_cast<const uint4*>(crow)[1];
+      chraw = *reinterpret_cast<const uint2*>(crow + 4 * wave);
+    };
+    // pair table: wavefront w writes the entries whose high nibble is 4w..4w+3; lane = row slot
+    auto build_table = [&]() {
+      const uint32_t cp[8] = {craw0.x, craw0.y, craw0.z, craw0.w, craw1.x, craw1.y, craw1.z, craw1.w};
+      uint32_t lo[16];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        lo[2 * i] = cp[i] & 0xffffu;
+        lo[2 * i + 1] = cp[i] >> 16;
+      }
+      uint32_t hv[4] = {chraw.x & 0xffffu, chraw.x >> 16, chraw.y & 0xffffu, chraw.y >> 16};
+      if constexpr (F16) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) lo[i] = bf16_bits_to_f16_bits(lo[i]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hv[i] = bf16_bits_to_f16_bits(hv[i]);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int hi = 4 * wave + i;
+        const uint32_t hs = hv[i] << 16;
+#pragma unroll
+        for (int l = 0; l < 16; ++l) tbl[(hi * 16 + l) * 64 + lane] = lo[l] | hs;
+      }
+    };
+
+    stage_load(0);
+    cent_load(u0);
     uint4 ring[kRing][2];
+    {
+      const uint8_t* wb = gbase + (size_t)u0 * 64 * rowbytes;
 #pragma unroll
-    for (int j = 0; j < kRing; ++j) {
-      const int gs = wave + 4 * j;
-      if (gs < nS) {
-        ring[j][0] = *reinterpret_cast<const uint4*>(wbase + lane_off[0] + (size_t)gs * sstride);
-        ring[j][1] = *reinterpret_cast<const uint4*>(wbase + lane_off[1] + (size_t)gs * sstride);
+      for (int j = 0; j < kRing; ++j) {
+        const int gs = wave + 4 * j;
+        const size_t off = (size_t)(gs < nS ? gs : 0) * sstride;
+        ring[j][0] = *reinterpret_cast<const uint4*>(wb + lane_off[0] + off);
+        ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off[1] + off);
       }
     }
 
-    for (int q0 = 0; q0 < Qmax; q0 += kRing) {
+    for (int u = u0; u < u1; ++u) {
+      const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
+      const uint8_t* wb_next = wb + 64 * rowbytes;
+      const bool has_next = u + 1 < u1;
+      build_table();
+      if (has_next) cent_load(u + 1);
+      __syncthreads();
+
+      cq_v16f acc0, acc1;
 #pragma unroll
-      for (int j = 0; j < kRing; ++j) {
-        const int q = q0 + j;
-        if (q < Qmax) {
-          if (q % qPerSlab == 0) {
-            // ---- stage the activations of K range [k0, k0 + KSc) for this block's tokens ----
-            __syncthreads();
-            const int k0 = (q / qPerSlab) * (qPerSlab << 8);
-            const int KSc = min(qPerSlab << 8, K - k0);
-            const int items = (KSc >> 3) * Mpad;
-            for (int it = tid; it < items; it += 256) {
-              const int c = it / Mpad, t = it - c * Mpad;
-              uint4 v = make_uint4(0u, 0u, 0u, 0u);
-              if (t < Mb) {
-                const int m = m0 + 32 * tb + t;
-                const size_t src = p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
-                const size_t e0 = src * K + k0 + c * 8;
-                if constexpr (AK == CQ_A_INT8_CODES) {
-                  const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0);
-                  const uint32_t rw[2] = {raw.x, raw.y};
-                  uint32_t o[4];
+      for (int i = 0; i < 16; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
+
+      // Ring loads are issued unconditionally (with the address clamped to a step that exists) so
+      // that the number of loads in flight is the same on every path and the wait before a slot is
+      // consumed only covers that slot; math for steps past the end of K is skipped.
+      const size_t clamp_off = 0;  // step 0 of the unit always exists
+      for (int q0 = 0; q0 < Qpad; q0 += kRing) {
 #pragma unroll
-                  for (int h = 0; h < 2; ++h) {
-                    const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
-                    const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
-                    o[2 * h] = code_to_bf16_bits(b0) | (code_to_bf16_bits(b1) << 16);
-                    o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
-                  }
-                  v = make_uint4(o[0], o[1], o[2], o[3]);
-                } else if constexpr (AK == CQ_A_F16) {
-                  v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0);
-                } else {
-                  const float4 f0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0);
-                  const float4 f1 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0 + 4);
-                  v.x = f32_to_f16_bits_sat(f0.x) | (f32_to_f16_bits_sat(f0.y) << 16);
-                  v.y = f32_to_f16_bits_sat(f0.z) | (f32_to_f16_bits_sat(f0.w) << 16);
-                  v.z = f32_to_f16_bits_sat(f1.x) | (f32_to_f16_bits_sat(f1.y) << 16);
-                  v.w = f32_to_f16_bits_sat(f1.z) | (f32_to_f16_bits_sat(f1.w) << 16);
-                }
+        for (int j = 0; j < kRing; ++j) {
+          const int q = q0 + j;
+          if (j % 4 == 0) {
+            // slab boundary (qPerSlab is a multiple of 4): publish the slab held in registers, then
+            // start loading the one after it so that its latency hides behind this slab's math
+            if (q < Qmax && q % qPerSlab == 0 && (multi || u == u0)) {
+              const int sl = q / qPerSlab;
+              __syncthreads();
+              stage_store(sl);
+              __syncthreads();
+              if (multi) {
+                if (sl + 1 < nSlab) stage_load(sl + 1);
+                else if (has_next) stage_load(0);
               }
-              slab[it] = v;
             }
-            __syncthreads();
           }
           const int gs = wave + 4 * q;
+          const uint4 w0 = ring[j][0], w1 = ring[j][1];
+          {
+            const int qq = q + kRing;  // the step that reuses this ring slot
+            const bool same = qq < Qpad;
+            const int gn = wave + 4 * (same ? qq : qq - Qpad);
+            const uint8_t* base = (same || !has_next) ? wb : wb_next;
+            const size_t off = (gn < nS && (same || has_next)) ? (size_t)gn * sstride : clamp_off;
+            ring[j][0] = *reinterpret_cast<const uint4*>(base + lane_off[0] + off);
+            ring[j][1] = *reinterpret_cast<const uint4*>(base + lane_off[1] + off);
+          }
           if (gs < nS) {
-            const uint4 w0 = ring[j][0], w1 = ring[j][1];
-            const int gn = gs + 4 * kRing;
-            if (gn < nS) {
-              ring[j][0] = *reinterpret_cast<const uint4*>(wbase + lane_off[0] + (size_t)gn * sstride);
-              ring[j][1] = *reinterpret_cast<const uint4*>(wbase + lane_off[1] + (size_t)gn * sstride);
-            }
             // chunk (8 k) index inside the slab of this lane's first fragment
             const int ls = gs - (q / qPerSlab) * (qPerSlab << 2);
             const uint4* bsrc = slab + (size_t)(ls * 8 + g2 * 4) * Mpad + tj;
@@ -237,61 +299,63 @@ __global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
           }
         }
       }
-    }
 
-    // ---- reduce the four K partials (fixed order) and finish ----
-    __syncthreads();
+      // ---- reduce the four K partials (fixed order) through the table's LDS and finish ----
+      __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      red[(wave * 32 + i) * 64 + lane] = acc0[i];
-      red[(wave * 32 + 16 + i) * 64 + lane] = acc1[i];
-    }
-    __syncthreads();
-    // wavefront w finishes accumulator registers 8w..8w+7 of the 32 (row block w/2, v = 8(w%2)..+7)
-    float val[8];
+      for (int i = 0; i < 16; ++i) {
+        red[(wave * 32 + i) * 64 + lane] = acc0[i];
+        red[(wave * 32 + 16 + i) * 64 + lane] = acc1[i];
+      }
+      __syncthreads();
+      // wavefront w finishes accumulator registers 8w..8w+7 of the 32 (row block w/2, v = 8(w%2)..+7)
+      float val[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = wave * 8 + i;
-      float s = red[(0 * 32 + r) * 64 + lane];
-      s += red[(1 * 32 + r) * 64 + lane];
-      s += red[(2 * 32 + r) * 64 + lane];
-      s += red[(3 * 32 + r) * 64 + lane];
-      val[i] = s;
-    }
-    if (r32 < Mb) {
-      const int m = m0 + 32 * tb + r32;
-      float sc = 1.f;
-      if (p.row_scale) sc = p.row_scale[p.row_gather ? p.row_gather[m] : m];
-      const int rb = wave >> 1;
+      for (int i = 0; i < 8; ++i) {
+        const int r = wave * 8 + i;
+        float s = red[(0 * 32 + r) * 64 + lane];
+        s += red[(1 * 32 + r) * 64 + lane];
+        s += red[(2 * 32 + r) * 64 + lane];
+        s += red[(3 * 32 + r) * 64 + lane];
+        val[i] = s;
+      }
+      __syncthreads();  // the next unit's table overwrites this region
+      if (r32 < Mb) {
+        const int m = m0 + 32 * tb + r32;
+        float sc = 1.f;
+        if (p.row_scale) sc = p.row_scale[p.row_gather ? p.row_gather[m] : m];
+        const int rb = wave >> 1;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        // MFMA 32x32 output: register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
-        const int vb = (wave & 1) * 2 + h;
-        const int row = n0 + rb * 32 + vb * 8 + g2 * 4;
-        const float x0 = sc * val[4 * h], x1 = sc * val[4 * h + 1], x2 = sc * val[4 * h + 2],
-                    x3 = sc * val[4 * h + 3];
-        if constexpr (EPI == CQ_EPI_SWIGLU) {
-          const float h0 = x0 / (1.f + __expf(-x0)) * x1;
-          const float h1 = x2 / (1.f + __expf(-x2)) * x3;
-          const size_t o = (size_t)m * p.out_ld + (row >> 1);
-          if constexpr (OUTK == CQ_OUT_F16) {
-            *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + o) =
-                f32_to_f16_bits_sat(h0) | (f32_to_f16_bits_sat(h1) << 16);
+        for (int h = 0; h < 2; ++h) {
+          // MFMA 32x32 output: register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+          const int vb = (wave & 1) * 2 + h;
+          const int row = u * 64 + rb * 32 + vb * 8 + g2 * 4;
+          const float x0 = sc * val[4 * h], x1 = sc * val[4 * h + 1], x2 = sc * val[4 * h + 2],
+                      x3 = sc * val[4 * h + 3];
+          if constexpr (EPI == CQ_EPI_SWIGLU) {
+            const float h0 = x0 / (1.f + __expf(-x0)) * x1;
+            const float h1 = x2 / (1.f + __expf(-x2)) * x3;
+            const size_t o = (size_t)m * p.out_ld + (row >> 1);
+            if constexpr (OUTK == CQ_OUT_F16) {
+              *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + o) =
+                  f32_to_f16_bits_sat(h0) | (f32_to_f16_bits_sat(h1) << 16);
+            } else {
+              *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + o) = make_float2(h0, h1);
+            }
           } else {
-            *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + o) = make_float2(h0, h1);
-          }
-        } else {
-          const size_t o = (size_t)m * p.out_ld + row;
-          if constexpr (OUTK == CQ_OUT_F16) {
-            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + o) =
-                make_uint2(f32_to_f16_bits_sat(x0) | (f32_to_f16_bits_sat(x1) << 16),
-                           f32_to_f16_bits_sat(x2) | (f32_to_f16_bits_sat(x3) << 16));
-          } else {
-            *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + o) = make_float4(x0, x1, x2, x3);
+            const size_t o = (size_t)m * p.out_ld + row;
+            if constexpr (OUTK == CQ_OUT_F16) {
+              *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + o) =
+                  make_uint2(f32_to_f16_bits_sat(x0) | (f32_to_f16_bits_sat(x1) << 16),
+                             f32_to_f16_bits_sat(x2) | (f32_to_f16_bits_sat(x3) << 16));
+            } else {
+              *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + o) = make_float4(x0, x1, x2, x3);
+            }
           }
         }
       }
     }
+    __syncthreads();  // the slab is restaged for the next token block
   }
 }
 
@@ -305,7 +369,8 @@ cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
       return CQ_ERR_HIP;
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.N / 64, G), dim3(256), kTableBytes + kSlabBytes, s, a);
+  const int n_units = a.N / 64;
+  hipLaunchKernelGGL(kern, dim3((n_units + a.upw - 1) / a.upw, G), dim3(256), kTableBytes + kSlabBytes, s, a);
   return cq_check_launch();
 }
 
@@ -338,6 +403,15 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   a.group_offsets = group_offsets;
   a.out = out;
   a.out_ld = epilogue == CQ_EPI_SWIGLU ? W->N / 2 : W->N;
+  {
+    // enough workgroups to fill 256 CUs a few times over, few enough that the per-workgroup
+    // prologue (activation staging) is amortised over several units
+    const long units = (long)(W->N / 64) * W->G;
+    long upw = (units + 1023) / 1024;
+    if (upw < 1) upw = 1;
+    if (upw > 16) upw = 16;
+    a.upw = (int)upw;
+  }
   switch (a_kind) {
     case CQ_A_INT8_CODES: return dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s);
     case CQ_A_F16: return dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s);

@@ -66,8 +66,11 @@ extern "C" cq_status cq_moe_workspace_layout(const cq_layer* L, int T, cq_moe_la
   return CQ_OK;
 }
 
-extern "C" cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y, void* workspace,
-                                    size_t workspace_bytes, cq_stream stream) {
+namespace {
+
+// ev: NULL, or CQ_N_STAGES + 1 events recorded at the stage boundaries.
+cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* workspace, size_t workspace_bytes,
+                    cq_stream stream, hipEvent_t* ev) {
   cq_status st = validate_layer(L, T);
   if (st != CQ_OK) return st;
   if (!X || !Y) return CQ_ERR_NULL;
@@ -90,17 +93,51 @@ extern "C" cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, fl
   void* scratch = ws + lay.scratch;
   const size_t scratch_bytes = lay.total - lay.scratch;
   const int M = T * (L->top_k + L->S);
+  hipStream_t hs = (hipStream_t)stream;
+  auto mark = [&](int i) -> bool { return !ev || hipEventRecord(ev[i], hs) == hipSuccess; };
 
+  if (!mark(0)) return CQ_ERR_HIP;
   st = cq_rotate_quant(X, L->R, T, L->H, L->act_bits, XR, Q, scale, scratch, scratch_bytes, stream);
   if (st != CQ_OK) return st;
+  if (!mark(1)) return CQ_ERR_HIP;
   st = cq_route_permute(XR, L->Wr, L->bias, nullptr, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets, perm,
                         inv_perm, src_token, scratch, scratch_bytes, stream);
   if (st != CQ_OK) return st;
+  if (!mark(2)) return CQ_ERR_HIP;
   st = cq_codebook_grouped_gemm(&L->gate_up, Q, CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU, Hbuf,
                                 CQ_OUT_F16, scratch, scratch_bytes, stream);
   if (st != CQ_OK) return st;
+  if (!mark(3)) return CQ_ERR_HIP;
   st = cq_codebook_grouped_gemm(&L->down, Hbuf, CQ_A_F16, nullptr, nullptr, offsets, M, CQ_EPI_NONE, Obuf,
                                 CQ_OUT_F32, scratch, scratch_bytes, stream);
   if (st != CQ_OK) return st;
-  return cq_combine(Obuf, tw, inv_perm, T, L->H, L->top_k, L->S, Y, stream);
+  if (!mark(4)) return CQ_ERR_HIP;
+  st = cq_combine(Obuf, tw, inv_perm, T, L->H, L->top_k, L->S, Y, stream);
+  if (st != CQ_OK) return st;
+  if (!mark(5)) return CQ_ERR_HIP;
+  return CQ_OK;
+}
+
+}  // namespace
+
+extern "C" cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y, void* workspace,
+                                    size_t workspace_bytes, cq_stream stream) {
+  return run_layer(L, X, T, Y, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" cq_status cq_moe_forward_timed(const cq_layer* L, const float* X, int T, float* Y, void* workspace,
+                                          size_t workspace_bytes, cq_stream stream, float* stage_ms) {
+  if (!stage_ms) return CQ_ERR_NULL;
+  hipEvent_t ev[CQ_N_STAGES + 1];
+  int made = 0;
+  cq_status st = CQ_OK;
+  for (; made <= CQ_N_STAGES; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) { st = CQ_ERR_HIP; break; }
+  if (st == CQ_OK) st = run_layer(L, X, T, Y, workspace, workspace_bytes, stream, ev);
+  if (st == CQ_OK && hipEventSynchronize(ev[CQ_N_STAGES]) != hipSuccess) st = CQ_ERR_HIP;
+  if (st == CQ_OK)
+    for (int i = 0; i < CQ_N_STAGES; ++i)
+      if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = CQ_ERR_HIP;
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return st;
 }
