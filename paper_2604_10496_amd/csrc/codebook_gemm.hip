@@ -24,13 +24,23 @@
 //   * Epilogue.  The four partial accumulators are summed through LDS in a fixed order (deterministic),
 //     scaled per token, optionally passed through SiLU(gate)*up (gate/up rows interleaved so both sit in
 //     one lane), and stored.
+#include <type_traits>
+
 #include "cq_internal.h"
 
 namespace {
 
 constexpr int kTableBytes = 65536;   // 256 entries x 64 row slots x 4 bytes
 constexpr int kSlabBytes = 65536;    // activation slab / reduction buffer
-constexpr int kRing = 8;             // K steps prefetched per wavefront
+#ifndef CQ_GEMM_WAVES
+#define CQ_GEMM_WAVES 8
+#endif
+#ifndef CQ_GEMM_RING
+#define CQ_GEMM_RING 4
+#endif
+constexpr int kWaves = CQ_GEMM_WAVES;  // wavefronts per workgroup: they split K (step s -> wavefront s % kWaves)
+constexpr int kRing = CQ_GEMM_RING;    // K steps prefetched per wavefront
+constexpr int kSlabCheck = 16 / kWaves;  // smallest number of wavefront steps in a slab (Mpad = 32)
 
 struct GemmArgs {
   const uint8_t* idx;       // canonical or prepacked index bytes, group-major
@@ -60,6 +70,12 @@ __device__ __forceinline__ uint32_t bf16_bits_to_f16_bits(uint32_t b) {
 // integer code -> bf16 bits: a float holding a small integer has zero low mantissa bits.
 __device__ __forceinline__ uint32_t code_to_bf16_bits(int c) { return __float_as_uint((float)c) >> 16; }
 
+// The pair table sits at LDS address 0 (the kernel has no static LDS, which the launcher verifies), so
+// a table lookup can use the byte offset built by v_perm_b32 as the LDS address itself.
+__device__ __forceinline__ uint32_t lds_read_u32(uint32_t byte_offset) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>((uintptr_t)byte_offset);
+}
+
 template <bool F16>
 __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f c) {
   cq_v4u bv = {b.x, b.y, b.z, b.w};
@@ -73,8 +89,10 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
 }
 
 template <int AK, int EPI, int OUTK>
-__global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
+__global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmArgs p) {
   constexpr bool F16 = (AK != CQ_A_INT8_CODES);
+  constexpr int NW = kWaves;
+  constexpr int NT = 64 * NW;
   extern __shared__ uint4 smem[];
   char* lds = reinterpret_cast<char*>(smem);
   uint32_t* tbl = reinterpret_cast<uint32_t*>(lds);
@@ -94,19 +112,19 @@ __global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
   const size_t rowbytes = (size_t)K >> 1;
   const uint8_t* gbase = p.idx + (size_t)grp * N * rowbytes;
   const int r32 = lane & 31, g2 = lane >> 5;
-  size_t lane_off[2];
+  size_t lane_off0, lane_off1;
   int sstride;
   if (p.prepacked) {
-    lane_off[0] = (size_t)lane * 16;
-    lane_off[1] = 32 * rowbytes + (size_t)lane * 16;
+    lane_off0 = (size_t)lane * 16;
+    lane_off1 = 32 * rowbytes + (size_t)lane * 16;
     sstride = 1024;
   } else {
-    lane_off[0] = (size_t)r32 * rowbytes + g2 * 16;
-    lane_off[1] = (size_t)(32 + r32) * rowbytes + g2 * 16;
+    lane_off0 = (size_t)r32 * rowbytes + g2 * 16;
+    lane_off1 = (size_t)(32 + r32) * rowbytes + g2 * 16;
     sstride = 32;
   }
   const int nS = K >> 6;                            // K steps of 64
-  const int Qmax = (nS + 3) >> 2;                   // steps per wavefront (upper bound)
+  const int Qmax = (nS + NW - 1) / NW;              // steps per wavefront (upper bound)
   const int Qpad = (Qmax + kRing - 1) / kRing * kRing;
   const uint32_t lanebase0 = (uint32_t)(r32 * 4);
   const uint32_t lanebase1 = (uint32_t)((32 + r32) * 4);
@@ -114,36 +132,40 @@ __global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
 
   for (int tb = 0; tb < n_tb; ++tb) {
     const int Mb = min(32, Me - 32 * tb);
-    const int Mpad = Mb <= 8 ? 8 : Mb <= 16 ? 16 : 32;      // divides 256: a thread stages one token
-    const int qPerSlab = Mpad == 8 ? 16 : Mpad == 16 ? 8 : 4;  // wavefront steps per slab (x256 k)
-    const int KSfull = qPerSlab << 8;
-    const bool multi = KSfull < K;                          // activations do not fit: restage per slab
-    const int nSlab = multi ? (K + KSfull - 1) / KSfull : 1;
-    const int tj = r32 < Mpad ? r32 : 0;                    // token column this lane feeds to the B operand
+    const int Mpad = Mb <= 8 ? 8 : Mb <= 16 ? 16 : 32;     // divides the workgroup: a thread stages one token
+    const int KSfull = 32768 / Mpad;                       // k values per slab (slab bytes / 2 / Mpad)
+    const int qPerSlab = (KSfull >> 6) / NW;               // wavefront steps per slab
+    const bool multi = KSfull < K;                         // activations do not fit: restage per slab
+    const int tj = r32 < Mpad ? r32 : 0;                   // token column this lane feeds to the B operand
 
-    // ---- this thread's staging duty: token st, chunks sc0 + i * cstep ----
+    // ---- this thread's staging duty: token st, 8-wide k chunks sc0, sc0 + cstep, ... ----
     const int st = tid & (Mpad - 1);
-    const int sc0 = tid / Mpad, cstep = 256 / Mpad;
+    const int sc0 = tid / Mpad, cstep = NT / Mpad;
     const bool svalid = st < Mb;
     size_t srow = 0;
     if (svalid) {
       const int m = m0 + 32 * tb + st;
       srow = (p.row_gather ? (size_t)p.row_gather[m] : (size_t)m) * K;
     }
-    uint4 sreg[16];
-    auto stage_load = [&](int sl) {
+    auto stage = [&](int sl) {
       const int k0 = sl * KSfull;
       const int nC = min(KSfull, K - k0) >> 3;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int c = sc0 + i * cstep;
+      for (int c = sc0; c < nC; c += cstep) {
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (svalid && c < nC) {
+        if (svalid) {
           const size_t e0 = srow + k0 + c * 8;
           if constexpr (AK == CQ_A_INT8_CODES) {
             const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0);
-            v.x = raw.x;
-            v.y = raw.y;
+            const uint32_t rw[2] = {raw.x, raw.y};
+            uint32_t o[4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
+              const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
+              o[2 * h] = code_to_bf16_bits(b0) | (code_to_bf16_bits(b1) << 16);
+              o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
+            }
+            v = make_uint4(o[0], o[1], o[2], o[3]);
           } else if constexpr (AK == CQ_A_F16) {
             v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0);
           } else {
@@ -155,44 +177,22 @@ __global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
             v.w = f32_to_f16_bits_sat(f1.z) | (f32_to_f16_bits_sat(f1.w) << 16);
           }
         }
-        sreg[i] = v;
-      }
-    };
-    auto stage_store = [&](int sl) {
-      const int k0 = sl * KSfull;
-      const int nC = min(KSfull, K - k0) >> 3;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int c = sc0 + i * cstep;
-        if (c < nC) {
-          uint4 v = sreg[i];
-          if constexpr (AK == CQ_A_INT8_CODES) {
-            const uint32_t rw[2] = {v.x, v.y};
-            uint32_t o[4];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-              const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
-              const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
-              o[2 * h] = code_to_bf16_bits(b0) | (code_to_bf16_bits(b1) << 16);
-              o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
-            }
-            v = make_uint4(o[0], o[1], o[2], o[3]);
-          }
-          slab[c * Mpad + st] = v;
-        }
+        slab[c * Mpad + st] = v;
       }
     };
 
     // ---- centroid rows of a unit, held raw in registers one unit ahead ----
     uint4 craw0, craw1;
-    uint2 chraw;
+    uint32_t chraw[(16 / NW + 1) / 2];
     auto cent_load = [&](int u) {
       const uint16_t* crow = p.cent + ((size_t)grp * N + (size_t)u * 64 + lane) * CQ_N_CENTROIDS;
       craw0 = reinterpret_cast<const uint4*>(crow)[0];
       craw1 = reinterpret_cast<const uint4*>(crow)[1];
-      chraw = *reinterpret_cast<const uint2*>(crow + 4 * wave);
+#pragma unroll
+      for (int i = 0; i < (16 / NW + 1) / 2; ++i)
+        chraw[i] = *reinterpret_cast<const uint32_t*>(crow + (16 / NW) * wave + 2 * i);
     };
-    // pair table: wavefront w writes the entries whose high nibble is 4w..4w+3; lane = row slot
+    // pair table: wavefront w writes the entries whose high nibble is in its share; lane = row slot
     auto build_table = [&]() {
       const uint32_t cp[8] = {craw0.x, craw0.y, craw0.z, craw0.w, craw1.x, craw1.y, craw1.z, craw1.w};
       uint32_t lo[16];
@@ -201,159 +201,193 @@ __global__ __launch_bounds__(256, 1) void gemm_small_kernel(const GemmArgs p) {
         lo[2 * i] = cp[i] & 0xffffu;
         lo[2 * i + 1] = cp[i] >> 16;
       }
-      uint32_t hv[4] = {chraw.x & 0xffffu, chraw.x >> 16, chraw.y & 0xffffu, chraw.y >> 16};
       if constexpr (F16) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) lo[i] = bf16_bits_to_f16_bits(lo[i]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) hv[i] = bf16_bits_to_f16_bits(hv[i]);
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int hi = 4 * wave + i;
-        const uint32_t hs = hv[i] << 16;
+      for (int i = 0; i < 16 / NW; ++i) {
+        uint32_t hv = (i & 1) ? (chraw[i >> 1] >> 16) : (chraw[i >> 1] & 0xffffu);
+        if constexpr (F16) hv = bf16_bits_to_f16_bits(hv);
+        const int hi = (16 / NW) * wave + i;
+        const uint32_t hs = hv << 16;
 #pragma unroll
         for (int l = 0; l < 16; ++l) tbl[(hi * 16 + l) * 64 + lane] = lo[l] | hs;
       }
     };
 
-    stage_load(0);
+    // per-token scale of this lane's output column (loop invariant: loaded once per token block)
+    float sc = 1.f;
+    if (p.row_scale && r32 < Mb) {
+      const int m = m0 + 32 * tb + r32;
+      sc = p.row_scale[p.row_gather ? p.row_gather[m] : m];
+    }
     cent_load(u0);
+    __builtin_amdgcn_sched_barrier(0);  // keep the centroid loads older than the ring loads
     uint4 ring[kRing][2];
     {
       const uint8_t* wb = gbase + (size_t)u0 * 64 * rowbytes;
 #pragma unroll
       for (int j = 0; j < kRing; ++j) {
-        const int gs = wave + 4 * j;
+        const int gs = wave + NW * j;
         const size_t off = (size_t)(gs < nS ? gs : 0) * sstride;
-        ring[j][0] = *reinterpret_cast<const uint4*>(wb + lane_off[0] + off);
-        ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off[1] + off);
+        ring[j][0] = *reinterpret_cast<const uint4*>(wb + lane_off0 + off);
+        ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off1 + off);
       }
     }
 
-    for (int u = u0; u < u1; ++u) {
-      const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
-      const uint8_t* wb_next = wb + 64 * rowbytes;
-      const bool has_next = u + 1 < u1;
-      build_table();
-      if (has_next) cent_load(u + 1);
-      __syncthreads();
+    // The unit loop exists in two instantiations.  When the block's activations fit in LDS for the whole
+    // of K (the decode case) they are staged once, up front, and the loop body contains no conditional
+    // loads at all: the number of loads in flight is then the same on every path, which lets each wait
+    // cover exactly one ring slot.  Otherwise the slab is restaged inside the loop.
+    auto run_units = [&](auto multi_tag) {
+      constexpr bool MULTI = decltype(multi_tag)::value;
+      for (int u = u0; u < u1; ++u) {
+        const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
+        const bool has_next = u + 1 < u1;
+        const uint8_t* wb_next = has_next ? wb + 64 * rowbytes : wb;
+        build_table();
+        __syncthreads();
 
-      cq_v16f acc0, acc1;
+        cq_v16f acc0, acc1;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
+        for (int i = 0; i < 16; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
 
-      // Ring loads are issued unconditionally (with the address clamped to a step that exists) so
-      // that the number of loads in flight is the same on every path and the wait before a slot is
-      // consumed only covers that slot; math for steps past the end of K is skipped.
-      const size_t clamp_off = 0;  // step 0 of the unit always exists
-      for (int q0 = 0; q0 < Qpad; q0 += kRing) {
+        // Ring loads are issued unconditionally (address clamped to step 0 when the step does not exist)
+        // so that the number of loads in flight is the same on every path and the wait before a slot
+        // is consumed covers that slot only; the math of steps past the end of K is skipped.
+        auto ring_round = [&](const int q0) {
 #pragma unroll
-        for (int j = 0; j < kRing; ++j) {
-          const int q = q0 + j;
-          if (j % 4 == 0) {
-            // slab boundary (qPerSlab is a multiple of 4): publish the slab held in registers, then
-            // start loading the one after it so that its latency hides behind this slab's math
-            if (q < Qmax && q % qPerSlab == 0 && (multi || u == u0)) {
-              const int sl = q / qPerSlab;
-              __syncthreads();
-              stage_store(sl);
-              __syncthreads();
-              if (multi) {
-                if (sl + 1 < nSlab) stage_load(sl + 1);
-                else if (has_next) stage_load(0);
+          for (int j = 0; j < kRing; ++j) {
+            const int q = q0 + j;
+            if constexpr (MULTI) {
+              if (j % kSlabCheck == 0) {
+                // slab boundary: restage the activations for the next K range
+                if (q < Qmax && q % qPerSlab == 0) {
+                  __syncthreads();
+                  stage(q / qPerSlab);
+                  __syncthreads();
+                }
+              }
+            }
+            const int gs = wave + NW * q;
+            // LDS addresses of this step's 32 table lookups (pair index byte -> entry, row slot -> bank);
+            // computed first so that the ring slot is dead before it is refilled (the refill can then
+            // land in the very same registers)
+            uint32_t o0[16], o1[16];
+            {
+              const uint4 w0 = ring[j][0], w1 = ring[j][1];
+              const uint32_t wd0[4] = {w0.x, w0.y, w0.z, w0.w};
+              const uint32_t wd1[4] = {w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+              for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                  o0[jj * 4 + i] = __builtin_amdgcn_perm(wd0[jj], lanebase0, 0x0c0c0400u + (i << 8));
+                  o1[jj * 4 + i] = __builtin_amdgcn_perm(wd1[jj], lanebase1, 0x0c0c0400u + (i << 8));
+                  // pin the address here: it must not be recomputed from the ring slot after the refill
+                  asm volatile("" : "+v"(o0[jj * 4 + i]), "+v"(o1[jj * 4 + i]));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);  // the refill below must not move above the last use of the slot
+            {
+              const int qq = q + kRing;  // the step that reuses this ring slot
+              const bool same = qq < Qpad;
+              const int gn = wave + NW * (same ? qq : qq - Qpad);
+              const uint8_t* base = same ? wb : wb_next;
+              const size_t off = (gn < nS && (same || has_next)) ? (size_t)gn * sstride : 0;
+              ring[j][0] = *reinterpret_cast<const uint4*>(base + lane_off0 + off);
+              ring[j][1] = *reinterpret_cast<const uint4*>(base + lane_off1 + off);
+            }
+            if (gs < nS) {
+              // chunk (8 k) index inside the slab of this lane's first fragment
+              const int ls = gs - (q / qPerSlab) * (qPerSlab * NW);
+              const uint4* bsrc = slab + (size_t)(ls * 8 + g2 * 4) * Mpad + tj;
+#pragma unroll
+              for (int jj = 0; jj < 4; ++jj) {
+                const uint4 bf = bsrc[(size_t)jj * Mpad];
+                cq_v4u a0, a1;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                  a0[i] = lds_read_u32(o0[jj * 4 + i]);
+                  a1[i] = lds_read_u32(o1[jj * 4 + i]);
+                }
+                acc0 = mfma32<F16>(a0, bf, acc0);
+                acc1 = mfma32<F16>(a1, bf, acc1);
               }
             }
           }
-          const int gs = wave + 4 * q;
-          const uint4 w0 = ring[j][0], w1 = ring[j][1];
-          {
-            const int qq = q + kRing;  // the step that reuses this ring slot
-            const bool same = qq < Qpad;
-            const int gn = wave + 4 * (same ? qq : qq - Qpad);
-            const uint8_t* base = (same || !has_next) ? wb : wb_next;
-            const size_t off = (gn < nS && (same || has_next)) ? (size_t)gn * sstride : clamp_off;
-            ring[j][0] = *reinterpret_cast<const uint4*>(base + lane_off[0] + off);
-            ring[j][1] = *reinterpret_cast<const uint4*>(base + lane_off[1] + off);
+        };
+        for (int q0 = 0; q0 < Qpad; q0 += kRing) {
+          // The next unit's centroid rows are requested ahead of a round's weight loads (every round
+          // in the single-slab loop, so that no load is conditional; only the last request matters):
+          // a fixed number of younger loads then sits behind them, and the wait at the top of the
+          // next unit does not drain the weight ring.
+          if (MULTI ? (q0 + kRing >= Qpad) : true) {
+            cent_load(has_next ? u + 1 : u);
+            __builtin_amdgcn_sched_barrier(0);
           }
-          if (gs < nS) {
-            // chunk (8 k) index inside the slab of this lane's first fragment
-            const int ls = gs - (q / qPerSlab) * (qPerSlab << 2);
-            const uint4* bsrc = slab + (size_t)(ls * 8 + g2 * 4) * Mpad + tj;
-            const uint32_t wd0[4] = {w0.x, w0.y, w0.z, w0.w};
-            const uint32_t wd1[4] = {w1.x, w1.y, w1.z, w1.w};
+          ring_round(q0);
+        }
+
+        // ---- reduce the K partials (fixed order) through the table's LDS and finish ----
+        __syncthreads();
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-              const uint4 bf = bsrc[(size_t)jj * Mpad];
-              cq_v4u a0, a1;
+        for (int i = 0; i < 16; ++i) {
+          red[(wave * 32 + i) * 64 + lane] = acc0[i];
+          red[(wave * 32 + 16 + i) * 64 + lane] = acc1[i];
+        }
+        __syncthreads();
+        // wavefront w finishes accumulator registers RPW*w .. RPW*w + RPW-1 of the 32
+        constexpr int RPW = 32 / NW;
+        float val[RPW];
 #pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const uint32_t o0 = __builtin_amdgcn_perm(wd0[jj], lanebase0, 0x0c0c0400u + (i << 8));
-                const uint32_t o1 = __builtin_amdgcn_perm(wd1[jj], lanebase1, 0x0c0c0400u + (i << 8));
-                a0[i] = *reinterpret_cast<const uint32_t*>(lds + o0);
-                a1[i] = *reinterpret_cast<const uint32_t*>(lds + o1);
+        for (int i = 0; i < RPW; ++i) {
+          const int r = wave * RPW + i;
+          float s = red[r * 64 + lane];
+#pragma unroll
+          for (int w = 1; w < NW; ++w) s += red[(w * 32 + r) * 64 + lane];
+          val[i] = s;
+        }
+        __syncthreads();  // the next unit's table overwrites this region
+        if (r32 < Mb) {
+          const int m = m0 + 32 * tb + r32;
+#pragma unroll
+          for (int h = 0; h < RPW / 4; ++h) {
+            // MFMA 32x32 output: register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+            const int r = wave * RPW + 4 * h;          // first of four registers: r = 16*rb + 4*vb
+            const int row = u * 64 + (r >> 4) * 32 + ((r >> 2) & 3) * 8 + g2 * 4;
+            const float x0 = sc * val[4 * h], x1 = sc * val[4 * h + 1], x2 = sc * val[4 * h + 2],
+                        x3 = sc * val[4 * h + 3];
+            if constexpr (EPI == CQ_EPI_SWIGLU) {
+              const float h0 = x0 / (1.f + __expf(-x0)) * x1;
+              const float h1 = x2 / (1.f + __expf(-x2)) * x3;
+              const size_t o = (size_t)m * p.out_ld + (row >> 1);
+              if constexpr (OUTK == CQ_OUT_F16) {
+                *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + o) =
+                    f32_to_f16_bits_sat(h0) | (f32_to_f16_bits_sat(h1) << 16);
+              } else {
+                *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + o) = make_float2(h0, h1);
               }
-              acc0 = mfma32<F16>(a0, bf, acc0);
-              acc1 = mfma32<F16>(a1, bf, acc1);
+            } else {
+              const size_t o = (size_t)m * p.out_ld + row;
+              if constexpr (OUTK == CQ_OUT_F16) {
+                *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + o) =
+                    make_uint2(f32_to_f16_bits_sat(x0) | (f32_to_f16_bits_sat(x1) << 16),
+                               f32_to_f16_bits_sat(x2) | (f32_to_f16_bits_sat(x3) << 16));
+              } else {
+                *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + o) = make_float4(x0, x1, x2, x3);
+              }
             }
           }
         }
       }
-
-      // ---- reduce the four K partials (fixed order) through the table's LDS and finish ----
-      __syncthreads();
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        red[(wave * 32 + i) * 64 + lane] = acc0[i];
-        red[(wave * 32 + 16 + i) * 64 + lane] = acc1[i];
-      }
-      __syncthreads();
-      // wavefront w finishes accumulator registers 8w..8w+7 of the 32 (row block w/2, v = 8(w%2)..+7)
-      float val[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int r = wave * 8 + i;
-        float s = red[(0 * 32 + r) * 64 + lane];
-        s += red[(1 * 32 + r) * 64 + lane];
-        s += red[(2 * 32 + r) * 64 + lane];
-        s += red[(3 * 32 + r) * 64 + lane];
-        val[i] = s;
-      }
-      __syncthreads();  // the next unit's table overwrites this region
-      if (r32 < Mb) {
-        const int m = m0 + 32 * tb + r32;
-        float sc = 1.f;
-        if (p.row_scale) sc = p.row_scale[p.row_gather ? p.row_gather[m] : m];
-        const int rb = wave >> 1;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          // MFMA 32x32 output: register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
-          const int vb = (wave & 1) * 2 + h;
-          const int row = u * 64 + rb * 32 + vb * 8 + g2 * 4;
-          const float x0 = sc * val[4 * h], x1 = sc * val[4 * h + 1], x2 = sc * val[4 * h + 2],
-                      x3 = sc * val[4 * h + 3];
-          if constexpr (EPI == CQ_EPI_SWIGLU) {
-            const float h0 = x0 / (1.f + __expf(-x0)) * x1;
-            const float h1 = x2 / (1.f + __expf(-x2)) * x3;
-            const size_t o = (size_t)m * p.out_ld + (row >> 1);
-            if constexpr (OUTK == CQ_OUT_F16) {
-              *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + o) =
-                  f32_to_f16_bits_sat(h0) | (f32_to_f16_bits_sat(h1) << 16);
-            } else {
-              *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + o) = make_float2(h0, h1);
-            }
-          } else {
-            const size_t o = (size_t)m * p.out_ld + row;
-            if constexpr (OUTK == CQ_OUT_F16) {
-              *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + o) =
-                  make_uint2(f32_to_f16_bits_sat(x0) | (f32_to_f16_bits_sat(x1) << 16),
-                             f32_to_f16_bits_sat(x2) | (f32_to_f16_bits_sat(x3) << 16));
-            } else {
-              *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + o) = make_float4(x0, x1, x2, x3);
-            }
-          }
-        }
-      }
+    };
+    if (multi) {
+      run_units(std::true_type{});
+    } else {
+      stage(0);
+      run_units(std::false_type{});
     }
     __syncthreads();  // the slab is restaged for the next token block
   }
@@ -364,13 +398,16 @@ cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
   auto kern = gemm_small_kernel<AK, EPI, OUTK>;
   static bool configured = false;
   if (!configured) {
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
+    if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             kTableBytes + kSlabBytes) != hipSuccess)
       return CQ_ERR_HIP;
     configured = true;
   }
   const int n_units = a.N / 64;
-  hipLaunchKernelGGL(kern, dim3((n_units + a.upw - 1) / a.upw, G), dim3(256), kTableBytes + kSlabBytes, s, a);
+  hipLaunchKernelGGL(kern, dim3((n_units + a.upw - 1) / a.upw, G), dim3(64 * kWaves), kTableBytes + kSlabBytes, s, a);
   return cq_check_launch();
 }
 
@@ -404,12 +441,12 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   a.out = out;
   a.out_ld = epilogue == CQ_EPI_SWIGLU ? W->N / 2 : W->N;
   {
-    // enough workgroups to fill 256 CUs a few times over, few enough that the per-workgroup
-    // prologue (activation staging) is amortised over several units
+    // about one workgroup per compute unit: the per-workgroup prologue (activation staging, first
+    // table, ring fill) is paid once and there is no partially filled last round of workgroups
     const long units = (long)(W->N / 64) * W->G;
-    long upw = (units + 1023) / 1024;
+    long upw = (units + 255) / 256;
     if (upw < 1) upw = 1;
-    if (upw > 16) upw = 16;
+    if (upw > W->N / 64) upw = W->N / 64;
     a.upw = (int)upw;
   }
   switch (a_kind) {
