@@ -31,10 +31,12 @@ struct cq_gemm_f32_plan {
 };
 cq_gemm_f32_plan cq_gemm_f32_make_plan(int T, int N, int K);
 cq_status cq_gemm_f32_launch(const float* A, const float* B, int b_transposed, int T, int N, int K,
-                             const cq_gemm_f32_plan& plan, float* C_or_partials, hipStream_t s);
+                             const cq_gemm_f32_plan& plan, float* C_or_partials, uint32_t* zero_me, int zero_n,
+                             hipStream_t s);
 
 cq_status cq_quantize_launch(const float* partials, int ksplit, int T, int H, int act_bits,
-                             float* XR_out, int8_t* Q_out, float* scale_out, hipStream_t s);
+                             float* XR_out, int8_t* Q_out, float* scale_out, uint32_t* amax_bits,
+                             hipStream_t s);
 
 cq_status cq_topk_launch(const float* logit_partials, int ksplit, const float* bias, int T, int E, int top_k,
                          float* logits_out, int32_t* topk_ids, float* topk_w, hipStream_t s);

@@ -15,10 +15,14 @@
 
 namespace {
 
-template <int MB, int WM, bool BT>
+template <int MB, int WM, bool BT, int D>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B,
-                                                       float* __restrict__ C, int T, int N, int K, int kchunk) {
+                                                       float* __restrict__ C, int T, int N, int K, int kchunk,
+                                                       uint32_t* __restrict__ zero_me, int zero_n) {
   constexpr int WN = 4 / WM;
+  // side job of the first workgroup: clear a small buffer the next kernel accumulates into
+  if (zero_me && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+    for (int i = threadIdx.x; i < zero_n; i += 256) zero_me[i] = 0u;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int wm = wave % WM, wn = wave / WM;
@@ -28,6 +32,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
   const int j = lane & 15, g = lane >> 4;
   const int kbeg = blockIdx.z * kchunk;
   const int kend = min(K, kbeg + kchunk);
+  const int steps = (kend - kbeg) >> 4;
 
   const float* pa[MB];
 #pragma unroll
@@ -52,8 +57,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 #pragma unroll
     for (int n = 0; n < 4; ++n) acc[mb][n] = cq_v4f{0.f, 0.f, 0.f, 0.f};
 
-  float4 a_cur[MB], b_cur[4], a_nxt[MB], b_nxt[4];
-  auto load = [&](float4* a, float4* b, int ks) {
+  // register ring of D K-steps; loads are unconditional (step index clamped) so that every wait
+  // covers exactly one slot
+  float4 ra[D][MB], rb[D][4];
+  auto load = [&](float4* a, float4* b, int step) {
+    const int ks = kbeg + 16 * min(step, steps - 1);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) a[mb] = *reinterpret_cast<const float4*>(pa[mb] + ks);
 #pragma unroll
@@ -61,30 +69,35 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
       b[x] = BT ? *reinterpret_cast<const float4*>(pb[x] + ks)
                 : *reinterpret_cast<const float4*>(pb[x] + (size_t)ks * N);
   };
-  load(a_cur, b_cur, kbeg);
-  for (int ks = kbeg; ks < kend; ks += 16) {
-    const bool more = ks + 16 < kend;
-    if (more) load(a_nxt, b_nxt, ks + 16);
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
+  for (int d = 0; d < D; ++d) load(ra[d], rb[d], d);
+  for (int s0 = 0; s0 < steps; s0 += D) {
 #pragma unroll
-      for (int n = 0; n < 4; ++n) {
-        const float4 bq = BT ? b_cur[n] : b_cur[m];
-        const int be = BT ? m : n;
-        const float bval = be == 0 ? bq.x : be == 1 ? bq.y : be == 2 ? bq.z : bq.w;
+    for (int d = 0; d < D; ++d) {
+      const int st = s0 + d;
+      float4 a_cur[MB], b_cur[4];
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          const float4 aq = a_cur[mb];
-          const float aval = m == 0 ? aq.x : m == 1 ? aq.y : m == 2 ? aq.z : aq.w;
-          acc[mb][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aval, bval, acc[mb][n], 0, 0, 0);
+      for (int mb = 0; mb < MB; ++mb) a_cur[mb] = ra[d][mb];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) b_cur[x] = rb[d][x];
+      load(ra[d], rb[d], st + D);
+      if (st < steps) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+#pragma unroll
+          for (int n = 0; n < 4; ++n) {
+            const float4 bq = BT ? b_cur[n] : b_cur[m];
+            const int be = BT ? m : n;
+            const float bval = be == 0 ? bq.x : be == 1 ? bq.y : be == 2 ? bq.z : bq.w;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+              const float4 aq = a_cur[mb];
+              const float aval = m == 0 ? aq.x : m == 1 ? aq.y : m == 2 ? aq.z : aq.w;
+              acc[mb][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aval, bval, acc[mb][n], 0, 0, 0);
+            }
+          }
         }
       }
-    }
-    if (more) {
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) a_cur[mb] = a_nxt[mb];
-#pragma unroll
-      for (int x = 0; x < 4; ++x) b_cur[x] = b_nxt[x];
     }
   }
 
@@ -107,6 +120,55 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
         *reinterpret_cast<float4*>(Cz + (size_t)tok * N + c0 + 4 * j) = o;
       }
     }
+  }
+}
+
+// Few tokens: a row is spread over several workgroups.  Pass 1 reduces the K-split partials in a fixed
+// order, keeps X_R and folds the chunk maximum into amax_bits[t] with an integer atomic max (the bit
+// pattern of a non-negative float orders like the float, and a maximum does not depend on the order of
+// its operands, so the result is deterministic).  Pass 2 rounds x / s to the nearest integer.
+__global__ __launch_bounds__(256) void reduce_amax_kernel(const float* part, int ksplit, int in_place, int T, int H,
+                                                          float* XR, uint32_t* __restrict__ amax_bits) {
+  __shared__ float red[4];
+  const int t = blockIdx.y, tid = threadIdx.x;
+  const int c = (blockIdx.x * 256 + tid) * 4;
+  float amax = 0.f;
+  if (c < H) {
+    float4 v = *reinterpret_cast<const float4*>(part + (size_t)t * H + c);
+    for (int z = 1; z < ksplit; ++z) {
+      const float4 p = *reinterpret_cast<const float4*>(part + ((size_t)z * T + t) * H + c);
+      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    if (!in_place) *reinterpret_cast<float4*>(XR + (size_t)t * H + c) = v;
+    amax = fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w)));
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+  if ((tid & 63) == 0) red[tid >> 6] = amax;
+  __syncthreads();
+  if (tid == 0) {
+    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    atomicMax(amax_bits + t, __float_as_uint(amax));
+  }
+}
+
+__global__ __launch_bounds__(256) void codes_kernel(const float* __restrict__ XR, const uint32_t* __restrict__ amax_bits,
+                                                    int H, float qmax, int8_t* __restrict__ Q,
+                                                    float* __restrict__ scale) {
+  const int t = blockIdx.y, tid = threadIdx.x;
+  const int c = (blockIdx.x * 256 + tid) * 4;
+  const float amax = __uint_as_float(amax_bits[t]);
+  const float s = amax == 0.f ? 1.f : amax / qmax;
+  if (blockIdx.x == 0 && tid == 0) scale[t] = s;
+  if (c < H) {
+    const float4 v = *reinterpret_cast<const float4*>(XR + (size_t)t * H + c);
+    const float r0 = fminf(fmaxf(rintf(v.x / s), -qmax), qmax);
+    const float r1 = fminf(fmaxf(rintf(v.y / s), -qmax), qmax);
+    const float r2 = fminf(fmaxf(rintf(v.z / s), -qmax), qmax);
+    const float r3 = fminf(fmaxf(rintf(v.w / s), -qmax), qmax);
+    const uint32_t packed = ((uint32_t)(int)r0 & 0xffu) | (((uint32_t)(int)r1 & 0xffu) << 8) |
+                            (((uint32_t)(int)r2 & 0xffu) << 16) | (((uint32_t)(int)r3 & 0xffu) << 24);
+    *reinterpret_cast<uint32_t*>(Q + (size_t)t * H + c) = packed;
   }
 }
 
@@ -169,38 +231,55 @@ cq_gemm_f32_plan cq_gemm_f32_make_plan(int T, int N, int K) {
 }
 
 cq_status cq_gemm_f32_launch(const float* A, const float* B, int b_transposed, int T, int N, int K,
-                             const cq_gemm_f32_plan& plan, float* C, hipStream_t s) {
+                             const cq_gemm_f32_plan& plan, float* C, uint32_t* zero_me, int zero_n, hipStream_t s) {
   const int kchunk = plan.kchunk;
   dim3 block(256);
   if (plan.mb == 4) {
     dim3 grid((N + 127) / 128, (T + 127) / 128, plan.ksplit);
     if (b_transposed)
-      hipLaunchKernelGGL((gemm_f32_kernel<4, 2, true>), grid, block, 0, s, A, B, C, T, N, K, kchunk);
+      hipLaunchKernelGGL((gemm_f32_kernel<4, 2, true, 2>), grid, block, 0, s, A, B, C, T, N, K, kchunk, zero_me,
+                         zero_n);
     else
-      hipLaunchKernelGGL((gemm_f32_kernel<4, 2, false>), grid, block, 0, s, A, B, C, T, N, K, kchunk);
+      hipLaunchKernelGGL((gemm_f32_kernel<4, 2, false, 2>), grid, block, 0, s, A, B, C, T, N, K, kchunk, zero_me,
+                         zero_n);
   } else {
     dim3 grid((N + 255) / 256, (T + 15) / 16, plan.ksplit);
     if (b_transposed)
-      hipLaunchKernelGGL((gemm_f32_kernel<1, 1, true>), grid, block, 0, s, A, B, C, T, N, K, kchunk);
+      hipLaunchKernelGGL((gemm_f32_kernel<1, 1, true, 4>), grid, block, 0, s, A, B, C, T, N, K, kchunk, zero_me,
+                         zero_n);
     else
-      hipLaunchKernelGGL((gemm_f32_kernel<1, 1, false>), grid, block, 0, s, A, B, C, T, N, K, kchunk);
+      hipLaunchKernelGGL((gemm_f32_kernel<1, 1, false, 4>), grid, block, 0, s, A, B, C, T, N, K, kchunk, zero_me,
+                         zero_n);
   }
   return cq_check_launch();
 }
 
 cq_status cq_quantize_launch(const float* partials, int ksplit, int T, int H, int act_bits, float* XR_out,
-                             int8_t* Q_out, float* scale_out, hipStream_t s) {
+                             int8_t* Q_out, float* scale_out, uint32_t* amax_bits, hipStream_t s) {
   const float qmax = (float)((1 << (act_bits - 1)) - 1);
   const int in_place = (partials == XR_out && ksplit == 1) ? 1 : 0;
-  hipLaunchKernelGGL(quantize_kernel, dim3(T), dim3(256), 0, s, partials, ksplit, in_place, T, H, qmax, XR_out,
-                     Q_out, scale_out);
+  if (amax_bits) {  // few tokens: spread every row over several workgroups (amax_bits was zeroed upstream)
+    dim3 grid((H + 1023) / 1024, T);
+    hipLaunchKernelGGL(reduce_amax_kernel, grid, dim3(256), 0, s, partials, ksplit, in_place, T, H, XR_out,
+                       amax_bits);
+    hipLaunchKernelGGL(codes_kernel, grid, dim3(256), 0, s, (const float*)XR_out, (const uint32_t*)amax_bits, H, qmax,
+                       Q_out, scale_out);
+  } else {
+    hipLaunchKernelGGL(quantize_kernel, dim3(T), dim3(256), 0, s, partials, ksplit, in_place, T, H, qmax, XR_out,
+                       Q_out, scale_out);
+  }
   return cq_check_launch();
 }
+
+namespace {
+constexpr int kFewTokens = 256;  // below this a token row is quantized by several workgroups
+size_t amax_bytes(int T) { return T < kFewTokens ? cq_align_up((size_t)T * sizeof(uint32_t), 256) : 0; }
+}  // namespace
 
 extern "C" size_t cq_rotate_quant_workspace_bytes(int T, int H) {
   if (T <= 0 || H <= 0) return 0;
   const cq_gemm_f32_plan p = cq_gemm_f32_make_plan(T, H, H);
-  return p.ksplit > 1 ? cq_align_up((size_t)p.ksplit * T * H * sizeof(float), 256) : 0;
+  return amax_bytes(T) + (p.ksplit > 1 ? cq_align_up((size_t)p.ksplit * T * H * sizeof(float), 256) : 0);
 }
 
 extern "C" cq_status cq_rotate_quant(const float* X, const float* R, int T, int H, int act_bits, float* XR_out,
@@ -213,8 +292,10 @@ extern "C" cq_status cq_rotate_quant(const float* X, const float* R, int T, int 
   if (need > 0 && (!workspace || workspace_bytes < need)) return CQ_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   const cq_gemm_f32_plan p = cq_gemm_f32_make_plan(T, H, H);
-  float* dst = p.ksplit > 1 ? (float*)workspace : XR_out;
-  cq_status st = cq_gemm_f32_launch(X, R, 0, T, H, H, p, dst, s);
+  uint32_t* amax = amax_bytes(T) ? (uint32_t*)workspace : nullptr;
+  float* part = (float*)((char*)workspace + amax_bytes(T));
+  float* dst = p.ksplit > 1 ? part : XR_out;
+  cq_status st = cq_gemm_f32_launch(X, R, 0, T, H, H, p, dst, amax, T, s);
   if (st != CQ_OK) return st;
-  return cq_quantize_launch(dst, p.ksplit, T, H, act_bits, XR_out, Q_out, scale_out, s);
+  return cq_quantize_launch(dst, p.ksplit, T, H, act_bits, XR_out, Q_out, scale_out, amax, s);
 }

@@ -21,6 +21,77 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 
 __device__ __forceinline__ uint64_t lanemask_lt(int lane) { return (1ull << lane) - 1ull; }
 
+// Top-k of one token by one wavefront.  val[s] is the logit of expert s*64 + lane.  Called by all
+// wavefronts of the workgroup together (it contains workgroup barriers); sk/si/sv/ss are this
+// wavefront's 64-entry LDS scratch arrays.  Writes ids (descending logit, ties -> lower id) and the
+// softmax over the selected logits; lds_ids, if given, also receives the ids.
+template <int NSLOT>
+__device__ __forceinline__ void wave_topk(const float (&val)[NSLOT], int nslot, int E, int k, bool active, int lane,
+                                          uint32_t* sk, int* si, float* sv, float* ss, int32_t* ids_out,
+                                          float* w_out, int* lds_ids) {
+  const uint64_t lt = lanemask_lt(lane);
+  uint32_t key[NSLOT];
+#pragma unroll
+  for (int s = 0; s < NSLOT; ++s) key[s] = (s < nslot && (s * 64 + lane) < E) ? order_key(val[s]) : 0u;
+  // k-th largest key: keep the largest prefix such that at least k keys are >= it.
+  uint32_t kth = 0u;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = kth | (1u << bit);
+    int cnt = 0;
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s)
+      if (s < nslot) cnt += __popcll(__ballot((s * 64 + lane) < E && key[s] >= cand));
+    if (cnt >= k) kth = cand;
+  }
+  int n_gt = 0;
+#pragma unroll
+  for (int s = 0; s < NSLOT; ++s)
+    if (s < nslot) n_gt += __popcll(__ballot((s * 64 + lane) < E && key[s] > kth));
+  const int need = k - n_gt;  // how many of the keys equal to kth are admitted (lowest ids first)
+  int base = 0, ties_seen = 0;
+#pragma unroll
+  for (int s = 0; s < NSLOT; ++s) {
+    if (s < nslot) {
+      const bool valid = (s * 64 + lane) < E;
+      const bool eq = valid && key[s] == kth;
+      const uint64_t m_eq = __ballot(eq);
+      const int tie_rank = ties_seen + __popcll(m_eq & lt);
+      const bool sel = valid && (key[s] > kth || (eq && tie_rank < need));
+      const uint64_t m_sel = __ballot(sel);
+      const int pos = base + __popcll(m_sel & lt);
+      if (sel && active) {
+        sk[pos] = key[s];
+        si[pos] = s * 64 + lane;
+        sv[pos] = val[s];
+      }
+      base += __popcll(m_sel);
+      ties_seen += __popcll(m_eq);
+    }
+  }
+  __syncthreads();
+  if (active && lane < k) {
+    const uint32_t mk = sk[lane];
+    const int mi = si[lane];
+    int rank = 0;
+    for (int p = 0; p < k; ++p) {
+      const uint32_t ok = sk[p];
+      const int oi = si[p];
+      rank += (ok > mk || (ok == mk && oi < mi)) ? 1 : 0;
+    }
+    ids_out[rank] = mi;
+    if (lds_ids) lds_ids[rank] = mi;
+    ss[rank] = sv[lane];
+  }
+  __syncthreads();
+  float ex = 0.f;
+  if (active && lane < k) ex = expf(ss[lane] - ss[0]);
+  float sum = ex;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+  if (active && lane < k) w_out[lane] = ex / sum;
+  __syncthreads();  // the scratch arrays may be reused by the caller's next token
+}
+
 __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ part, int ksplit,
                                                    const float* __restrict__ bias, int T, int E, int k,
                                                    float* __restrict__ logits_out, int32_t* __restrict__ ids,
@@ -33,79 +104,149 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ par
   const int t = blockIdx.x * 4 + wave;
   const bool active = t < T;
   const int nslot = (E + 63) / 64;
-  const uint64_t lt = lanemask_lt(lane);
-
   float val[kMaxSlots];
-  uint32_t key[kMaxSlots];
 #pragma unroll
   for (int s = 0; s < kMaxSlots; ++s) {
     const int e = s * 64 + lane;
     val[s] = 0.f;
-    key[s] = 0u;
     if (s < nslot && e < E && active) {
       float x = part[(size_t)t * E + e];
       for (int z = 1; z < ksplit; ++z) x += part[((size_t)z * T + t) * E + e];
       if (bias) x += bias[e];
       if (logits_out) logits_out[(size_t)t * E + e] = x;
       val[s] = x;
-      key[s] = order_key(x);
     }
   }
-  // k-th largest key: keep the largest prefix such that at least k keys are >= it.
-  uint32_t kth = 0u;
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t cand = kth | (1u << bit);
-    int cnt = 0;
+  const size_t o = active ? (size_t)t * k : 0;
+  wave_topk<kMaxSlots>(val, nslot, E, k, active, lane, s_key[wave], s_id[wave], s_val[wave], s_sorted[wave], ids + o,
+                       w + o, nullptr);
+}
+
+// Router logits for decode-sized batches: one workgroup per (token, four experts); its four wavefronts
+// split K, issue all their loads at once (one memory latency in total) and combine through LDS in a
+// fixed order.  Plain fp32 FMAs: T*E*H is tiny here.
+__global__ __launch_bounds__(256) void logits_small_kernel(const float* __restrict__ XR, const float* __restrict__ Wr,
+                                                           const float* __restrict__ bias, int H, int E,
+                                                           float* __restrict__ logits) {
+  __shared__ float part[4][4];
+  const int t = blockIdx.y, e0 = blockIdx.x * 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float* xr = XR + (size_t)t * H;
+  const float* wr[4];
 #pragma unroll
-    for (int s = 0; s < kMaxSlots; ++s)
-      if (s < nslot) cnt += __popcll(__ballot((s * 64 + lane) < E && key[s] >= cand));
-    if (cnt >= k) kth = cand;
+  for (int u = 0; u < 4; ++u) wr[u] = Wr + (size_t)min(e0 + u, E - 1) * H;
+  float sum[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int c0 = wave * 1024 + lane * 4; c0 < H; c0 += 4096) {
+    float4 a[4], b[4][4];
+    float keep[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = c0 + 256 * i;
+      keep[i] = c < H ? 1.f : 0.f;
+      const int cc = c < H ? c : 0;
+      a[i] = *reinterpret_cast<const float4*>(xr + cc);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) b[u][i] = *reinterpret_cast<const float4*>(wr[u] + cc);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        sum[u] += keep[i] * (a[i].x * b[u][i].x + a[i].y * b[u][i].y + a[i].z * b[u][i].z + a[i].w * b[u][i].w);
   }
-  int n_gt = 0;
 #pragma unroll
-  for (int s = 0; s < kMaxSlots; ++s)
-    if (s < nslot) n_gt += __popcll(__ballot((s * 64 + lane) < E && key[s] > kth));
-  const int need = k - n_gt;  // how many of the keys equal to kth are admitted (lowest ids first)
-  int base = 0, ties_seen = 0;
+  for (int u = 0; u < 4; ++u) {
+    float v = sum[u];
 #pragma unroll
-  for (int s = 0; s < kMaxSlots; ++s) {
-    if (s < nslot) {
-      const bool valid = (s * 64 + lane) < E;
-      const bool eq = valid && key[s] == kth;
-      const uint64_t m_eq = __ballot(eq);
-      const int tie_rank = ties_seen + __popcll(m_eq & lt);
-      const bool sel = valid && (key[s] > kth || (eq && tie_rank < need));
-      const uint64_t m_sel = __ballot(sel);
-      const int pos = base + __popcll(m_sel & lt);
-      if (sel && active) {
-        s_key[wave][pos] = key[s];
-        s_id[wave][pos] = s * 64 + lane;
-        s_val[wave][pos] = val[s];
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    if (lane == 0) part[wave][u] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < 4 && e0 + threadIdx.x < E) {
+    const int u = threadIdx.x;
+    float v = ((part[0][u] + part[1][u]) + part[2][u]) + part[3][u];
+    if (bias) v += bias[e0 + u];
+    logits[(size_t)t * E + e0 + u] = v;
+  }
+}
+
+// Decode-sized batches: top-k and the whole stable grouping in ONE workgroup of 16 wavefronts (a
+// launch costs more than this work does).  Requires T*k <= 1024 and E <= 128.
+constexpr int kFusedMaxAssign = 1024;
+constexpr int kFusedMaxE = 128;
+__global__ __launch_bounds__(1024) void route_fused_kernel(const float* logits_in, int T, int E, int k, int S,
+                                                           float* logits_out,
+                                                           int32_t* __restrict__ ids, float* __restrict__ w,
+                                                           int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
+                                                           int32_t* __restrict__ inv_perm,
+                                                           int32_t* __restrict__ src_token) {
+  __shared__ uint32_t s_key[16][64];
+  __shared__ int s_id[16][64];
+  __shared__ float s_val[16][64];
+  __shared__ float s_sorted[16][64];
+  __shared__ int s_ids[kFusedMaxAssign];
+  __shared__ int s_chunk[16][kFusedMaxE];
+  __shared__ int s_off[kFusedMaxE + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nslot = (E + 63) / 64;
+  for (int t0 = 0; t0 < T; t0 += 16) {
+    const int t = t0 + wave;
+    const bool active = t < T;
+    float val[2] = {0.f, 0.f};
+    if (active) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+        if (s < nslot && s * 64 + lane < E) val[s] = logits_in[(size_t)t * E + s * 64 + lane];
+      if (logits_out && logits_out != logits_in) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+          if (s < nslot && s * 64 + lane < E) logits_out[(size_t)t * E + s * 64 + lane] = val[s];
       }
-      base += __popcll(m_sel);
-      ties_seen += __popcll(m_eq);
     }
+    const size_t o = active ? (size_t)t * k : 0;
+    wave_topk<2>(val, nslot, E, k, active, lane, s_key[wave], s_id[wave], s_val[wave], s_sorted[wave], ids + o, w + o,
+                 active ? s_ids + o : nullptr);
   }
+  // ---- stable grouping by expert: wavefront c ranks assignments 64c .. 64c+63 ----
+  const int A = T * k;
+  for (int i = tid; i < 16 * kFusedMaxE; i += 1024) (&s_chunk[0][0])[i] = 0;
   __syncthreads();
-  if (active && lane < k) {
-    const uint32_t mk = s_key[wave][lane];
-    const int mi = s_id[wave][lane];
-    int rank = 0;
-    for (int p = 0; p < k; ++p) {
-      const uint32_t ok = s_key[wave][p];
-      const int oi = s_id[wave][p];
-      rank += (ok > mk || (ok == mk && oi < mi)) ? 1 : 0;
+  const int a = tid;
+  const bool valid = a < A;
+  const int id = valid ? s_ids[a] : 0;
+  uint64_t mask = __ballot(valid);
+  for (int bit = 0; bit < 7; ++bit) {
+    const bool set = (id >> bit) & 1;
+    const uint64_t bal = __ballot(valid && set);
+    mask &= set ? bal : ~bal;
+  }
+  const int rank = __popcll(mask & lanemask_lt(lane));
+  if (valid && rank == 0) s_chunk[wave][id] = __popcll(mask);
+  __syncthreads();
+  if (tid < E) {
+    int tot = 0;
+    for (int c = 0; c < 16; ++c) {  // exclusive prefix over chunks, in place
+      const int v = s_chunk[c][tid];
+      s_chunk[c][tid] = tot;
+      tot += v;
     }
-    ids[(size_t)t * k + rank] = mi;
-    s_sorted[wave][rank] = s_val[wave][lane];
+    s_off[tid + 1] = tot;
   }
+  if (tid == 0) s_off[0] = 0;
   __syncthreads();
-  float ex = 0.f;
-  if (active && lane < k) ex = expf(s_sorted[wave][lane] - s_sorted[wave][0]);
-  float sum = ex;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-  if (active && lane < k) w[(size_t)t * k + lane] = ex / sum;
+  if (tid == 0)
+    for (int e = 0; e < E; ++e) s_off[e + 1] += s_off[e];
+  __syncthreads();
+  if (tid <= E) offsets[tid] = s_off[tid];
+  for (int s = tid; s < S; s += 1024) offsets[E + s + 1] = A + (s + 1) * T;
+  if (valid) {
+    const int pos = s_off[id] + s_chunk[wave][id] + rank;
+    perm[pos] = a;
+    inv_perm[a] = pos;
+    if (src_token) src_token[pos] = a / k;
+  }
+  if (src_token)
+    for (int i = tid; i < S * T; i += 1024) src_token[A + i] = i % T;
 }
 
 // pass 1: per-block histogram of expert ids
@@ -242,8 +383,21 @@ extern "C" cq_status cq_route_permute(const float* XR, const float* Wr, const fl
   const cq_gemm_f32_plan p = cq_gemm_f32_make_plan(T, E, H);
   const size_t part_bytes = cq_align_up((size_t)p.ksplit * T * E * sizeof(float), 256);
   cq_status st;
+  // decode-sized problems: a small logits kernel, then top-k + grouping fused in one workgroup
+  if ((long)T * top_k <= kFusedMaxAssign && E <= kFusedMaxE && (!XR || (long)T * E * H <= (1L << 22))) {
+    const float* lg = logits_in;
+    if (XR) {
+      float* dst = logits_out ? logits_out : (float*)workspace;
+      hipLaunchKernelGGL(logits_small_kernel, dim3((E + 3) / 4, T), dim3(256), 0, s, XR, Wr, bias, H, E, dst);
+      lg = dst;
+    }
+    hipLaunchKernelGGL(route_fused_kernel, dim3(1), dim3(1024), 0, s, lg, T, E, top_k, n_shared,
+                       XR ? (float*)nullptr : logits_out, topk_ids, topk_w, expert_offsets, perm, inv_perm,
+                       src_token);
+    return cq_check_launch();
+  }
   if (XR) {
-    st = cq_gemm_f32_launch(XR, Wr, 1, T, E, H, p, (float*)workspace, s);
+    st = cq_gemm_f32_launch(XR, Wr, 1, T, E, H, p, (float*)workspace, nullptr, 0, s);
     if (st != CQ_OK) return st;
     st = cq_topk_launch((const float*)workspace, p.ksplit, bias, T, E, top_k, logits_out, topk_ids, topk_w, s);
   } else {
