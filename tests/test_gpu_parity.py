@@ -13,6 +13,10 @@ from tests import helpers as Hp
 pytestmark = pytest.mark.gpu
 
 OUT_TOL = 2e-3   # relative L2 per token row (the bar the task states for layer outputs)
+# Routing weights: d(w)/w is about the absolute error of a logit difference.  Logits are computed in
+# fp32 (magnitudes up to ~64 with the Zipf bias: ulp 4e-6) over K <= 4096 terms, so a difference
+# carries up to ~1e-4 of absolute error; ids, which is what must be exact, are protected by the margin.
+W_RTOL = 3e-4
 
 
 def _say(msg):
@@ -101,7 +105,7 @@ def test_rotate_quant_identity_and_grid(B):
 # ---------------------------------------------------------------------------------------------
 def _check_routing(got, ref_ids, ref_w, ref_off, ref_perm, ref_inv, T, k, S):
     assert np.array_equal(got["ids"].cpu().numpy(), ref_ids)
-    assert np.allclose(got["w"].cpu().numpy(), ref_w, rtol=2e-5, atol=1e-7)
+    assert np.allclose(got["w"].cpu().numpy(), ref_w, rtol=W_RTOL, atol=1e-7)
     E = ref_off.size - 1
     off = got["offsets"].cpu().numpy()
     assert np.array_equal(off[:E + 1], ref_off)
@@ -277,7 +281,7 @@ def _check_layer(B, cfg, only_tokens=None, label=""):
     n_tie = Hp.check_codes(mid["Q"].cpu().numpy(), ref["q"], ref["XR"], ref["scale"])
     assert np.allclose(mid["scale"].cpu().numpy(), ref["scale"], rtol=1e-5)
     assert np.array_equal(mid["ids"].cpu().numpy(), ref["ids"])
-    assert np.allclose(mid["w"].cpu().numpy(), ref["w"], rtol=2e-5, atol=1e-7)
+    assert np.allclose(mid["w"].cpu().numpy(), ref["w"], rtol=W_RTOL, atol=1e-7)
     assert np.array_equal(mid["offsets"].cpu().numpy()[:cfg.E + 1], ref["offsets"])
     assert np.array_equal(mid["perm"].cpu().numpy(), ref["perm"])
     assert np.array_equal(mid["inv_perm"].cpu().numpy(), ref["inv_perm"])
@@ -315,3 +319,53 @@ def test_layer_without_prepack(B):
     layer = B.device_layer_from_inputs(L, use_prepacked=False)
     Y = B.cq_moe_forward(layer, _dev(L.X)).cpu().numpy()
     assert Hp.row_rel_l2(Y, ref["Y"]).max() <= OUT_TOL
+
+
+# ---------------------------------------------------------------------------------------------
+# full benchmark sizes, in the launch configuration bench.py times
+# ---------------------------------------------------------------------------------------------
+def _full_size(B, name, n_sample):
+    import torch
+    cfg = synth.CONFIGS[name]
+    _say(f"full size {name}: generating inputs")
+    L = Hp.make_inputs(cfg)
+    layer = B.device_layer_from_inputs(L)
+    Y = B.cq_moe_forward(layer, _dev(L.X))
+    torch.cuda.synchronize()
+    _say("  gpu done; oracle front end + sampled tokens")
+    rng = np.random.default_rng(7)
+    toks = np.sort(rng.choice(cfg.T, size=min(n_sample, cfg.T), replace=False))
+    ref = Hp.oracle_forward(L, only_tokens=toks)
+    mid = B.moe_intermediates(layer, cfg.T)
+    n_tie = Hp.check_codes(mid["Q"].cpu().numpy(), ref["q"], ref["XR"], ref["scale"])
+    assert np.array_equal(mid["ids"].cpu().numpy(), ref["ids"])
+    assert np.array_equal(mid["offsets"].cpu().numpy()[:cfg.E + 1], ref["offsets"])
+    assert np.array_equal(mid["perm"].cpu().numpy(), ref["perm"])
+    assert np.array_equal(mid["inv_perm"].cpu().numpy(), ref["inv_perm"])
+    assert np.allclose(mid["w"].cpu().numpy(), ref["w"], rtol=W_RTOL, atol=1e-7)
+    Yh = Y.cpu().numpy()
+    assert np.all(np.isfinite(Yh))
+    err = Hp.row_rel_l2(Yh[toks], ref["Y"][toks])
+    counts = np.diff(ref["offsets"])
+    _say(f"  {name}: redrawn={L.redrawn_rows} tie codes={n_tie} sampled rows={toks.size} "
+         f"max row rel L2={err.max():.3e} expert load min/mean/max={counts.min()}/{counts.mean():.1f}/{counts.max()}")
+    assert err.max() <= OUT_TOL
+    return counts
+
+
+def test_full_mixtral_decode(B):
+    _full_size(B, "mixtral_decode", 16)
+
+
+def test_full_dsv2lite(B):
+    _full_size(B, "dsv2lite", 48)
+
+
+def test_full_qwen3_zipf(B):
+    counts = _full_size(B, "qwen3_zipf", 48)
+    assert counts.max() > 8 * max(1.0, np.median(counts))     # the Zipf bias really skews the load
+
+
+def test_full_mixtral_prefill(B):
+    counts = _full_size(B, "mixtral_prefill", 24)
+    assert counts.max() <= 1.5 * counts.mean()                 # no bias: load within 1.5x of uniform
