@@ -49,7 +49,8 @@ typedef void* cq_stream; /* hipStream_t */
 /* kinds of the activation operand of cq_codebook_grouped_gemm */
 enum { CQ_A_INT8_CODES = 0, /* int8 container holding integer codes (|q| <= 127)          */
        CQ_A_F16 = 1,        /* IEEE half                                                    */
-       CQ_A_F32 = 2 };      /* float; rounded to half (RNE, saturating) when staged         */
+       CQ_A_F32 = 2,        /* float; rounded to half (RNE, saturating) when staged         */
+       CQ_A_BF16 = 3 };     /* bfloat16 bit patterns (e.g. integer codes stored as bf16)    */
 /* epilogues */
 enum { CQ_EPI_NONE = 0,     /* out[m, n] = scale[m] * sum_k W_c[n,k] a[m,k]                 */
        CQ_EPI_SWIGLU = 1 }; /* N = 2I rows interleaved (2i = gate i, 2i+1 = up i):
@@ -158,7 +159,7 @@ cq_status cq_combine(const float* O, const float* topk_w, const int32_t* inv_per
  */
 typedef struct {
   size_t total;
-  size_t XR, Q, scale, logits, topk_ids, topk_w, offsets, perm, inv_perm, src_token, Hbuf, Obuf, scratch;
+  size_t XR, Q, Q16, scale, logits, topk_ids, topk_w, offsets, perm, inv_perm, src_token, Hbuf, Obuf, scratch;
 } cq_moe_layout;
 size_t cq_moe_workspace_bytes(const cq_layer* L, int T);
 cq_status cq_moe_workspace_layout(const cq_layer* L, int T, cq_moe_layout* out);

@@ -15,7 +15,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libcq.so")
 
 CQ_OK = 0
-CQ_A_INT8_CODES, CQ_A_F16, CQ_A_F32 = 0, 1, 2
+CQ_A_INT8_CODES, CQ_A_F16, CQ_A_F32, CQ_A_BF16 = 0, 1, 2, 3
 CQ_EPI_NONE, CQ_EPI_SWIGLU = 0, 1
 CQ_OUT_F32, CQ_OUT_F16 = 0, 1
 
@@ -42,7 +42,7 @@ class Layer(ctypes.Structure):
 
 class MoeLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
-                ("total", "XR", "Q", "scale", "logits", "topk_ids", "topk_w", "offsets", "perm", "inv_perm",
+                ("total", "XR", "Q", "Q16", "scale", "logits", "topk_ids", "topk_w", "offsets", "perm", "inv_perm",
                  "src_token", "Hbuf", "Obuf", "scratch")]
 
 

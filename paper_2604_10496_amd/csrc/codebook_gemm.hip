@@ -30,6 +30,7 @@
 
 namespace {
 
+constexpr int kSmallMaxRows = 32;     // one token block: beyond this the large-tile kernel is better
 constexpr int kTableBytes = 65536;   // 256 entries x 64 row slots x 4 bytes
 constexpr int kSlabBytes = 65536;    // activation slab / reduction buffer
 #ifndef CQ_GEMM_WAVES
@@ -54,6 +55,7 @@ struct GemmArgs {
   void* out;
   int out_ld;
   int upw;                  // 64-row units per workgroup (consecutive, same expert)
+  int max_rows;             // groups with more rows are left to the large-tile kernel
 };
 
 __device__ __forceinline__ uint32_t f32_to_f16_bits_sat(float x) {
@@ -90,7 +92,7 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
 
 template <int AK, int EPI, int OUTK>
 __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmArgs p) {
-  constexpr bool F16 = (AK != CQ_A_INT8_CODES);
+  constexpr bool F16 = (AK == CQ_A_F16 || AK == CQ_A_F32);
   constexpr int NW = kWaves;
   constexpr int NT = 64 * NW;
   extern __shared__ uint4 smem[];
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   const int grp = blockIdx.y;
   const int m0 = p.group_offsets[grp];
   const int Me = p.group_offsets[grp + 1] - m0;
-  if (Me <= 0) return;
+  if (Me <= 0 || Me > p.max_rows) return;
   const int N = p.N, K = p.K;
   const int nUnits = N >> 6;
   const int u0 = blockIdx.x * p.upw;
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
               o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
             }
             v = make_uint4(o[0], o[1], o[2], o[3]);
-          } else if constexpr (AK == CQ_A_F16) {
+          } else if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
             v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0);
           } else {
             const float4 f0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0);
@@ -426,8 +428,6 @@ cq_status dispatch_epi(const GemmArgs& a, int G, int epilogue, int out_kind, hip
 cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                                   const int32_t* row_gather, const int32_t* group_offsets, int M_total,
                                   int epilogue, void* out, int out_kind, void* workspace, hipStream_t s) {
-  (void)workspace;
-  (void)M_total;
   GemmArgs a;
   a.idx = W->prepacked ? (const uint8_t*)W->prepacked : W->idx;
   a.cent = W->cent;
@@ -449,17 +449,25 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     if (upw > W->N / 64) upw = W->N / 64;
     a.upw = (int)upw;
   }
+  // Groups of up to 32 rows go to the streaming kernel above; larger ones to the large-tile kernel (when
+  // the row count allows its 256-row tiles), which runs off a device-built tile list.
+  const bool large = cq_gemm_large_supported(W) && M_total > kSmallMaxRows;
+  a.max_rows = large ? kSmallMaxRows : 0x7fffffff;
+  cq_status st;
   switch (a_kind) {
-    case CQ_A_INT8_CODES: return dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s);
-    case CQ_A_F16: return dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s);
-    default: return dispatch_epi<CQ_A_F32>(a, W->G, epilogue, out_kind, s);
+    case CQ_A_INT8_CODES: st = dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s); break;
+    case CQ_A_F16: st = dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s); break;
+    case CQ_A_BF16: st = dispatch_epi<CQ_A_BF16>(a, W->G, epilogue, out_kind, s); break;
+    default: st = dispatch_epi<CQ_A_F32>(a, W->G, epilogue, out_kind, s); break;
   }
+  if (st != CQ_OK || !large) return st;
+  return cq_gemm_large_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, kSmallMaxRows, epilogue,
+                              out, out_kind, workspace, s);
 }
 
 extern "C" size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, int M_total) {
-  (void)W;
-  (void)M_total;
-  return 0;
+  if (!W || W->G <= 0 || M_total <= kSmallMaxRows || !cq_gemm_large_supported(W)) return 0;
+  return cq_gemm_large_workspace_bytes(W->G, M_total);
 }
 
 extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, const void* A, int a_kind,
@@ -467,15 +475,19 @@ extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, cons
                                               const int32_t* group_offsets, int M_total, int epilogue, void* out,
                                               int out_kind, void* workspace, size_t workspace_bytes,
                                               cq_stream stream) {
-  (void)workspace_bytes;
   if (!W || !A || !group_offsets || !out) return CQ_ERR_NULL;
   if ((!W->idx && !W->prepacked) || !W->cent) return CQ_ERR_NULL;
   if (W->G <= 0 || W->N <= 0 || W->K <= 0 || M_total < 0) return CQ_ERR_SHAPE;
   if (W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;
-  if (a_kind != CQ_A_INT8_CODES && a_kind != CQ_A_F16 && a_kind != CQ_A_F32) return CQ_ERR_UNSUPPORTED;
+  if (a_kind != CQ_A_INT8_CODES && a_kind != CQ_A_F16 && a_kind != CQ_A_F32 && a_kind != CQ_A_BF16)
+    return CQ_ERR_UNSUPPORTED;
   if (epilogue != CQ_EPI_NONE && epilogue != CQ_EPI_SWIGLU) return CQ_ERR_UNSUPPORTED;
   if (out_kind != CQ_OUT_F32 && out_kind != CQ_OUT_F16) return CQ_ERR_UNSUPPORTED;
   if (M_total == 0) return CQ_OK;
+  {
+    const size_t need = cq_grouped_gemm_workspace_bytes(W, M_total);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CQ_ERR_WORKSPACE;
+  }
   return cq_gemm_codebook_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, epilogue, out,
                                  out_kind, workspace, (hipStream_t)stream);
 }

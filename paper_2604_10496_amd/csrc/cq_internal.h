@@ -35,8 +35,12 @@ cq_status cq_gemm_f32_launch(const float* A, const float* B, int b_transposed, i
                              hipStream_t s);
 
 cq_status cq_quantize_launch(const float* partials, int ksplit, int T, int H, int act_bits,
-                             float* XR_out, int8_t* Q_out, float* scale_out, uint32_t* amax_bits,
-                             hipStream_t s);
+                             float* XR_out, int8_t* Q_out, uint16_t* Q16_out, float* scale_out,
+                             uint32_t* amax_bits, hipStream_t s);
+// cq_rotate_quant with an optional second copy of the codes as bf16 bit patterns [T,H]
+cq_status cq_rotate_quant_ex(const float* X, const float* R, int T, int H, int act_bits, float* XR_out,
+                             int8_t* Q_out, uint16_t* Q16_out, float* scale_out, void* workspace,
+                             size_t workspace_bytes, cq_stream stream);
 
 cq_status cq_topk_launch(const float* logit_partials, int ksplit, const float* bias, int T, int E, int top_k,
                          float* logits_out, int32_t* topk_ids, float* topk_w, hipStream_t s);
@@ -49,5 +53,12 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
                                   const float* row_scale, const int32_t* row_gather,
                                   const int32_t* group_offsets, int M_total, int epilogue,
                                   void* out, int out_kind, void* workspace, hipStream_t s);
+
+// large-tile (prefill) path of the codebook product
+bool cq_gemm_large_supported(const cq_codebook_weights* W);
+size_t cq_gemm_large_workspace_bytes(int G, int M_total);
+cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
+                               const int32_t* row_gather, const int32_t* group_offsets, int M_total, int small_max,
+                               int epilogue, void* out, int out_kind, void* workspace, hipStream_t s);
 
 #endif  // CQ_INTERNAL_H_

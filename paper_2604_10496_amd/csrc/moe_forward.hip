@@ -18,6 +18,12 @@ cq_status validate_layer(const cq_layer* L, int T) {
   return CQ_OK;
 }
 
+// Batches large enough for the large-tile product get the codes a second time as bf16, so that staging
+// them into LDS is a plain copy.
+bool use_bf16_codes(const cq_layer* L, int T) {
+  return (long)T * (L->top_k + L->S) > 32 && cq_gemm_large_supported(&L->gate_up);
+}
+
 void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   const size_t M = (size_t)T * (L->top_k + L->S), A = (size_t)T * L->top_k;
   size_t off = 0;
@@ -28,6 +34,7 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   };
   o->XR = take((size_t)T * L->H * 4);
   o->Q = take((size_t)T * L->H);
+  o->Q16 = take(use_bf16_codes(L, T) ? (size_t)T * L->H * 2 : 0);
   o->scale = take((size_t)T * 4);
   o->logits = take((size_t)T * L->E * 4);
   o->topk_ids = take(A * 4);
@@ -97,14 +104,17 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
   auto mark = [&](int i) -> bool { return !ev || hipEventRecord(ev[i], hs) == hipSuccess; };
 
   if (!mark(0)) return CQ_ERR_HIP;
-  st = cq_rotate_quant(X, L->R, T, L->H, L->act_bits, XR, Q, scale, scratch, scratch_bytes, stream);
+  const bool bf16_codes = use_bf16_codes(L, T);
+  uint16_t* Q16 = bf16_codes ? (uint16_t*)(ws + lay.Q16) : nullptr;
+  st = cq_rotate_quant_ex(X, L->R, T, L->H, L->act_bits, XR, Q, Q16, scale, scratch, scratch_bytes, stream);
   if (st != CQ_OK) return st;
   if (!mark(1)) return CQ_ERR_HIP;
   st = cq_route_permute(XR, L->Wr, L->bias, nullptr, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets, perm,
                         inv_perm, src_token, scratch, scratch_bytes, stream);
   if (st != CQ_OK) return st;
   if (!mark(2)) return CQ_ERR_HIP;
-  st = cq_codebook_grouped_gemm(&L->gate_up, Q, CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU, Hbuf,
+  st = cq_codebook_grouped_gemm(&L->gate_up, bf16_codes ? (const void*)Q16 : (const void*)Q,
+                                bf16_codes ? CQ_A_BF16 : CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU, Hbuf,
                                 CQ_OUT_F16, scratch, scratch_bytes, stream);
   if (st != CQ_OK) return st;
   if (!mark(3)) return CQ_ERR_HIP;

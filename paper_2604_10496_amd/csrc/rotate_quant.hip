@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void reduce_amax_kernel(const float* part, int
 
 __global__ __launch_bounds__(256) void codes_kernel(const float* __restrict__ XR, const uint32_t* __restrict__ amax_bits,
                                                     int H, float qmax, int8_t* __restrict__ Q,
-                                                    float* __restrict__ scale) {
+                                                    uint16_t* __restrict__ Q16, float* __restrict__ scale) {
   const int t = blockIdx.y, tid = threadIdx.x;
   const int c = (blockIdx.x * 256 + tid) * 4;
   const float amax = __uint_as_float(amax_bits[t]);
@@ -169,6 +169,10 @@ __global__ __launch_bounds__(256) void codes_kernel(const float* __restrict__ XR
     const uint32_t packed = ((uint32_t)(int)r0 & 0xffu) | (((uint32_t)(int)r1 & 0xffu) << 8) |
                             (((uint32_t)(int)r2 & 0xffu) << 16) | (((uint32_t)(int)r3 & 0xffu) << 24);
     *reinterpret_cast<uint32_t*>(Q + (size_t)t * H + c) = packed;
+    if (Q16)  // the same codes as bf16 bit patterns (exact: small integers), ready to be an MFMA operand
+      *reinterpret_cast<uint2*>(Q16 + (size_t)t * H + c) =
+          make_uint2((__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xffff0000u),
+                     (__float_as_uint(r2) >> 16) | (__float_as_uint(r3) & 0xffff0000u));
   }
 }
 
@@ -176,7 +180,7 @@ __global__ __launch_bounds__(256) void codes_kernel(const float* __restrict__ XR
 // maximum, then round x / s to the nearest integer (ties to even, v_rndne_f32).
 __global__ __launch_bounds__(256) void quantize_kernel(const float* part, int ksplit, int in_place, int T, int H,
                                                        float qmax, float* XR, int8_t* __restrict__ Q,
-                                                       float* __restrict__ scale) {
+                                                       uint16_t* __restrict__ Q16, float* __restrict__ scale) {
   __shared__ float red[4];
   const int t = blockIdx.x;
   const int tid = threadIdx.x;
@@ -201,13 +205,17 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* part, int ks
   int8_t* q = Q + (size_t)t * H;
   for (int c = tid * 4; c < H; c += 256 * 4) {
     const float4 v = *reinterpret_cast<const float4*>(xr + c);  // this thread's own stores above
-    float r0 = fminf(fmaxf(rintf(v.x / s), -qmax), qmax);
+    const float r0 = fminf(fmaxf(rintf(v.x / s), -qmax), qmax);
     float r1 = fminf(fmaxf(rintf(v.y / s), -qmax), qmax);
     float r2 = fminf(fmaxf(rintf(v.z / s), -qmax), qmax);
     float r3 = fminf(fmaxf(rintf(v.w / s), -qmax), qmax);
     const uint32_t packed = ((uint32_t)(int)r0 & 0xffu) | (((uint32_t)(int)r1 & 0xffu) << 8) |
                             (((uint32_t)(int)r2 & 0xffu) << 16) | (((uint32_t)(int)r3 & 0xffu) << 24);
     *reinterpret_cast<uint32_t*>(q + c) = packed;
+    if (Q16)
+      *reinterpret_cast<uint2*>(Q16 + (size_t)t * H + c) =
+          make_uint2((__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xffff0000u),
+                     (__float_as_uint(r2) >> 16) | (__float_as_uint(r3) & 0xffff0000u));
   }
 }
 
@@ -255,7 +263,8 @@ cq_status cq_gemm_f32_launch(const float* A, const float* B, int b_transposed, i
 }
 
 cq_status cq_quantize_launch(const float* partials, int ksplit, int T, int H, int act_bits, float* XR_out,
-                             int8_t* Q_out, float* scale_out, uint32_t* amax_bits, hipStream_t s) {
+                             int8_t* Q_out, uint16_t* Q16_out, float* scale_out, uint32_t* amax_bits,
+                             hipStream_t s) {
   const float qmax = (float)((1 << (act_bits - 1)) - 1);
   const int in_place = (partials == XR_out && ksplit == 1) ? 1 : 0;
   if (amax_bits) {  // few tokens: spread every row over several workgroups (amax_bits was zeroed upstream)
@@ -263,10 +272,10 @@ cq_status cq_quantize_launch(const float* partials, int ksplit, int T, int H, in
     hipLaunchKernelGGL(reduce_amax_kernel, grid, dim3(256), 0, s, partials, ksplit, in_place, T, H, XR_out,
                        amax_bits);
     hipLaunchKernelGGL(codes_kernel, grid, dim3(256), 0, s, (const float*)XR_out, (const uint32_t*)amax_bits, H, qmax,
-                       Q_out, scale_out);
+                       Q_out, Q16_out, scale_out);
   } else {
     hipLaunchKernelGGL(quantize_kernel, dim3(T), dim3(256), 0, s, partials, ksplit, in_place, T, H, qmax, XR_out,
-                       Q_out, scale_out);
+                       Q_out, Q16_out, scale_out);
   }
   return cq_check_launch();
 }
@@ -282,9 +291,9 @@ extern "C" size_t cq_rotate_quant_workspace_bytes(int T, int H) {
   return amax_bytes(T) + (p.ksplit > 1 ? cq_align_up((size_t)p.ksplit * T * H * sizeof(float), 256) : 0);
 }
 
-extern "C" cq_status cq_rotate_quant(const float* X, const float* R, int T, int H, int act_bits, float* XR_out,
-                                     int8_t* Q_out, float* scale_out, void* workspace, size_t workspace_bytes,
-                                     cq_stream stream) {
+cq_status cq_rotate_quant_ex(const float* X, const float* R, int T, int H, int act_bits, float* XR_out,
+                             int8_t* Q_out, uint16_t* Q16_out, float* scale_out, void* workspace,
+                             size_t workspace_bytes, cq_stream stream) {
   if (!X || !R || !XR_out || !Q_out || !scale_out) return CQ_ERR_NULL;
   if (T <= 0 || H <= 0 || H % 64 != 0) return CQ_ERR_SHAPE;
   if (act_bits != 4 && act_bits != 8) return CQ_ERR_UNSUPPORTED;
@@ -297,5 +306,12 @@ extern "C" cq_status cq_rotate_quant(const float* X, const float* R, int T, int 
   float* dst = p.ksplit > 1 ? part : XR_out;
   cq_status st = cq_gemm_f32_launch(X, R, 0, T, H, H, p, dst, amax, T, s);
   if (st != CQ_OK) return st;
-  return cq_quantize_launch(dst, p.ksplit, T, H, act_bits, XR_out, Q_out, scale_out, amax, s);
+  return cq_quantize_launch(dst, p.ksplit, T, H, act_bits, XR_out, Q_out, Q16_out, scale_out, amax, s);
+}
+
+extern "C" cq_status cq_rotate_quant(const float* X, const float* R, int T, int H, int act_bits, float* XR_out,
+                                     int8_t* Q_out, float* scale_out, void* workspace, size_t workspace_bytes,
+                                     cq_stream stream) {
+  return cq_rotate_quant_ex(X, R, T, H, act_bits, XR_out, Q_out, nullptr, scale_out, workspace, workspace_bytes,
+                            stream);
 }

@@ -166,7 +166,11 @@ def _rand_weights(rng, G, N, K, cent=None):
 
 @pytest.mark.parametrize("prepacked", [True, False])
 @pytest.mark.parametrize("N,K,counts", [(64, 64, [1]), (128, 256, [3, 0, 32, 33]), (192, 1408, [7, 70, 0, 1]),
-                                        (64, 4096, [16, 5])])
+                                        (64, 4096, [16, 5]),
+                                        # 256-row matrices with K % 128 == 0: groups above 32 rows take the
+                                        # large-tile kernel (tiles of 256 and 128 tokens, ragged tails)
+                                        (256, 128, [33]), (512, 384, [40, 0, 300, 7, 129, 128, 257]),
+                                        (256, 1408, [600, 31, 32, 33])])
 def test_gemm_integer_centroids_exact(B, N, K, counts, prepacked):
     """Centroids k-8 and integer codes: every partial sum is an integer below 2^24, so the result must
     equal the exact integer product whatever the summation order."""
@@ -209,11 +213,11 @@ def test_gemm_rank_one_and_gather_scale(B):
         assert np.allclose(out[m], ref, rtol=1e-6, atol=1e-6)
 
 
-@pytest.mark.parametrize("a_kind", ["f16", "f32"])
-def test_gemm_float_rows_against_oracle(B, a_kind):
+@pytest.mark.parametrize("N,counts", [(128, [5, 40, 0]), (256, [5, 140, 50])])
+@pytest.mark.parametrize("a_kind", ["f16", "f32", "bf16"])
+def test_gemm_float_rows_against_oracle(B, a_kind, N, counts):
     rng = np.random.default_rng(31)
-    G, N, K = 3, 128, 768
-    counts = [5, 40, 0]
+    G, K = 3, 768
     M = sum(counts)
     idx, cent = _rand_weights(rng, G, N, K)
     A = (rng.standard_normal((M, K)) * 3).astype(np.float32)
@@ -223,6 +227,11 @@ def test_gemm_float_rows_against_oracle(B, a_kind):
     if a_kind == "f16":
         out = B.cq_codebook_grouped_gemm(W, _dev(A16), B.CQ_A_F16, None, None, _dev(off), M, B.CQ_EPI_NONE,
                                          B.CQ_OUT_F32)
+    elif a_kind == "bf16":
+        Ab = synth.f32_to_bf16_bits(A)
+        A16 = synth.bf16_bits_to_f32(Ab)          # the rounded values the oracle multiplies
+        out = B.cq_codebook_grouped_gemm(W, _dev(Ab.view(np.int16)), B.CQ_A_BF16, None, None, _dev(off), M,
+                                         B.CQ_EPI_NONE, B.CQ_OUT_F32)
     else:
         out = B.cq_codebook_grouped_gemm(W, _dev(A), B.CQ_A_F32, None, None, _dev(off), M, B.CQ_EPI_NONE,
                                          B.CQ_OUT_F32)
@@ -235,11 +244,11 @@ def test_gemm_float_rows_against_oracle(B, a_kind):
         assert Hp.row_rel_l2(out[rows], ref).max() < 2e-5
 
 
+@pytest.mark.parametrize("I,counts", [(96, [33, 6]), (256, [33, 6, 200])])
 @pytest.mark.parametrize("out_kind", ["f16", "f32"])
-def test_gemm_swiglu_epilogue(B, out_kind):
+def test_gemm_swiglu_epilogue(B, out_kind, I, counts):
     rng = np.random.default_rng(41)
-    G, I, K = 2, 96, 256
-    counts = [33, 6]
+    G, K = len(counts), 256
     M = sum(counts)
     gate = [(rng.integers(0, 256, size=(I, K // 2), dtype=np.uint8), synth.draw_centroids(rng, I)) for _ in range(G)]
     up = [(rng.integers(0, 256, size=(I, K // 2), dtype=np.uint8), synth.draw_centroids(rng, I)) for _ in range(G)]
