@@ -467,7 +467,7 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
 
 extern "C" size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, int M_total) {
   if (!W || W->G <= 0 || M_total <= kSmallMaxRows || !cq_gemm_large_supported(W)) return 0;
-  return cq_gemm_large_workspace_bytes(W->G, M_total);
+  return cq_gemm_large_workspace_bytes(W->G, M_total, W->K, true);  // worst case over the operand kinds
 }
 
 extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, const void* A, int a_kind,

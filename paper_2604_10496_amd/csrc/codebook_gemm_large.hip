@@ -8,29 +8,40 @@
 //     centroid tables it needs are loop invariant and live in registers.  Decoding is pure vector ALU:
 //     nibbles become byte selectors, v_perm_b32 picks the low and the high bytes of the centroids out
 //     of register-resident byte tables (two 8-entry halves merged by bit 3 of the index), two more
-//     perm levels interleave them into bf16/f16 pairs.  About 4 ALU operations per weight, against
-//     CT multiply-adds per weight on the matrix cores;
-//   * LDS holds only the activation tile (double buffered, fragment order, conflict-free 16-byte reads)
-//     and is read once per wavefront per K step: about 60 % of its bandwidth at full MFMA rate.
-// Token tiles come from a device-built work list (groups are ragged and their sizes are only known on
-// the device); the list index is remapped so that tiles sharing weights run on the same XCD (L2).
+//     perm levels interleave them into bf16/f16 pairs.  About 2.3 ALU operations per MFMA, which the
+//     matrix pipe hides completely (measured);
+//   * LDS holds only the activation tiles.  They arrive by direct global->LDS loads (no staging
+//     registers, no ds_write), four tiles deep, and each wavefront reads a tile once per K step.
+// The activation operand is 16-bit (bf16 integer codes or f16 rows); other kinds are converted by a
+// small pre-pass.  Token tiles come from a device-built work list (groups are ragged and their sizes
+// are only known on the device); the list index is remapped so that tiles sharing activations run on
+// the same XCD (L2).
 #include <type_traits>
 
 #include "cq_internal.h"
+
+#ifndef CQ_PROBE
+#define CQ_PROBE 0
+#endif
+
+void cq_large_tile_caps(int G, int M_total, int* cap256, int* cap128);
 
 namespace {
 
 constexpr int kLargeRows = 256;  // weight rows per workgroup
 constexpr int kStepK = 64;       // K per pipeline step
+constexpr int kStepBytes = kStepK * 2;  // one token's share of a step in LDS and in global memory
+constexpr int kNBuf = 4;         // activation tiles in LDS
 
 struct LargeArgs {
   const uint8_t* idx;
   const uint16_t* cent;
   int prepacked;
   int N, K;
-  const void* A;
+  const uint16_t* A;           // [rows, K] bf16 or f16
+  const int32_t* a_gather;     // sorted row -> row of A, or NULL
   const float* row_scale;
-  const int32_t* row_gather;
+  const int32_t* scale_gather; // sorted row -> entry of row_scale, or NULL
   void* out;
   int out_ld;
   const int32_t* tiles;   // [cap][4]: group, first row (absolute sorted row), row count, unused
@@ -75,6 +86,9 @@ __device__ __forceinline__ RowTable make_row_table(const uint16_t* crow) {
 
 // 8 packed indices (one dword, weight 2i in the low nibble of byte i) -> 4 dwords of 16-bit pairs
 __device__ __forceinline__ cq_v4u decode8(uint32_t d, const RowTable& t) {
+#if CQ_PROBE & 2
+  return cq_v4u{d, d ^ t.lo[0], d ^ t.hi[1], d ^ t.lo[2]};
+#endif
   const uint32_t sA = d & 0x07070707u;                 // even weights: selector within a half table
   const uint32_t sB = (d >> 4) & 0x07070707u;          // odd weights
   const uint32_t mA = ((d >> 3) & 0x01010101u) * 0xffu;  // 0xff where bit 3 of the index is set
@@ -106,14 +120,46 @@ __device__ __forceinline__ cq_v16f mfma_large(const cq_v4u a, const cq_v4u b, cq
                                                    __builtin_bit_cast(cq_v8bf16, b), c, 0, 0, 0);
 }
 
-// AK: activation kind; C = CT/32 token blocks per workgroup (8 or 4)
-template <int AK, int EPI, int OUTK, int C>
+// ---- memory operations the compiler must not track -------------------------------------------------
+// The pipeline keeps loads in flight across several K steps.  The compiler's own wait insertion would
+// drain them (it treats an LDS read after a direct-to-LDS load as dependent on it), so the loop's
+// global loads are issued from inline assembly and waited for by explicit vmcnt counts.  The kernel has
+// no static LDS (verified by the launcher): dynamic LDS starts at address 0 and byte offsets are LDS
+// addresses.
+
+// 16 bytes per lane from global memory into the registers `dst`; valid only after a vm_wait that
+// names `dst`
+__device__ __forceinline__ void load_global_async(cq_v4u& dst, const uint8_t* src) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(src) : "memory");
+}
+// (m0 is a reserved register: the compiler loads it right before each use of its own and does not
+// keep values in it, which is what clobbering it here relies on)
+#pragma clang diagnostic ignored "-Winline-asm"
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base uniform)
+__device__ __forceinline__ void load_global_to_lds(uint32_t lds_base, const uint8_t* src) {
+#if !(CQ_PROBE & 1)
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory", "m0");
+#endif
+}
+// wait until at most N of this wavefront's vector-memory loads are outstanding; the registers passed
+// through become usable only after it
+template <int N>
+__device__ __forceinline__ void vm_wait(cq_v4u& a, cq_v4u& b) {
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void vm_wait(cq_v4u& a, cq_v4u& b, cq_v4u& c, cq_v4u& d) {
+  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
+}
+__device__ __forceinline__ cq_v4u lds_read_u128(uint32_t byte_offset) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) cq_v4u*>((uintptr_t)byte_offset);
+}
+
+// F16: the activations are f16 (else bf16); C = CT/32 token blocks per workgroup (8 or 4)
+template <bool F16, int EPI, int OUTK, int C>
 __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
-  constexpr bool F16 = (AK == CQ_A_F16 || AK == CQ_A_F32);
   constexpr int CT = 32 * C;
-  constexpr int TPT = 256 / CT;          // threads per token when staging
-  constexpr int CPT = 8 / TPT;           // 16-byte chunks (8 k) per thread per step
-  extern __shared__ uint4 smem[];        // two activation tiles of [8 chunks][CT tokens] x 16 bytes
+  constexpr uint32_t kBufBytes = CT * kStepBytes;  // one activation tile: CT tokens x 128 bytes
 
   // ---- which tile: XCD-aware remap of the linear workgroup id (ids go round-robin over 8 XCDs) ----
   // XCD x takes the contiguous share [x*per_xcd, (x+1)*per_xcd) of the real work items (the grid is
@@ -134,15 +180,15 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   const size_t rowbytes = (size_t)K >> 1;
   const int n0 = rt * kLargeRows + wave * 64;  // this wavefront's 64 rows
   const uint8_t* wbase = p.idx + ((size_t)grp * N + n0) * rowbytes;
-  size_t lane_off0, lane_off1;
+  const uint8_t *wp0, *wp1;  // this lane's 16 bytes of step 0, for each of its two rows
   int sstride;
   if (p.prepacked) {
-    lane_off0 = (size_t)lane * 16;
-    lane_off1 = 32 * rowbytes + (size_t)lane * 16;
+    wp0 = wbase + (size_t)lane * 16;
+    wp1 = wbase + 32 * rowbytes + (size_t)lane * 16;
     sstride = 1024;
   } else {
-    lane_off0 = (size_t)r32 * rowbytes + g2 * 16;
-    lane_off1 = (size_t)(32 + r32) * rowbytes + g2 * 16;
+    wp0 = wbase + (size_t)r32 * rowbytes + g2 * 16;
+    wp1 = wbase + (size_t)(32 + r32) * rowbytes + g2 * 16;
     sstride = 32;
   }
   const int nS = K / kStepK;
@@ -151,58 +197,44 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   const RowTable t0 = make_row_table<F16>(cbase + (size_t)r32 * CQ_N_CENTROIDS);
   const RowTable t1 = make_row_table<F16>(cbase + (size_t)(32 + r32) * CQ_N_CENTROIDS);
 
-  // ---- activation staging: thread -> (token, part of the 64-wide K step) ----
-  const int stok = tid % CT, spart = tid / CT;
-  const bool svalid = stok < mcnt;
-  size_t srow = 0;
-  if (svalid) {
-    const int m = mrow0 + stok;
-    srow = (p.row_gather ? (size_t)p.row_gather[m] : (size_t)m) * K;
+  // ---- activation tiles ----
+  // LDS tile: token-major, 128 bytes (8 chunks of 8 k) per token; chunk c of token t sits at position
+  // c ^ ((t >> 1) & 7) of the token's row.  With that swizzle the 16 lanes of one phase of a fragment
+  // read (16 consecutive tokens, same chunk) hit 16 different 16-byte bank groups.
+  // Transfer: one direct-to-LDS load moves 8 tokens x 128 bytes (8 lanes per token: whole contiguous
+  // row segments on the global side, 1 KiB contiguous in LDS).  The swizzle is applied on the global
+  // side: lane (token, position) fetches chunk position ^ ((token >> 1) & 7).  Wavefront w moves
+  // tokens [w*CT/4, (w+1)*CT/4) of every step: C loads.
+  // Tokens past the end of the tile load the tile's last row instead (no branches in the pipeline);
+  // a token is one output column, and those columns are never stored.
+  const uint8_t* ap[C];
+#pragma unroll
+  for (int i = 0; i < C; ++i) {
+    const int tok = wave * (CT / 4) + i * 8 + (lane >> 3);
+    const int m = mrow0 + min(tok, mcnt - 1);
+    const size_t row = (size_t)(p.a_gather ? p.a_gather[m] : m);
+    const int chunk = (lane & 7) ^ ((tok >> 1) & 7);
+    ap[i] = reinterpret_cast<const uint8_t*>(p.A) + (row * (size_t)K + chunk * 8) * 2;
   }
-  uint4 sreg[CPT];
-  auto stage_load = [&](int s) {
-    const size_t e0 = srow + (size_t)s * kStepK + spart * (CPT * 8);
+  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(wave * (CT / 4) * kStepBytes);
+  auto fetch_tile = [&](int s, int buf) {  // activations of step s into tile `buf`
+    const size_t o = (size_t)s * kStepBytes;
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (svalid) {
-        if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
-          v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0 + c * 8);
-        } else if constexpr (AK == CQ_A_INT8_CODES) {
-          const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0 + c * 8);
-          v.x = raw.x;
-          v.y = raw.y;
-        } else {
-          const float4 f0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0 + c * 8);
-          const float4 f1 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0 + c * 8 + 4);
-          v.x = f32_to_f16_sat(f0.x) | (f32_to_f16_sat(f0.y) << 16);
-          v.y = f32_to_f16_sat(f0.z) | (f32_to_f16_sat(f0.w) << 16);
-          v.z = f32_to_f16_sat(f1.x) | (f32_to_f16_sat(f1.y) << 16);
-          v.w = f32_to_f16_sat(f1.z) | (f32_to_f16_sat(f1.w) << 16);
-        }
-      }
-      sreg[c] = v;
-    }
+    for (int i = 0; i < C; ++i) load_global_to_lds(buf * kBufBytes + lds_wave + i * 1024, ap[i] + o);
   };
-  auto stage_store = [&](int buf) {
-    uint4* dst = smem + buf * (8 * CT);
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      uint4 v = sreg[c];
-      if constexpr (AK == CQ_A_INT8_CODES) {
-        const uint32_t rw[2] = {v.x, v.y};
-        uint32_t o[4];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
-          const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
-          o[2 * h] = code_bf16(b0) | (code_bf16(b1) << 16);
-          o[2 * h + 1] = code_bf16(b2) | (code_bf16(b3) << 16);
-        }
-        v = make_uint4(o[0], o[1], o[2], o[3]);
-      }
-      dst[(spart * CPT + c) * CT + stok] = v;
-    }
+  auto fetch_weights = [&](cq_v4u (&w)[2], int s) {
+    const size_t o = (size_t)s * sstride;
+#if !(CQ_PROBE & 8)
+    load_global_async(w[0], wp0 + o);
+    load_global_async(w[1], wp1 + o);
+#else
+    w[0][0] += (uint32_t)o;
+#endif
+  };
+  // fragment read: lane (token r32 of block cb, k group g2) wants chunk g2*4 + jj of sub-step jj
+  const uint32_t boff = (uint32_t)r32 * kStepBytes + ((uint32_t)((g2 * 4) ^ ((r32 >> 1) & 7)) << 4);
+  auto read_b = [&](int buf, int jj, int cb) {
+    return lds_read_u128((boff ^ ((uint32_t)jj << 4)) + buf * kBufBytes + cb * 32 * kStepBytes);
   };
 
   cq_v16f acc[2][C];
@@ -213,56 +245,76 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
 
-  // prologue: activations of step 0 into buffer 0, weights of steps 0 and 1 into registers
-  stage_load(0);
-  uint4 wq[2][2];
-  wq[0][0] = *reinterpret_cast<const uint4*>(wbase + lane_off0);
-  wq[0][1] = *reinterpret_cast<const uint4*>(wbase + lane_off1);
-  {
-    const size_t o1 = (size_t)min(1, nS - 1) * sstride;
-    wq[1][0] = *reinterpret_cast<const uint4*>(wbase + lane_off0 + o1);
-    wq[1][1] = *reinterpret_cast<const uint4*>(wbase + lane_off1 + o1);
-  }
-  stage_store(0);
+  // Pipeline: at the start of step s the weights and the activation tile of step s+3 are requested
+  // (weights: ring of four register pairs; tiles: ring of four LDS buffers, tile s in buffer s%4).
+  // At the end of step s every wavefront waits for its own share of tile s+2 (the C+2 loads requested
+  // during step s may stay in flight), then the workgroup barrier publishes it; the last sub-step of
+  // step s+1 already reads from it.  The barrier also retires tile s, which the requests of step s+1
+  // overwrite.  Loads thus have two full steps (about 2 us) to arrive.
+  // vector-memory loads a wavefront issues per step: the wait counts below depend on it
+  constexpr int kPerStep = ((CQ_PROBE & 1) ? 0 : C) + ((CQ_PROBE & 8) ? 0 : 2);
+  cq_v4u wq[kNBuf][2];
+  fetch_weights(wq[0], 0);
+  fetch_tile(0, 0);
+  fetch_weights(wq[1], min(1, nS - 1));
+  fetch_tile(min(1, nS - 1), 1);
+  fetch_weights(wq[2], min(2, nS - 1));
+  fetch_tile(min(2, nS - 1), 2);
+  vm_wait<kPerStep>(wq[0][0], wq[0][1], wq[1][0], wq[1][1]);
   __syncthreads();
 
-  for (int s0 = 0; s0 < nS; s0 += 2) {
+  // Software pipeline over the 16-wide K sub-steps.  While the matrix cores work through the 2*C MFMAs
+  // of one sub-step, the vector ALU decodes the A fragments of the next one and LDS delivers its B
+  // fragments (a wavefront issues in order, so the pipes only overlap if their instructions alternate;
+  // the group barriers below ask the scheduler for exactly that).
+  // The B fragments live in one register set: as soon as the two MFMAs of a token block are issued,
+  // its registers take the block's fragment of the next sub-step (a full sub-step of slack).
+  cq_v4u af[2][2];
+  cq_v4u bfr[C];
+  af[0][0] = decode8(wq[0][0][0], t0);
+  af[0][1] = decode8(wq[0][1][0], t1);
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      const int s = s0 + par;  // K is a multiple of 128 on this path: both halves always exist
-      {
-        // next step's activations and the weights two steps ahead start their trip now
-        stage_load(min(s + 1, nS - 1));
-        const uint4 w0 = wq[par][0], w1 = wq[par][1];
-        {
-          const size_t o2 = (size_t)min(s + 2, nS - 1) * sstride;
-          wq[par][0] = *reinterpret_cast<const uint4*>(wbase + lane_off0 + o2);
-          wq[par][1] = *reinterpret_cast<const uint4*>(wbase + lane_off1 + o2);
+  for (int cb = 0; cb < C; ++cb) bfr[cb] = read_b(0, 0, cb);
+
+  int s0 = 0;
+  do {  // at least two steps exist (no zero-trip path: the accumulators stay in their AGPRs throughout)
+#pragma unroll
+    for (int par = 0; par < 4; ++par) {  // step s0 + par uses weights wq[par] and tile buffer par
+      if (par == 2 && s0 + 2 >= nS) break;  // K is a multiple of 128: steps come in pairs
+      const int s3 = min(s0 + par + 3, nS - 1);
+      fetch_weights(wq[(par + 3) & 3], s3);
+      fetch_tile(s3, (par + 3) & 3);
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int cur = jj & 1, nxt = cur ^ 1;
+        // next sub-step: jj + 1 of this step, or the first one of the next step
+        const int nbuf = jj < 3 ? par : (par + 1) & 3, njj = (jj + 1) & 3;
+        af[nxt][0] = decode8(wq[nbuf][0][njj], t0);
+        af[nxt][1] = decode8(wq[nbuf][1][njj], t1);
+#pragma unroll
+        for (int cb = 0; cb < C; ++cb) {
+          const cq_v4u b = bfr[cb];
+          acc[0][cb] = mfma_large<F16>(af[cur][0], b, acc[0][cb]);
+          acc[1][cb] = mfma_large<F16>(af[cur][1], b, acc[1][cb]);
+#if !(CQ_PROBE & 4)
+          bfr[cb] = read_b(nbuf, njj, cb);
+#endif
         }
-        const uint4* bt = smem + par * (8 * CT);
-        const uint32_t wd0[4] = {w0.x, w0.y, w0.z, w0.w};
-        const uint32_t wd1[4] = {w1.x, w1.y, w1.z, w1.w};
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const cq_v4u a0 = decode8(wd0[jj], t0);
-          const cq_v4u a1 = decode8(wd1[jj], t1);
-          const uint4* brow = bt + (g2 * 4 + jj) * CT + r32;
-#pragma unroll
-          for (int cb = 0; cb < C; ++cb) {
-            const uint4 bq = brow[cb * 32];
-            const cq_v4u b = {bq.x, bq.y, bq.z, bq.w};
-            acc[0][cb] = mfma_large<F16>(a0, b, acc[0][cb]);
-            acc[1][cb] = mfma_large<F16>(a1, b, acc[1][cb]);
-          }
-          // keep the four sub-steps apart: hoisting all decodes and fragment reads to the top would
-          // cost more registers than the accumulators leave
-          __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < 2 * C; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // one MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);                   // four vector ALU operations
+          if (i % 2 == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
         }
-        stage_store(par ^ 1);
-        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
       }
+      vm_wait<kPerStep>(wq[(par + 2) & 3][0], wq[(par + 2) & 3][1]);
+      __syncthreads();
     }
-  }
+    s0 += 4;
+  } while (s0 < nS);
+  // nothing of this workgroup may still be on its way into LDS when the workgroup ends
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- epilogue: per-token scale, optional SiLU(gate)*up, store ----
 #pragma unroll
@@ -271,7 +323,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (tok < mcnt) {
       const int m = mrow0 + tok;
       float sc = 1.f;
-      if (p.row_scale) sc = p.row_scale[p.row_gather ? p.row_gather[m] : m];
+      if (p.row_scale) sc = p.row_scale[p.scale_gather ? p.scale_gather[m] : m];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
 #pragma unroll
@@ -302,6 +354,38 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
       }
     }
   }
+}
+
+// Pre-pass for activation kinds the main kernel does not read: sorted row m of the result is row
+// src(m) of A as bf16 (exact for integer codes) or f16 (saturating, from fp32).  8 values per thread.
+template <int AK>
+__global__ __launch_bounds__(256) void convert_rows_kernel(const void* __restrict__ A, const int32_t* __restrict__ gather,
+                                                           int M, int K, uint16_t* __restrict__ out) {
+  const int cpr = K >> 3;  // 8-value chunks per row
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)M * cpr) return;
+  const int m = (int)(i / cpr), c = (int)(i - (size_t)m * cpr);
+  const size_t src = (size_t)(gather ? gather[m] : m) * K + (size_t)c * 8;
+  uint32_t o[4];
+  if constexpr (AK == CQ_A_INT8_CODES) {
+    const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(A) + src);
+    const uint32_t rw[2] = {raw.x, raw.y};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
+      const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
+      o[2 * h] = code_bf16(b0) | (code_bf16(b1) << 16);
+      o[2 * h + 1] = code_bf16(b2) | (code_bf16(b3) << 16);
+    }
+  } else {
+    const float4 f0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(A) + src);
+    const float4 f1 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(A) + src + 4);
+    o[0] = f32_to_f16_sat(f0.x) | (f32_to_f16_sat(f0.y) << 16);
+    o[1] = f32_to_f16_sat(f0.z) | (f32_to_f16_sat(f0.w) << 16);
+    o[2] = f32_to_f16_sat(f1.x) | (f32_to_f16_sat(f1.y) << 16);
+    o[3] = f32_to_f16_sat(f1.z) | (f32_to_f16_sat(f1.w) << 16);
+  }
+  *reinterpret_cast<uint4*>(out + (size_t)m * K + (size_t)c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
 // One workgroup: cut every group with more than `small_max` rows into token tiles of 256 (while more
@@ -360,12 +444,15 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
   if (tid == 0) { counts[0] = base256; counts[1] = base128; }
 }
 
-template <int AK, int EPI, int OUTK, int C>
+template <bool F16, int EPI, int OUTK, int C>
 cq_status launch_large(const LargeArgs& a, int max_tiles, hipStream_t s) {
-  auto kern = gemm_large_kernel<AK, EPI, OUTK, C>;
-  constexpr int lds = 2 * 8 * (32 * C) * 16;
+  auto kern = gemm_large_kernel<F16, EPI, OUTK, C>;
+  constexpr int lds = kNBuf * 32 * C * kStepBytes;
   static bool configured = false;
   if (!configured) {
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
+    if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
         hipSuccess)
       return CQ_ERR_HIP;
@@ -377,26 +464,32 @@ cq_status launch_large(const LargeArgs& a, int max_tiles, hipStream_t s) {
   return cq_check_launch();
 }
 
-template <int AK, int EPI, int OUTK>
+template <bool F16, int EPI, int OUTK>
 cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, const int32_t* counts, int max256,
                       int max128, hipStream_t s) {
   a.tiles = t256;
   a.n_tiles = counts;
-  cq_status st = launch_large<AK, EPI, OUTK, 8>(a, max256, s);
+  cq_status st = launch_large<F16, EPI, OUTK, 8>(a, max256, s);
   if (st != CQ_OK) return st;
   a.tiles = t128;
   a.n_tiles = counts + 1;
-  return launch_large<AK, EPI, OUTK, 4>(a, max128, s);
+  return launch_large<F16, EPI, OUTK, 4>(a, max128, s);
 }
 
-template <int AK>
+template <bool F16>
 cq_status dispatch_large(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
                          const int32_t* counts, int max256, int max128, hipStream_t s) {
   if (epilogue == CQ_EPI_SWIGLU)
-    return out_kind == CQ_OUT_F16 ? launch_both<AK, CQ_EPI_SWIGLU, CQ_OUT_F16>(a, t256, t128, counts, max256, max128, s)
-                                  : launch_both<AK, CQ_EPI_SWIGLU, CQ_OUT_F32>(a, t256, t128, counts, max256, max128, s);
-  return out_kind == CQ_OUT_F16 ? launch_both<AK, CQ_EPI_NONE, CQ_OUT_F16>(a, t256, t128, counts, max256, max128, s)
-                                : launch_both<AK, CQ_EPI_NONE, CQ_OUT_F32>(a, t256, t128, counts, max256, max128, s);
+    return out_kind == CQ_OUT_F16 ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16>(a, t256, t128, counts, max256, max128, s)
+                                  : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32>(a, t256, t128, counts, max256, max128, s);
+  return out_kind == CQ_OUT_F16 ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16>(a, t256, t128, counts, max256, max128, s)
+                                : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32>(a, t256, t128, counts, max256, max128, s);
+}
+
+size_t tile_list_bytes(int G, int M_total) {
+  int c256, c128;
+  cq_large_tile_caps(G, M_total, &c256, &c128);
+  return cq_align_up(256 + (size_t)(c256 + c128) * 4 * sizeof(int32_t), 256);
 }
 
 }  // namespace
@@ -408,10 +501,11 @@ void cq_large_tile_caps(int G, int M_total, int* cap256, int* cap128) {
   if (*cap128 < 1) *cap128 = 1;
 }
 
-size_t cq_gemm_large_workspace_bytes(int G, int M_total) {
-  int c256, c128;
-  cq_large_tile_caps(G, M_total, &c256, &c128);
-  return cq_align_up(256 + (size_t)(c256 + c128) * 4 * sizeof(int32_t), 256);
+// tile lists, plus (with_conversion) room for the activations as 16-bit rows [M_total, K]
+size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion) {
+  size_t n = tile_list_bytes(G, M_total);
+  if (with_conversion) n += cq_align_up((size_t)M_total * K * sizeof(uint16_t), 256);
+  return n;
 }
 
 bool cq_gemm_large_supported(const cq_codebook_weights* W) {
@@ -433,19 +527,30 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
   a.prepacked = W->prepacked ? 1 : 0;
   a.N = W->N;
   a.K = W->K;
-  a.A = A;
+  a.A = (const uint16_t*)A;
+  a.a_gather = row_gather;
   a.row_scale = row_scale;
-  a.row_gather = row_gather;
+  a.scale_gather = row_gather;
   a.out = out;
   a.out_ld = epilogue == CQ_EPI_SWIGLU ? W->N / 2 : W->N;
   a.tiles = nullptr;
   a.n_tiles = nullptr;
   a.row_tiles = W->N / kLargeRows;
-  switch (a_kind) {
-    case CQ_A_INT8_CODES:
-      return dispatch_large<CQ_A_INT8_CODES>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, s);
-    case CQ_A_F16: return dispatch_large<CQ_A_F16>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, s);
-    case CQ_A_BF16: return dispatch_large<CQ_A_BF16>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, s);
-    default: return dispatch_large<CQ_A_F32>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, s);
+  if (a_kind == CQ_A_INT8_CODES || a_kind == CQ_A_F32) {
+    // 16-bit copy of the rows in sorted order (the gather is applied here)
+    uint16_t* A16 = (uint16_t*)((char*)workspace + tile_list_bytes(W->G, M_total));
+    const size_t chunks = (size_t)M_total * (W->K / 8);
+    const unsigned blocks = (unsigned)((chunks + 255) / 256);
+    if (a_kind == CQ_A_INT8_CODES)
+      hipLaunchKernelGGL(convert_rows_kernel<CQ_A_INT8_CODES>, dim3(blocks), dim3(256), 0, s, A, row_gather, M_total,
+                         W->K, A16);
+    else
+      hipLaunchKernelGGL(convert_rows_kernel<CQ_A_F32>, dim3(blocks), dim3(256), 0, s, A, row_gather, M_total, W->K,
+                         A16);
+    a.A = A16;
+    a.a_gather = nullptr;
   }
+  const bool f16 = a_kind == CQ_A_F16 || a_kind == CQ_A_F32;
+  return f16 ? dispatch_large<true>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, s)
+             : dispatch_large<false>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, s);
 }

@@ -56,7 +56,9 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
 
 // large-tile (prefill) path of the codebook product
 bool cq_gemm_large_supported(const cq_codebook_weights* W);
-size_t cq_gemm_large_workspace_bytes(int G, int M_total);
+// with_conversion: include room for a 16-bit copy of the activation rows (needed for CQ_A_INT8_CODES
+// and CQ_A_F32 operands; bf16 / f16 operands are read in place)
+size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion);
 cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                                const int32_t* row_gather, const int32_t* group_offsets, int M_total, int small_max,
                                int epilogue, void* out, int out_kind, void* workspace, hipStream_t s);

@@ -48,10 +48,15 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   size_t scratch = cq_rotate_quant_workspace_bytes(T, L->H);
   const size_t r = cq_route_permute_workspace_bytes(T, L->H, L->E, L->top_k);
   if (r > scratch) scratch = r;
-  const size_t g1 = cq_grouped_gemm_workspace_bytes(&L->gate_up, (int)M);
-  if (g1 > scratch) scratch = g1;
-  const size_t g2 = cq_grouped_gemm_workspace_bytes(&L->down, (int)M);
-  if (g2 > scratch) scratch = g2;
+  // the layer feeds both products 16-bit operands (bf16 codes, f16 h): tile lists only
+  if (use_bf16_codes(L, T)) {
+    const size_t g1 = cq_gemm_large_workspace_bytes(L->gate_up.G, (int)M, L->gate_up.K, false);
+    if (g1 > scratch) scratch = g1;
+  }
+  if (M > 32 && cq_gemm_large_supported(&L->down)) {
+    const size_t g2 = cq_gemm_large_workspace_bytes(L->down.G, (int)M, L->down.K, false);
+    if (g2 > scratch) scratch = g2;
+  }
   o->scratch = take(scratch);
   o->total = off;
 }
@@ -113,13 +118,14 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
                         inv_perm, src_token, scratch, scratch_bytes, stream);
   if (st != CQ_OK) return st;
   if (!mark(2)) return CQ_ERR_HIP;
-  st = cq_codebook_grouped_gemm(&L->gate_up, bf16_codes ? (const void*)Q16 : (const void*)Q,
-                                bf16_codes ? CQ_A_BF16 : CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU, Hbuf,
-                                CQ_OUT_F16, scratch, scratch_bytes, stream);
+  // (internal launcher: the layer was validated above and the scratch area is sized for 16-bit operands)
+  st = cq_gemm_codebook_launch(&L->gate_up, bf16_codes ? (const void*)Q16 : (const void*)Q,
+                               bf16_codes ? CQ_A_BF16 : CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU,
+                               Hbuf, CQ_OUT_F16, scratch, hs);
   if (st != CQ_OK) return st;
   if (!mark(3)) return CQ_ERR_HIP;
-  st = cq_codebook_grouped_gemm(&L->down, Hbuf, CQ_A_F16, nullptr, nullptr, offsets, M, CQ_EPI_NONE, Obuf,
-                                CQ_OUT_F32, scratch, scratch_bytes, stream);
+  st = cq_gemm_codebook_launch(&L->down, Hbuf, CQ_A_F16, nullptr, nullptr, offsets, M, CQ_EPI_NONE, Obuf, CQ_OUT_F32,
+                               scratch, hs);
   if (st != CQ_OK) return st;
   if (!mark(4)) return CQ_ERR_HIP;
   st = cq_combine(Obuf, tw, inv_perm, T, L->H, L->top_k, L->S, Y, stream);
