@@ -7,9 +7,9 @@
 //   * a lane owns one row of each of its two 32-row blocks for the whole K loop, so the two 16-entry
 //     centroid tables it needs are loop invariant and live in registers.  Decoding is pure vector ALU:
 //     nibbles become byte selectors, v_perm_b32 picks the low and the high bytes of the centroids out
-//     of register-resident byte tables (two 8-entry halves merged by bit 3 of the index), two more
-//     perm levels interleave them into bf16/f16 pairs.  About 2.3 ALU operations per MFMA, which the
-//     matrix pipe hides completely (measured);
+//     of register-resident byte tables (two 8-entry halves; a third perm, steered by bit 3 of the
+//     index, picks between them), two more perm levels interleave the bytes into bf16/f16 pairs.
+//     About 1.7 ALU operations per MFMA, all full rate, hidden behind the matrix pipe;
 //   * LDS holds only the activation tiles.  They arrive by direct global->LDS loads (no staging
 //     registers, no ds_write), four tiles deep, and each wavefront reads a tile once per K step.
 // The activation operand is 16-bit (bf16 integer codes or f16 rows); other kinds are converted by a
@@ -91,14 +91,16 @@ __device__ __forceinline__ cq_v4u decode8(uint32_t d, const RowTable& t) {
 #endif
   const uint32_t sA = d & 0x07070707u;                 // even weights: selector within a half table
   const uint32_t sB = (d >> 4) & 0x07070707u;          // odd weights
-  const uint32_t mA = ((d >> 3) & 0x01010101u) * 0xffu;  // 0xff where bit 3 of the index is set
-  const uint32_t mB = ((d >> 7) & 0x01010101u) * 0xffu;
+  // bit 3 of an index picks the upper half table: as a byte selector, byte i of the result comes from
+  // the lower-half candidate (source bytes 0-3) or the upper-half one (bytes 4-7)
+  const uint32_t mA = ((d >> 1) & 0x04040404u) | 0x03020100u;
+  const uint32_t mB = ((d >> 5) & 0x04040404u) | 0x03020100u;
   const uint32_t loA0 = __builtin_amdgcn_perm(t.lo[1], t.lo[0], sA), loA1 = __builtin_amdgcn_perm(t.lo[3], t.lo[2], sA);
   const uint32_t hiA0 = __builtin_amdgcn_perm(t.hi[1], t.hi[0], sA), hiA1 = __builtin_amdgcn_perm(t.hi[3], t.hi[2], sA);
   const uint32_t loB0 = __builtin_amdgcn_perm(t.lo[1], t.lo[0], sB), loB1 = __builtin_amdgcn_perm(t.lo[3], t.lo[2], sB);
   const uint32_t hiB0 = __builtin_amdgcn_perm(t.hi[1], t.hi[0], sB), hiB1 = __builtin_amdgcn_perm(t.hi[3], t.hi[2], sB);
-  const uint32_t loA = (mA & loA1) | (~mA & loA0), hiA = (mA & hiA1) | (~mA & hiA0);
-  const uint32_t loB = (mB & loB1) | (~mB & loB0), hiB = (mB & hiB1) | (~mB & hiB0);
+  const uint32_t loA = __builtin_amdgcn_perm(loA1, loA0, mA), hiA = __builtin_amdgcn_perm(hiA1, hiA0, mA);
+  const uint32_t loB = __builtin_amdgcn_perm(loB1, loB0, mB), hiB = __builtin_amdgcn_perm(hiB1, hiB0, mB);
   // 16-bit values: xa01 = {even0, even1}, xa23 = {even2, even3}; same for the odd weights
   const uint32_t xa01 = __builtin_amdgcn_perm(hiA, loA, 0x05010400u), xa23 = __builtin_amdgcn_perm(hiA, loA, 0x07030602u);
   const uint32_t xb01 = __builtin_amdgcn_perm(hiB, loB, 0x05010400u), xb23 = __builtin_amdgcn_perm(hiB, loB, 0x07030602u);
@@ -155,6 +157,14 @@ __device__ __forceinline__ cq_v4u lds_read_u128(uint32_t byte_offset) {
   return *reinterpret_cast<const __attribute__((address_space(3))) cq_v4u*>((uintptr_t)byte_offset);
 }
 
+// LDS row stride (bytes) of the epilogue's staging tile of 64 tokens x the workgroup's output columns
+constexpr int epilogue_row_stride(int epi, int outk) {
+  const int esize = outk == CQ_OUT_F16 ? 2 : 4;
+  const int row = (epi == CQ_EPI_SWIGLU ? kLargeRows / 2 : kLargeRows) * esize;
+  const int quad = (epi == CQ_EPI_SWIGLU ? 2 : 4) * esize;
+  return row + (quad == 16 ? 16 : 8);
+}
+
 // F16: the activations are f16 (else bf16); C = CT/32 token blocks per workgroup (8 or 4)
 template <bool F16, int EPI, int OUTK, int C>
 __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
@@ -176,6 +186,9 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r32 = lane & 31, g2 = lane >> 5;
+#if CQ_PROBE & 16
+  const long long pt0 = clock64(), pw0 = wall_clock64();
+#endif
   const int N = p.N, K = p.K;
   const size_t rowbytes = (size_t)K >> 1;
   const int n0 = rt * kLargeRows + wave * 64;  // this wavefront's 64 rows
@@ -217,10 +230,12 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     ap[i] = reinterpret_cast<const uint8_t*>(p.A) + (row * (size_t)K + chunk * 8) * 2;
   }
   const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(wave * (CT / 4) * kStepBytes);
-  auto fetch_tile = [&](int s, int buf) {  // activations of step s into tile `buf`
+  // this wavefront's loads i0 .. i0+n-1 of the activations of step s into tile `buf`
+  auto fetch_tile = [&](int s, int buf, int i0, int n) {
     const size_t o = (size_t)s * kStepBytes;
 #pragma unroll
-    for (int i = 0; i < C; ++i) load_global_to_lds(buf * kBufBytes + lds_wave + i * 1024, ap[i] + o);
+    for (int i = 0; i < C; ++i)
+      if (i >= i0 && i < i0 + n) load_global_to_lds(buf * kBufBytes + lds_wave + i * 1024, ap[i] + o);
   };
   auto fetch_weights = [&](cq_v4u (&w)[2], int s) {
     const size_t o = (size_t)s * sstride;
@@ -255,11 +270,11 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   constexpr int kPerStep = ((CQ_PROBE & 1) ? 0 : C) + ((CQ_PROBE & 8) ? 0 : 2);
   cq_v4u wq[kNBuf][2];
   fetch_weights(wq[0], 0);
-  fetch_tile(0, 0);
+  fetch_tile(0, 0, 0, C);
   fetch_weights(wq[1], min(1, nS - 1));
-  fetch_tile(min(1, nS - 1), 1);
+  fetch_tile(min(1, nS - 1), 1, 0, C);
   fetch_weights(wq[2], min(2, nS - 1));
-  fetch_tile(min(2, nS - 1), 2);
+  fetch_tile(min(2, nS - 1), 2, 0, C);
   vm_wait<kPerStep>(wq[0][0], wq[0][1], wq[1][0], wq[1][1]);
   __syncthreads();
 
@@ -276,6 +291,9 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
 #pragma unroll
   for (int cb = 0; cb < C; ++cb) bfr[cb] = read_b(0, 0, cb);
 
+#if CQ_PROBE & 16
+  const long long pt1 = clock64();
+#endif
   int s0 = 0;
   do {  // at least two steps exist (no zero-trip path: the accumulators stay in their AGPRs throughout)
 #pragma unroll
@@ -283,10 +301,10 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
       if (par == 2 && s0 + 2 >= nS) break;  // K is a multiple of 128: steps come in pairs
       const int s3 = min(s0 + par + 3, nS - 1);
       fetch_weights(wq[(par + 3) & 3], s3);
-      fetch_tile(s3, (par + 3) & 3);
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int cur = jj & 1, nxt = cur ^ 1;
+        fetch_tile(s3, (par + 3) & 3, jj * (C / 4), C / 4);  // spread over the step: no LDS write bursts
         // next sub-step: jj + 1 of this step, or the first one of the next step
         const int nbuf = jj < 3 ? par : (par + 1) & 3, njj = (jj + 1) & 3;
         af[nxt][0] = decode8(wq[nbuf][0][njj], t0);
@@ -316,44 +334,94 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   // nothing of this workgroup may still be on its way into LDS when the workgroup ends
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
+#if CQ_PROBE & 16
+  const long long pt2 = clock64();
+#endif
   // ---- epilogue: per-token scale, optional SiLU(gate)*up, store ----
+  // A lane holds 4 consecutive outputs of ONE token per accumulator quad, so storing from registers
+  // would touch 64 different cache lines per instruction.  Instead the tile goes through LDS (free
+  // now) 64 tokens at a time: row-major [token][this workgroup's columns] with a padded row stride
+  // (conflict-free writes), then the workgroup streams whole rows out, neighbouring lanes writing
+  // neighbouring bytes.
+  constexpr int kOutCols = EPI == CQ_EPI_SWIGLU ? kLargeRows / 2 : kLargeRows;
+  constexpr int kEsize = OUTK == CQ_OUT_F16 ? 2 : 4;
+  constexpr int kRowBytes = kOutCols * kEsize;                    // 256 .. 1024
+  constexpr int kQuadBytes = (EPI == CQ_EPI_SWIGLU ? 2 : 4) * kEsize;  // what one accumulator quad becomes
+  constexpr int kRowStride = kRowBytes + (kQuadBytes == 16 ? 16 : 8);
+  constexpr int kPiece = kRowStride % 16 == 0 ? 16 : 8;           // bytes per lane when streaming out
+  constexpr int kPiecesPerRow = kRowBytes / kPiece;
+  static_assert(kRowStride == epilogue_row_stride(EPI, OUTK), "the launcher sizes LDS with the same formula");
+  const size_t out_col0 = (size_t)rt * kOutCols;
+  typedef __attribute__((address_space(3))) uint32_t lds_u32;
+  typedef __attribute__((address_space(3))) cq_v4u lds_v4u;
+  typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t v2u;
+  typedef __attribute__((address_space(3))) v2u lds_v2u;
 #pragma unroll
-  for (int cb = 0; cb < C; ++cb) {
-    const int tok = cb * 32 + r32;
-    if (tok < mcnt) {
-      const int m = mrow0 + tok;
+  for (int pass = 0; pass < C / 2; ++pass) {
+    __syncthreads();  // the tile buffers (first pass) or the previous pass's rows are no longer read
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int cb = pass * 2 + half;
+      const int tl = half * 32 + r32;  // token within the pass
       float sc = 1.f;
-      if (p.row_scale) sc = p.row_scale[p.scale_gather ? p.scale_gather[m] : m];
+      if (p.row_scale) {
+        const int m = mrow0 + min(cb * 32 + r32, mcnt - 1);
+        sc = p.row_scale[p.scale_gather ? p.scale_gather[m] : m];
+      }
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
 #pragma unroll
         for (int vb = 0; vb < 4; ++vb) {
           // MFMA 32x32 output: register v holds row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
-          const int row = n0 + rb * 32 + vb * 8 + g2 * 4;
+          const int quad = (wave * 64 + rb * 32 + vb * 8 + g2 * 4) >> 2;  // which 4 weight rows of the tile
+          const uint32_t at = (uint32_t)tl * kRowStride + (uint32_t)quad * kQuadBytes;
           const float x0 = sc * acc[rb][cb][4 * vb], x1 = sc * acc[rb][cb][4 * vb + 1];
           const float x2 = sc * acc[rb][cb][4 * vb + 2], x3 = sc * acc[rb][cb][4 * vb + 3];
           if constexpr (EPI == CQ_EPI_SWIGLU) {
-            const float h0 = x0 / (1.f + __expf(-x0)) * x1;
-            const float h1 = x2 / (1.f + __expf(-x2)) * x3;
-            const size_t o = (size_t)m * p.out_ld + (row >> 1);
+            const float h0 = x0 * __builtin_amdgcn_rcpf(1.f + __expf(-x0)) * x1;
+            const float h1 = x2 * __builtin_amdgcn_rcpf(1.f + __expf(-x2)) * x3;
             if constexpr (OUTK == CQ_OUT_F16)
-              *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + o) =
-                  f32_to_f16_sat(h0) | (f32_to_f16_sat(h1) << 16);
+              *reinterpret_cast<lds_u32*>((uintptr_t)at) = f32_to_f16_sat(h0) | (f32_to_f16_sat(h1) << 16);
             else
-              *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + o) = make_float2(h0, h1);
+              *reinterpret_cast<lds_v2u*>((uintptr_t)at) = v2u{__float_as_uint(h0), __float_as_uint(h1)};
           } else {
-            const size_t o = (size_t)m * p.out_ld + row;
             if constexpr (OUTK == CQ_OUT_F16)
-              *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + o) =
-                  make_uint2(f32_to_f16_sat(x0) | (f32_to_f16_sat(x1) << 16),
-                             f32_to_f16_sat(x2) | (f32_to_f16_sat(x3) << 16));
+              *reinterpret_cast<lds_v2u*>((uintptr_t)at) = v2u{f32_to_f16_sat(x0) | (f32_to_f16_sat(x1) << 16),
+                                                                f32_to_f16_sat(x2) | (f32_to_f16_sat(x3) << 16)};
             else
-              *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + o) = make_float4(x0, x1, x2, x3);
+              *reinterpret_cast<lds_v4u*>((uintptr_t)at) =
+                  cq_v4u{__float_as_uint(x0), __float_as_uint(x1), __float_as_uint(x2), __float_as_uint(x3)};
           }
         }
       }
     }
+    __syncthreads();
+    // stream the 64 rows out: piece i of the pass = (token i / kPiecesPerRow, piece i % kPiecesPerRow)
+#pragma unroll
+    for (int it = 0; it < 64 * kPiecesPerRow / 256; ++it) {
+      const int i = it * 256 + tid;
+      const int tl = i / kPiecesPerRow, pc = i - tl * kPiecesPerRow;
+      const int tok = pass * 64 + tl;
+      if (tok < mcnt) {
+        const uint32_t at = (uint32_t)tl * kRowStride + (uint32_t)pc * kPiece;
+        char* dst = reinterpret_cast<char*>(p.out) + ((size_t)(mrow0 + tok) * p.out_ld + out_col0) * kEsize + (size_t)pc * kPiece;
+        if constexpr (kPiece == 16)
+          *reinterpret_cast<cq_v4u*>(dst) = *reinterpret_cast<const lds_v4u*>((uintptr_t)at);
+        else
+          *reinterpret_cast<v2u*>(dst) = *reinterpret_cast<const lds_v2u*>((uintptr_t)at);
+      }
+    }
   }
+#if CQ_PROBE & 16
+  __syncthreads();
+  if (tid == 0) {  // cycle counts of this workgroup, written over the start of the output (timing runs only)
+    long long* st = reinterpret_cast<long long*>(p.out) + (size_t)work * 4;
+    st[0] = pt1 - pt0;
+    st[1] = pt2 - pt1;
+    st[2] = clock64() - pt2;
+    st[3] = wall_clock64() - pw0;
+  }
+#endif
 }
 
 // Pre-pass for activation kinds the main kernel does not read: sorted row m of the result is row
@@ -447,7 +515,8 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
 template <bool F16, int EPI, int OUTK, int C>
 cq_status launch_large(const LargeArgs& a, int max_tiles, hipStream_t s) {
   auto kern = gemm_large_kernel<F16, EPI, OUTK, C>;
-  constexpr int lds = kNBuf * 32 * C * kStepBytes;
+  constexpr int lds_loop = kNBuf * 32 * C * kStepBytes, lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
+  constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
   static bool configured = false;
   if (!configured) {
     hipFuncAttributes fa;
