@@ -4,22 +4,30 @@
 
 namespace {
 
-// Y[t,:] = sum_j w[t,j] * O[inv_perm[t*k+j], :] + sum_s O[T*k + s*T + t, :], fixed order.
-__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ O, const float* __restrict__ w,
+// Y[t,:] = sum_j w[t,j] * O[inv_perm[t*k+j], :] + sum_s O[T*k + s*T + t, :], fixed order.  O may come
+// as `slices` partial copies (K splits of the down projection), added in slice order first.
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ O, int slices, size_t slice_stride,
+                                                      const float* __restrict__ w,
                                                       const int32_t* __restrict__ inv_perm, int T, int H, int k,
                                                       int S, float* __restrict__ Y) {
   const int t = blockIdx.x;
+  auto row_of = [&](size_t row, int c) {
+    float4 o = *reinterpret_cast<const float4*>(O + row * H + c);
+    for (int q = 1; q < slices; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(O + (size_t)q * slice_stride + row * H + c);
+      o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+    }
+    return o;
+  };
   for (int c = threadIdx.x * 4; c < H; c += 256 * 4) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int j = 0; j < k; ++j) {
       const float wt = w[(size_t)t * k + j];
-      const size_t row = (size_t)inv_perm[(size_t)t * k + j];
-      const float4 o = *reinterpret_cast<const float4*>(O + row * H + c);
+      const float4 o = row_of((size_t)inv_perm[(size_t)t * k + j], c);
       acc.x += wt * o.x; acc.y += wt * o.y; acc.z += wt * o.z; acc.w += wt * o.w;
     }
     for (int s = 0; s < S; ++s) {
-      const size_t row = (size_t)T * k + (size_t)s * T + t;
-      const float4 o = *reinterpret_cast<const float4*>(O + row * H + c);
+      const float4 o = row_of((size_t)T * k + (size_t)s * T + t, c);
       acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
     }
     *reinterpret_cast<float4*>(Y + (size_t)t * H + c) = acc;
@@ -97,13 +105,18 @@ extern "C" const char* cq_status_string(cq_status st) {
   }
 }
 
+cq_status cq_combine_launch(const float* O, int slices, size_t slice_stride, const float* topk_w,
+                            const int32_t* inv_perm, int T, int H, int top_k, int n_shared, float* Y, hipStream_t s) {
+  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, O, slices, slice_stride, topk_w, inv_perm, T, H, top_k,
+                     n_shared, Y);
+  return cq_check_launch();
+}
+
 extern "C" cq_status cq_combine(const float* O, const float* topk_w, const int32_t* inv_perm, int T, int H,
                                 int top_k, int n_shared, float* Y, cq_stream stream) {
   if (!O || !topk_w || !inv_perm || !Y) return CQ_ERR_NULL;
   if (T <= 0 || H <= 0 || H % 4 != 0 || top_k <= 0 || n_shared < 0) return CQ_ERR_SHAPE;
-  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, (hipStream_t)stream, O, topk_w, inv_perm, T, H, top_k,
-                     n_shared, Y);
-  return cq_check_launch();
+  return cq_combine_launch(O, 1, 0, topk_w, inv_perm, T, H, top_k, n_shared, Y, (hipStream_t)stream);
 }
 
 extern "C" size_t cq_prepack_bytes(const cq_codebook_weights* W) {

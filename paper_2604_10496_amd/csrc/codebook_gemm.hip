@@ -28,11 +28,16 @@
 
 #include "cq_internal.h"
 
+#ifndef CQ_PROBE
+#define CQ_PROBE 0
+#endif
+
 namespace {
 
 constexpr int kSmallMaxRows = 32;     // one token block: beyond this the large-tile kernel is better
 constexpr int kTableBytes = 65536;   // 256 entries x 64 row slots x 4 bytes
-constexpr int kSlabBytes = 65536;    // activation slab / reduction buffer
+constexpr int kSlabBytes = 65536;    // activation slab
+constexpr int kRedBytes = 32768;     // K partials of up to 16 token columns: 8 wavefronts x 32 registers x 32 lanes
 #ifndef CQ_GEMM_WAVES
 #define CQ_GEMM_WAVES 8
 #endif
@@ -56,6 +61,10 @@ struct GemmArgs {
   int out_ld;
   int upw;                  // 64-row units per workgroup (consecutive, same expert)
   int max_rows;             // groups with more rows are left to the large-tile kernel
+  int ksteps;               // K steps (of 64) per K split; blockIdx.z selects the split
+  int ksplit;               // number of K splits; > 1: scaled fp32 partial sums go to `partials`
+  float* partials;          // [ksplit][M_total][N]
+  size_t part_stride;       // M_total * N
 };
 
 __device__ __forceinline__ uint32_t f32_to_f16_bits_sat(float x) {
@@ -90,6 +99,13 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
   }
 }
 
+#if CQ_PROBE
+__device__ long long g_probe[8 * 4096];
+#define PROBE_T(x) const long long x = clock64()
+#else
+#define PROBE_T(x)
+#endif
+
 template <int AK, int EPI, int OUTK>
 __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmArgs p) {
   constexpr bool F16 = (AK == CQ_A_F16 || AK == CQ_A_F32);
@@ -100,6 +116,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   uint32_t* tbl = reinterpret_cast<uint32_t*>(lds);
   float* red = reinterpret_cast<float*>(lds);  // aliases the table between units
   uint4* slab = reinterpret_cast<uint4*>(lds + kTableBytes);
+  float* redc = reinterpret_cast<float*>(lds + kTableBytes + kSlabBytes);  // kRedBytes: partials of <= 16 tokens
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = blockIdx.y;
@@ -125,7 +142,12 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     lane_off1 = (size_t)(32 + r32) * rowbytes + g2 * 16;
     sstride = 32;
   }
-  const int nS = K >> 6;                            // K steps of 64
+  const int sb = blockIdx.z * p.ksteps;             // first K step (of 64) of this workgroup's K range
+  const int nS = min(p.ksteps, (K >> 6) - sb);      // its number of steps
+  if (nS <= 0) return;
+  const int Kl = nS << 6;
+  lane_off0 += (size_t)sb * sstride;
+  lane_off1 += (size_t)sb * sstride;
   const int Qmax = (nS + NW - 1) / NW;              // steps per wavefront (upper bound)
   const int Qpad = (Qmax + kRing - 1) / kRing * kRing;
   const uint32_t lanebase0 = (uint32_t)(r32 * 4);
@@ -137,8 +159,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     const int Mpad = Mb <= 8 ? 8 : Mb <= 16 ? 16 : 32;     // divides the workgroup: a thread stages one token
     const int KSfull = 32768 / Mpad;                       // k values per slab (slab bytes / 2 / Mpad)
     const int qPerSlab = (KSfull >> 6) / NW;               // wavefront steps per slab
-    const bool multi = KSfull < K;                         // activations do not fit: restage per slab
+    const bool multi = KSfull < Kl;                        // activations do not fit: restage per slab
     const int tj = r32 < Mpad ? r32 : 0;                   // token column this lane feeds to the B operand
+    const bool sep = Mpad <= 16;                           // partial sums get a region of their own
+    const int lane_c = (g2 << 4) + r32;                    // compact numbering of up to 16 real columns
 
     // ---- this thread's staging duty: token st, 8-wide k chunks sc0, sc0 + cstep, ... ----
     const int st = tid & (Mpad - 1);
@@ -151,11 +175,11 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     }
     auto stage = [&](int sl) {
       const int k0 = sl * KSfull;
-      const int nC = min(KSfull, K - k0) >> 3;
+      const int nC = min(KSfull, Kl - k0) >> 3;
       for (int c = sc0; c < nC; c += cstep) {
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (svalid) {
-          const size_t e0 = srow + k0 + c * 8;
+          const size_t e0 = srow + (size_t)sb * 64 + k0 + c * 8;
           if constexpr (AK == CQ_A_INT8_CODES) {
             const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0);
             const uint32_t rw[2] = {raw.x, raw.y};
@@ -242,14 +266,20 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     // of K (the decode case) they are staged once, up front, and the loop body contains no conditional
     // loads at all: the number of loads in flight is then the same on every path, which lets each wait
     // cover exactly one ring slot.  Otherwise the slab is restaged inside the loop.
-    auto run_units = [&](auto multi_tag) {
+    auto run_units = [&](auto multi_tag, auto sep_tag) {
       constexpr bool MULTI = decltype(multi_tag)::value;
+      constexpr bool SEP = decltype(sep_tag)::value;  // partials in their own region, 32 lanes per register row
+      float* rbase = SEP ? redc : red;
+      constexpr int rw = SEP ? 32 : 64;
+      const int rl = SEP ? lane_c : lane;
       for (int u = u0; u < u1; ++u) {
         const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
         const bool has_next = u + 1 < u1;
         const uint8_t* wb_next = has_next ? wb + 64 * rowbytes : wb;
+        PROBE_T(pt0);
         build_table();
         __syncthreads();
+        PROBE_T(pt1);
 
         cq_v16f acc0, acc1;
 #pragma unroll
@@ -333,25 +363,39 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         }
 
         // ---- reduce the K partials (fixed order) through the table's LDS and finish ----
-        __syncthreads();
+        // Only the lanes of real token columns carry results.  Up to 16 tokens their partials fit a
+        // region of their own (compact: 32 lanes per register), which needs one barrier per unit:
+        // a wavefront can only reach the next unit's partial writes after that unit's table barrier,
+        // which every wavefront passes after its reads here.  Beyond that the partials alias the table
+        // and two more barriers fence them from the lookups.
+        PROBE_T(pt2);
+        if (!SEP) __syncthreads();
+        PROBE_T(pt3);
+        if (r32 < Mpad) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          red[(wave * 32 + i) * 64 + lane] = acc0[i];
-          red[(wave * 32 + 16 + i) * 64 + lane] = acc1[i];
+          for (int i = 0; i < 16; ++i) {
+            rbase[(wave * 32 + i) * rw + rl] = acc0[i];
+            rbase[(wave * 32 + 16 + i) * rw + rl] = acc1[i];
+          }
         }
         __syncthreads();
         // wavefront w finishes accumulator registers RPW*w .. RPW*w + RPW-1 of the 32
         constexpr int RPW = 32 / NW;
         float val[RPW];
+        if (r32 < Mpad) {
 #pragma unroll
-        for (int i = 0; i < RPW; ++i) {
-          const int r = wave * RPW + i;
-          float s = red[r * 64 + lane];
+          for (int i = 0; i < RPW; ++i) {
+            const int r = wave * RPW + i;
+            float s = rbase[r * rw + rl];
 #pragma unroll
-          for (int w = 1; w < NW; ++w) s += red[(w * 32 + r) * 64 + lane];
-          val[i] = s;
+            for (int w = 1; w < NW; ++w) s += rbase[(w * 32 + r) * rw + rl];
+            val[i] = s;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < RPW; ++i) val[i] = 0.f;
         }
-        __syncthreads();  // the next unit's table overwrites this region
+        if (!SEP) __syncthreads();  // the next unit's table overwrites this region
         if (r32 < Mb) {
           const int m = m0 + 32 * tb + r32;
 #pragma unroll
@@ -361,6 +405,11 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
             const int row = u * 64 + (r >> 4) * 32 + ((r >> 2) & 3) * 8 + g2 * 4;
             const float x0 = sc * val[4 * h], x1 = sc * val[4 * h + 1], x2 = sc * val[4 * h + 2],
                         x3 = sc * val[4 * h + 3];
+            if (p.ksplit > 1) {  // partial sum of this K range (the launcher allows this for CQ_EPI_NONE only)
+              float* dst = p.partials + (size_t)blockIdx.z * p.part_stride + (size_t)m * N + row;
+              *reinterpret_cast<float4*>(dst) = make_float4(x0, x1, x2, x3);
+              continue;
+            }
             if constexpr (EPI == CQ_EPI_SWIGLU) {
               const float h0 = x0 / (1.f + __expf(-x0)) * x1;
               const float h1 = x2 / (1.f + __expf(-x2)) * x3;
@@ -383,13 +432,25 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
             }
           }
         }
+#if CQ_PROBE
+        if (lane == 0) {
+          const int wgslot = ((blockIdx.y * gridDim.x + blockIdx.x) & 255) + (p.K > p.N ? 256 : 0);
+          long long* g = g_probe + ((size_t)wgslot * 8 + wave) * 8;
+          const long long pt4 = clock64();
+          g[0] += pt1 - pt0; g[1] += pt2 - pt1; g[2] += pt3 - pt2; g[3] += pt4 - pt3; g[4] += 1;
+          if (u == u0) g[5] = wall_clock64();
+          g[6] = wall_clock64();
+        }
+#endif
       }
     };
     if (multi) {
-      run_units(std::true_type{});
+      if (sep) run_units(std::true_type{}, std::true_type{});
+      else run_units(std::true_type{}, std::false_type{});
     } else {
       stage(0);
-      run_units(std::false_type{});
+      if (sep) run_units(std::false_type{}, std::true_type{});
+      else run_units(std::false_type{}, std::false_type{});
     }
     __syncthreads();  // the slab is restaged for the next token block
   }
@@ -404,13 +465,41 @@ cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
     if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
     if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kTableBytes + kSlabBytes) != hipSuccess)
+                            kTableBytes + kSlabBytes + kRedBytes) != hipSuccess)
       return CQ_ERR_HIP;
     configured = true;
   }
   const int n_units = a.N / 64;
-  hipLaunchKernelGGL(kern, dim3((n_units + a.upw - 1) / a.upw, G), dim3(64 * kWaves), kTableBytes + kSlabBytes, s, a);
+  hipLaunchKernelGGL(kern, dim3((n_units + a.upw - 1) / a.upw, G, a.ksplit), dim3(64 * kWaves),
+                     kTableBytes + kSlabBytes + kRedBytes, s, a);
   return cq_check_launch();
+}
+
+// out[m, :] = sum over the K splits of partials[s][m, :] in the order s = 0, 1, ... for the rows of the
+// groups the streaming kernel handled (at most max_rows rows); other rows are left alone.
+template <int OUTK>
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ partials, size_t part_stride,
+                                                           int ksplit, const int32_t* __restrict__ group_offsets,
+                                                           int max_rows, int N, void* __restrict__ out) {
+  const int grp = blockIdx.y;
+  const int m0 = group_offsets[grp], Me = group_offsets[grp + 1] - m0;
+  if (Me <= 0 || Me > max_rows) return;
+  const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c >= N) return;
+  for (int m = m0; m < m0 + Me; ++m) {
+    const size_t at = (size_t)m * N + c;
+    float4 acc = *reinterpret_cast<const float4*>(partials + at);
+    for (int q = 1; q < ksplit; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(partials + (size_t)q * part_stride + at);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    if constexpr (OUTK == CQ_OUT_F16)
+      *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + at) =
+          make_uint2(f32_to_f16_bits_sat(acc.x) | (f32_to_f16_bits_sat(acc.y) << 16),
+                     f32_to_f16_bits_sat(acc.z) | (f32_to_f16_bits_sat(acc.w) << 16));
+    else
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + at) = acc;
+  }
 }
 
 template <int AK>
@@ -425,9 +514,32 @@ cq_status dispatch_epi(const GemmArgs& a, int G, int epilogue, int out_kind, hip
 
 }  // namespace
 
+// K split of the streaming kernel.  One workgroup keeps the activations of its K range in LDS for all
+// its 64-row units; with few tokens (the decode regime) a long K (the down projection) is therefore cut
+// into ranges of at most 4096 that different workgroups stream, and their partial sums are added in a
+// fixed order afterwards.  Plain products only (a nonlinear epilogue needs the whole sum).
+void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue, int* ksplit, int* ksteps) {
+  const int nS = W->K / 64;
+  *ksplit = 1;
+  *ksteps = nS;
+  if (epilogue != CQ_EPI_NONE || M_total > 256 || nS <= 64) return;
+  const int want = (nS + 63) / 64;
+  const int per = ((nS + want - 1) / want + kWaves - 1) / kWaves * kWaves;  // whole rounds of the wavefronts
+  *ksteps = per;
+  *ksplit = (nS + per - 1) / per;
+}
+
+size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue) {
+  int ksplit, ksteps;
+  cq_gemm_split_plan(W, M_total, epilogue, &ksplit, &ksteps);
+  return ksplit > 1 ? cq_align_up((size_t)ksplit * M_total * W->N * sizeof(float), 256) : 0;
+}
+
 cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                                   const int32_t* row_gather, const int32_t* group_offsets, int M_total,
-                                  int epilogue, void* out, int out_kind, void* workspace, hipStream_t s) {
+                                  int epilogue, void* out, int out_kind, void* workspace, hipStream_t s,
+                                  int* ksplit_left) {
+  if (ksplit_left) *ksplit_left = 1;
   GemmArgs a;
   a.idx = W->prepacked ? (const uint8_t*)W->prepacked : W->idx;
   a.cent = W->cent;
@@ -443,7 +555,10 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   {
     // about one workgroup per compute unit: the per-workgroup prologue (activation staging, first
     // table, ring fill) is paid once and there is no partially filled last round of workgroups
-    const long units = (long)(W->N / 64) * W->G;
+    cq_gemm_split_plan(W, M_total, epilogue, &a.ksplit, &a.ksteps);
+    a.partials = (float*)workspace;  // partial sums first, then the large-tile kernel's lists
+    a.part_stride = (size_t)M_total * W->N;
+    const long units = (long)(W->N / 64) * W->G * a.ksplit;
     long upw = (units + 255) / 256;
     if (upw < 1) upw = 1;
     if (upw > W->N / 64) upw = W->N / 64;
@@ -460,14 +575,45 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     case CQ_A_BF16: st = dispatch_epi<CQ_A_BF16>(a, W->G, epilogue, out_kind, s); break;
     default: st = dispatch_epi<CQ_A_F32>(a, W->G, epilogue, out_kind, s); break;
   }
-  if (st != CQ_OK || !large) return st;
+  if (st != CQ_OK) return st;
+  if (a.ksplit > 1) {
+    if (ksplit_left && !large) {
+      *ksplit_left = a.ksplit;  // the caller adds the partial sums itself (they are all there is)
+    } else {
+      const dim3 grid((W->N / 4 + 255) / 256, W->G);
+      if (out_kind == CQ_OUT_F16)
+        hipLaunchKernelGGL(sum_partials_kernel<CQ_OUT_F16>, grid, dim3(256), 0, s, a.partials, a.part_stride, a.ksplit,
+                           group_offsets, a.max_rows, W->N, out);
+      else
+        hipLaunchKernelGGL(sum_partials_kernel<CQ_OUT_F32>, grid, dim3(256), 0, s, a.partials, a.part_stride, a.ksplit,
+                           group_offsets, a.max_rows, W->N, out);
+      st = cq_check_launch();
+      if (st != CQ_OK) return st;
+    }
+  }
+  if (!large) return st;
+  void* large_ws = (char*)workspace + cq_gemm_partials_bytes(W, M_total, epilogue);
   return cq_gemm_large_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, kSmallMaxRows, epilogue,
-                              out, out_kind, workspace, s);
+                              out, out_kind, large_ws, s);
 }
 
+#if CQ_PROBE
+extern "C" int cq_probe_read(long long* host, int n, int clear) {
+  if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_probe), (size_t)n * 8) != hipSuccess) return 1;
+  if (clear) {
+    static long long zeros[8 * 4096];
+    if (hipMemcpyToSymbol(HIP_SYMBOL(g_probe), zeros, sizeof(zeros)) != hipSuccess) return 1;
+  }
+  return 0;
+}
+#endif
+
 extern "C" size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, int M_total) {
-  if (!W || W->G <= 0 || M_total <= kSmallMaxRows || !cq_gemm_large_supported(W)) return 0;
-  return cq_gemm_large_workspace_bytes(W->G, M_total, W->K, true);  // worst case over the operand kinds
+  if (!W || W->G <= 0 || W->N <= 0 || W->K <= 0 || M_total <= 0) return 0;
+  size_t n = cq_gemm_partials_bytes(W, M_total, CQ_EPI_NONE);
+  if (M_total > kSmallMaxRows && cq_gemm_large_supported(W))
+    n += cq_gemm_large_workspace_bytes(W->G, M_total, W->K, true);  // worst case over the operand kinds
+  return n;
 }
 
 extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, const void* A, int a_kind,
@@ -489,5 +635,5 @@ extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, cons
     if (need > 0 && (!workspace || workspace_bytes < need)) return CQ_ERR_WORKSPACE;
   }
   return cq_gemm_codebook_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, epilogue, out,
-                                 out_kind, workspace, (hipStream_t)stream);
+                                 out_kind, workspace, (hipStream_t)stream, nullptr);
 }

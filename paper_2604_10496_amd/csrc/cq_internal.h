@@ -49,10 +49,17 @@ cq_status cq_permute_launch(const int32_t* topk_ids, int T, int E, int top_k, in
                             int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm, int32_t* src_token,
                             void* workspace, hipStream_t s);
 
+// ksplit_left: NULL, or receives the number of K splits whose partial sums [ksplit][M_total][N] (fp32,
+// at the start of `workspace`) the caller must add itself; 1 means `out` is final.  With NULL the
+// launcher always finishes `out`.
 cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, int a_kind,
                                   const float* row_scale, const int32_t* row_gather,
                                   const int32_t* group_offsets, int M_total, int epilogue,
-                                  void* out, int out_kind, void* workspace, hipStream_t s);
+                                  void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left);
+size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue);
+// weighted combine over `slices` partial copies of O that are `slice_stride` floats apart
+cq_status cq_combine_launch(const float* O, int slices, size_t slice_stride, const float* topk_w,
+                            const int32_t* inv_perm, int T, int H, int top_k, int n_shared, float* Y, hipStream_t s);
 
 // large-tile (prefill) path of the codebook product
 bool cq_gemm_large_supported(const cq_codebook_weights* W);

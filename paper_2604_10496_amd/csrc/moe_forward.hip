@@ -53,8 +53,10 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
     const size_t g1 = cq_gemm_large_workspace_bytes(L->gate_up.G, (int)M, L->gate_up.K, false);
     if (g1 > scratch) scratch = g1;
   }
-  if (M > 32 && cq_gemm_large_supported(&L->down)) {
-    const size_t g2 = cq_gemm_large_workspace_bytes(L->down.G, (int)M, L->down.K, false);
+  {
+    size_t g2 = cq_gemm_partials_bytes(&L->down, (int)M, CQ_EPI_NONE);
+    if (M > 32 && cq_gemm_large_supported(&L->down))
+      g2 += cq_gemm_large_workspace_bytes(L->down.G, (int)M, L->down.K, false);
     if (g2 > scratch) scratch = g2;
   }
   o->scratch = take(scratch);
@@ -121,14 +123,17 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
   // (internal launcher: the layer was validated above and the scratch area is sized for 16-bit operands)
   st = cq_gemm_codebook_launch(&L->gate_up, bf16_codes ? (const void*)Q16 : (const void*)Q,
                                bf16_codes ? CQ_A_BF16 : CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU,
-                               Hbuf, CQ_OUT_F16, scratch, hs);
+                               Hbuf, CQ_OUT_F16, scratch, hs, nullptr);
   if (st != CQ_OK) return st;
   if (!mark(3)) return CQ_ERR_HIP;
+  int down_splits = 1;  // > 1: the down projection left K-split partial sums in the scratch area
   st = cq_gemm_codebook_launch(&L->down, Hbuf, CQ_A_F16, nullptr, nullptr, offsets, M, CQ_EPI_NONE, Obuf, CQ_OUT_F32,
-                               scratch, hs);
+                               scratch, hs, &down_splits);
   if (st != CQ_OK) return st;
   if (!mark(4)) return CQ_ERR_HIP;
-  st = cq_combine(Obuf, tw, inv_perm, T, L->H, L->top_k, L->S, Y, stream);
+  st = down_splits > 1 ? cq_combine_launch((const float*)scratch, down_splits, (size_t)M * L->H, tw, inv_perm, T,
+                                           L->H, L->top_k, L->S, Y, hs)
+                       : cq_combine_launch(Obuf, 1, 0, tw, inv_perm, T, L->H, L->top_k, L->S, Y, hs);
   if (st != CQ_OK) return st;
   if (!mark(5)) return CQ_ERR_HIP;
   return CQ_OK;

@@ -170,7 +170,11 @@ def _rand_weights(rng, G, N, K, cent=None):
                                         # 256-row matrices with K % 128 == 0: groups above 32 rows take the
                                         # large-tile kernel (tiles of 256 and 128 tokens, ragged tails)
                                         (256, 128, [33]), (512, 384, [40, 0, 300, 7, 129, 128, 257]),
-                                        (256, 1408, [600, 31, 32, 33])])
+                                        (256, 1408, [600, 31, 32, 33]),
+                                        # long K with few rows: K is split over workgroups and the partial
+                                        # sums are added afterwards (also next to large-tile groups, and
+                                        # with a token block of 17..32 rows that restages inside its range)
+                                        (64, 8192, [3, 0, 9]), (128, 14336, [5, 17, 33]), (256, 8192, [40, 7])])
 def test_gemm_integer_centroids_exact(B, N, K, counts, prepacked):
     """Centroids k-8 and integer codes: every partial sum is an integer below 2^24, so the result must
     equal the exact integer product whatever the summation order."""
