@@ -22,6 +22,22 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16/f16 MFMA, published
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# very script (scaled by what the counters read for the 1 GiB copy below); see profiles/
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(workload, kernel):
+    """Bytes per launch from the committed counter summary ("workload kernel bytes" lines), or None."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == workload and parts[1] == kernel:
+                    return int(parts[2])
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def parse_args():
@@ -135,13 +151,14 @@ def main():
         ach = gu_bytes / gu_s / 1e9
         roofline = {"bound": "hbm", "kernel": "gemm_small_kernel (gate/up codebook product + SwiGLU)",
                     "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
-                    "traffic": None, "algorithmic_bytes_per_launch": gu_bytes,
-                    "avg_launch_ms": stage["gate_up"]}
+                    "traffic": measured_traffic(cfg.name, "gemm_small_kernel"),
+                    "algorithmic_bytes_per_launch": gu_bytes, "avg_launch_ms": stage["gate_up"]}
     else:
         ach = gu_flops / gu_s / 1e12
-        roofline = {"bound": "mfma", "kernel": "gate/up codebook product + SwiGLU",
+        roofline = {"bound": "mfma", "kernel": "gemm_large_kernel (gate/up codebook product + SwiGLU)",
                     "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                    "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": measured_traffic(cfg.name, "gemm_large_kernel"),
                     "algorithmic_flops_per_launch": gu_flops, "avg_launch_ms": stage["gate_up"]}
 
     # measured streaming-read ceiling next to the nominal peak
@@ -155,7 +172,12 @@ def main():
         B.cq_stream_read(probe)
     torch.cuda.synchronize()
     read_gbps = probe.numel() * 10 / (time.perf_counter() - t0) / 1e9
-    del probe
+    # a plain copy of known size (1 GiB read + 1 GiB written): the yardstick the HBM counters of a
+    # profiled run are scaled by
+    dst = torch.empty_like(probe)
+    dst.copy_(probe)
+    torch.cuda.synchronize()
+    del probe, dst
 
     out = {
         "metric": "MoE-layer tokens/s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,

@@ -28,10 +28,6 @@
 
 #include "cq_internal.h"
 
-#ifndef CQ_PROBE
-#define CQ_PROBE 0
-#endif
-
 namespace {
 
 constexpr int kSmallMaxRows = 32;     // one token block: beyond this the large-tile kernel is better
@@ -99,12 +95,6 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
   }
 }
 
-#if CQ_PROBE
-__device__ long long g_probe[8 * 4096];
-#define PROBE_T(x) const long long x = clock64()
-#else
-#define PROBE_T(x)
-#endif
 
 template <int AK, int EPI, int OUTK>
 __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmArgs p) {
@@ -276,10 +266,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
         const bool has_next = u + 1 < u1;
         const uint8_t* wb_next = has_next ? wb + 64 * rowbytes : wb;
-        PROBE_T(pt0);
         build_table();
         __syncthreads();
-        PROBE_T(pt1);
 
         cq_v16f acc0, acc1;
 #pragma unroll
@@ -368,9 +356,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         // a wavefront can only reach the next unit's partial writes after that unit's table barrier,
         // which every wavefront passes after its reads here.  Beyond that the partials alias the table
         // and two more barriers fence them from the lookups.
-        PROBE_T(pt2);
         if (!SEP) __syncthreads();
-        PROBE_T(pt3);
         if (r32 < Mpad) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
@@ -432,16 +418,6 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
             }
           }
         }
-#if CQ_PROBE
-        if (lane == 0) {
-          const int wgslot = ((blockIdx.y * gridDim.x + blockIdx.x) & 255) + (p.K > p.N ? 256 : 0);
-          long long* g = g_probe + ((size_t)wgslot * 8 + wave) * 8;
-          const long long pt4 = clock64();
-          g[0] += pt1 - pt0; g[1] += pt2 - pt1; g[2] += pt3 - pt2; g[3] += pt4 - pt3; g[4] += 1;
-          if (u == u0) g[5] = wall_clock64();
-          g[6] = wall_clock64();
-        }
-#endif
       }
     };
     if (multi) {
@@ -597,16 +573,6 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
                               out, out_kind, large_ws, s);
 }
 
-#if CQ_PROBE
-extern "C" int cq_probe_read(long long* host, int n, int clear) {
-  if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_probe), (size_t)n * 8) != hipSuccess) return 1;
-  if (clear) {
-    static long long zeros[8 * 4096];
-    if (hipMemcpyToSymbol(HIP_SYMBOL(g_probe), zeros, sizeof(zeros)) != hipSuccess) return 1;
-  }
-  return 0;
-}
-#endif
 
 extern "C" size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, int M_total) {
   if (!W || W->G <= 0 || W->N <= 0 || W->K <= 0 || M_total <= 0) return 0;

@@ -19,10 +19,7 @@
 #include <type_traits>
 
 #include "cq_internal.h"
-
-#ifndef CQ_PROBE
-#define CQ_PROBE 0
-#endif
+#include "cq_decode.h"
 
 void cq_large_tile_caps(int G, int M_total, int* cap256, int* cap128);
 
@@ -44,8 +41,9 @@ struct LargeArgs {
   const int32_t* scale_gather; // sorted row -> entry of row_scale, or NULL
   void* out;
   int out_ld;
-  const int32_t* tiles;   // [cap][4]: group, first row (absolute sorted row), row count, unused
-  const int32_t* n_tiles; // number of entries in tiles
+  const int32_t* tiles;    // 256-token tiles [cap][4]: group, first row (absolute sorted row), row count, unused
+  const int32_t* tiles128; // 128-token tiles, same layout
+  const int32_t* n_tiles;  // [2]: number of entries in tiles, tiles128
   int row_tiles;          // N / 256
 };
 
@@ -54,63 +52,7 @@ __device__ __forceinline__ uint32_t f32_to_f16_sat(float x) {
   const _Float16 h = (_Float16)x;
   return (uint32_t) __builtin_bit_cast(uint16_t, h);
 }
-__device__ __forceinline__ uint32_t bf16_to_f16_bits(uint32_t b) {
-  const _Float16 h = (_Float16)__uint_as_float(b << 16);
-  return (uint32_t) __builtin_bit_cast(uint16_t, h);
-}
 __device__ __forceinline__ uint32_t code_bf16(int c) { return __float_as_uint((float)c) >> 16; }
-
-// Byte tables of one row's 16 centroids: lo[q] byte j = low byte of entry 4q+j, hi likewise.
-struct RowTable {
-  uint32_t lo[4], hi[4];
-};
-
-template <bool F16>
-__device__ __forceinline__ RowTable make_row_table(const uint16_t* crow) {
-  const uint4 c0 = reinterpret_cast<const uint4*>(crow)[0];
-  const uint4 c1 = reinterpret_cast<const uint4*>(crow)[1];
-  uint32_t p[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};  // p[i] = entries 2i (low half), 2i+1
-  if constexpr (F16) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) p[i] = bf16_to_f16_bits(p[i] & 0xffffu) | (bf16_to_f16_bits(p[i] >> 16) << 16);
-  }
-  RowTable t;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    // entries 4q..4q+3 live in p[2q] (4q, 4q+1) and p[2q+1] (4q+2, 4q+3)
-    t.lo[q] = __builtin_amdgcn_perm(p[2 * q + 1], p[2 * q], 0x06040200u);
-    t.hi[q] = __builtin_amdgcn_perm(p[2 * q + 1], p[2 * q], 0x07050301u);
-  }
-  return t;
-}
-
-// 8 packed indices (one dword, weight 2i in the low nibble of byte i) -> 4 dwords of 16-bit pairs
-__device__ __forceinline__ cq_v4u decode8(uint32_t d, const RowTable& t) {
-#if CQ_PROBE & 2
-  return cq_v4u{d, d ^ t.lo[0], d ^ t.hi[1], d ^ t.lo[2]};
-#endif
-  const uint32_t sA = d & 0x07070707u;                 // even weights: selector within a half table
-  const uint32_t sB = (d >> 4) & 0x07070707u;          // odd weights
-  // bit 3 of an index picks the upper half table: as a byte selector, byte i of the result comes from
-  // the lower-half candidate (source bytes 0-3) or the upper-half one (bytes 4-7)
-  const uint32_t mA = ((d >> 1) & 0x04040404u) | 0x03020100u;
-  const uint32_t mB = ((d >> 5) & 0x04040404u) | 0x03020100u;
-  const uint32_t loA0 = __builtin_amdgcn_perm(t.lo[1], t.lo[0], sA), loA1 = __builtin_amdgcn_perm(t.lo[3], t.lo[2], sA);
-  const uint32_t hiA0 = __builtin_amdgcn_perm(t.hi[1], t.hi[0], sA), hiA1 = __builtin_amdgcn_perm(t.hi[3], t.hi[2], sA);
-  const uint32_t loB0 = __builtin_amdgcn_perm(t.lo[1], t.lo[0], sB), loB1 = __builtin_amdgcn_perm(t.lo[3], t.lo[2], sB);
-  const uint32_t hiB0 = __builtin_amdgcn_perm(t.hi[1], t.hi[0], sB), hiB1 = __builtin_amdgcn_perm(t.hi[3], t.hi[2], sB);
-  const uint32_t loA = __builtin_amdgcn_perm(loA1, loA0, mA), hiA = __builtin_amdgcn_perm(hiA1, hiA0, mA);
-  const uint32_t loB = __builtin_amdgcn_perm(loB1, loB0, mB), hiB = __builtin_amdgcn_perm(hiB1, hiB0, mB);
-  // 16-bit values: xa01 = {even0, even1}, xa23 = {even2, even3}; same for the odd weights
-  const uint32_t xa01 = __builtin_amdgcn_perm(hiA, loA, 0x05010400u), xa23 = __builtin_amdgcn_perm(hiA, loA, 0x07030602u);
-  const uint32_t xb01 = __builtin_amdgcn_perm(hiB, loB, 0x05010400u), xb23 = __builtin_amdgcn_perm(hiB, loB, 0x07030602u);
-  cq_v4u o;
-  o[0] = __builtin_amdgcn_perm(xb01, xa01, 0x05040100u);  // weights 0,1
-  o[1] = __builtin_amdgcn_perm(xb01, xa01, 0x07060302u);  // weights 2,3
-  o[2] = __builtin_amdgcn_perm(xb23, xa23, 0x05040100u);  // weights 4,5
-  o[3] = __builtin_amdgcn_perm(xb23, xa23, 0x07060302u);  // weights 6,7
-  return o;
-}
 
 template <bool F16>
 __device__ __forceinline__ cq_v16f mfma_large(const cq_v4u a, const cq_v4u b, cq_v16f c) {
@@ -139,9 +81,7 @@ __device__ __forceinline__ void load_global_async(cq_v4u& dst, const uint8_t* sr
 #pragma clang diagnostic ignored "-Winline-asm"
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base uniform)
 __device__ __forceinline__ void load_global_to_lds(uint32_t lds_base, const uint8_t* src) {
-#if !(CQ_PROBE & 1)
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory", "m0");
-#endif
 }
 // wait until at most N of this wavefront's vector-memory loads are outstanding; the registers passed
 // through become usable only after it
@@ -165,30 +105,16 @@ constexpr int epilogue_row_stride(int epi, int outk) {
   return row + (quad == 16 ? 16 : 8);
 }
 
-// F16: the activations are f16 (else bf16); C = CT/32 token blocks per workgroup (8 or 4)
+// One tile: 256 weight rows (row tile rt) x up to 32*C tokens (rows mrow0 .. mrow0+mcnt-1 of group grp).
+// F16: the activations are f16 (else bf16); C = CT/32 token blocks (8 or 4).
 template <bool F16, int EPI, int OUTK, int C>
-__global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
+__device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, const int mrow0, const int mcnt,
+                                           const int rt) {
   constexpr int CT = 32 * C;
   constexpr uint32_t kBufBytes = CT * kStepBytes;  // one activation tile: CT tokens x 128 bytes
 
-  // ---- which tile: XCD-aware remap of the linear workgroup id (ids go round-robin over 8 XCDs) ----
-  // XCD x takes the contiguous share [x*per_xcd, (x+1)*per_xcd) of the real work items (the grid is
-  // sized for the worst case, the list is usually much shorter)
-  const int n_work = p.n_tiles[0] * p.row_tiles;
-  const int per_xcd = (n_work + 7) >> 3;
-  const int slot = blockIdx.x >> 3;
-  const int work = (blockIdx.x & 7) * per_xcd + slot;
-  if (slot >= per_xcd || work >= n_work) return;
-  const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
-  const int grp = p.tiles[tile * 4 + 0];
-  const int mrow0 = p.tiles[tile * 4 + 1];
-  const int mcnt = p.tiles[tile * 4 + 2];
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r32 = lane & 31, g2 = lane >> 5;
-#if CQ_PROBE & 16
-  const long long pt0 = clock64(), pw0 = wall_clock64();
-#endif
   const int N = p.N, K = p.K;
   const size_t rowbytes = (size_t)K >> 1;
   const int n0 = rt * kLargeRows + wave * 64;  // this wavefront's 64 rows
@@ -239,12 +165,8 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   };
   auto fetch_weights = [&](cq_v4u (&w)[2], int s) {
     const size_t o = (size_t)s * sstride;
-#if !(CQ_PROBE & 8)
     load_global_async(w[0], wp0 + o);
     load_global_async(w[1], wp1 + o);
-#else
-    w[0][0] += (uint32_t)o;
-#endif
   };
   // fragment read: lane (token r32 of block cb, k group g2) wants chunk g2*4 + jj of sub-step jj
   const uint32_t boff = (uint32_t)r32 * kStepBytes + ((uint32_t)((g2 * 4) ^ ((r32 >> 1) & 7)) << 4);
@@ -267,7 +189,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   // step s+1 already reads from it.  The barrier also retires tile s, which the requests of step s+1
   // overwrite.  Loads thus have two full steps (about 2 us) to arrive.
   // vector-memory loads a wavefront issues per step: the wait counts below depend on it
-  constexpr int kPerStep = ((CQ_PROBE & 1) ? 0 : C) + ((CQ_PROBE & 8) ? 0 : 2);
+  constexpr int kPerStep = C + 2;  // C tile loads + 2 weight loads
   cq_v4u wq[kNBuf][2];
   fetch_weights(wq[0], 0);
   fetch_tile(0, 0, 0, C);
@@ -291,9 +213,6 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
 #pragma unroll
   for (int cb = 0; cb < C; ++cb) bfr[cb] = read_b(0, 0, cb);
 
-#if CQ_PROBE & 16
-  const long long pt1 = clock64();
-#endif
   int s0 = 0;
   do {  // at least two steps exist (no zero-trip path: the accumulators stay in their AGPRs throughout)
 #pragma unroll
@@ -314,9 +233,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
           const cq_v4u b = bfr[cb];
           acc[0][cb] = mfma_large<F16>(af[cur][0], b, acc[0][cb]);
           acc[1][cb] = mfma_large<F16>(af[cur][1], b, acc[1][cb]);
-#if !(CQ_PROBE & 4)
           bfr[cb] = read_b(nbuf, njj, cb);
-#endif
         }
 #pragma unroll
         for (int i = 0; i < 2 * C; ++i) {
@@ -334,9 +251,6 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   // nothing of this workgroup may still be on its way into LDS when the workgroup ends
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-#if CQ_PROBE & 16
-  const long long pt2 = clock64();
-#endif
   // ---- epilogue: per-token scale, optional SiLU(gate)*up, store ----
   // A lane holds 4 consecutive outputs of ONE token per accumulator quad, so storing from registers
   // would touch 64 different cache lines per instruction.  Instead the tile goes through LDS (free
@@ -412,16 +326,31 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
       }
     }
   }
-#if CQ_PROBE & 16
-  __syncthreads();
-  if (tid == 0) {  // cycle counts of this workgroup, written over the start of the output (timing runs only)
-    long long* st = reinterpret_cast<long long*>(p.out) + (size_t)work * 4;
-    st[0] = pt1 - pt0;
-    st[1] = pt2 - pt1;
-    st[2] = clock64() - pt2;
-    st[3] = wall_clock64() - pw0;
+}
+
+// Work items = (token tile, row tile), 256-token tiles and 128-token tiles in ONE launch so that the
+// short list does not leave most of the chip idle.  XCD-aware remap of the linear workgroup id (ids go
+// round-robin over the 8 XCDs): XCD x takes a contiguous share of the 256-token work and then a
+// contiguous share of the 128-token work (neighbours share activations in its L2; equal mix on every
+// XCD).  The grid is sized for the worst case; the lists are usually much shorter.
+template <bool F16, int EPI, int OUTK>
+__global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
+  const int n256 = p.n_tiles[0] * p.row_tiles, n128 = p.n_tiles[1] * p.row_tiles;
+  const int per256 = (n256 + 7) >> 3, per128 = (n128 + 7) >> 3;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  if (slot < per256) {
+    const int work = xcd * per256 + slot;
+    if (work >= n256) return;
+    const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
+    const int32_t* t = p.tiles + tile * 4;
+    large_tile<F16, EPI, OUTK, 8>(p, t[0], t[1], t[2], rt);
+  } else if (slot < per256 + per128) {
+    const int work = xcd * per128 + (slot - per256);
+    if (work >= n128) return;
+    const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
+    const int32_t* t = p.tiles128 + tile * 4;
+    large_tile<F16, EPI, OUTK, 4>(p, t[0], t[1], t[2], rt);
   }
-#endif
 }
 
 // Pre-pass for activation kinds the main kernel does not read: sorted row m of the result is row
@@ -483,7 +412,8 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
     __syncthreads();
     if (tid == 0) {  // exclusive prefix in group order
       int s256 = base256, s128 = base128;
-      for (int i = 0; i < 1024; ++i) {
+      const int n = min(1024, G - g0);
+      for (int i = 0; i < n; ++i) {
         const int x = n256[i], y = n128[i];
         n256[i] = s256; n128[i] = s128;
         s256 += x; s128 += y;
@@ -512,10 +442,11 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
   if (tid == 0) { counts[0] = base256; counts[1] = base128; }
 }
 
-template <bool F16, int EPI, int OUTK, int C>
-cq_status launch_large(const LargeArgs& a, int max_tiles, hipStream_t s) {
-  auto kern = gemm_large_kernel<F16, EPI, OUTK, C>;
-  constexpr int lds_loop = kNBuf * 32 * C * kStepBytes, lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
+template <bool F16, int EPI, int OUTK>
+cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, const int32_t* counts, int max256,
+                      int max128, hipStream_t s) {
+  auto kern = gemm_large_kernel<F16, EPI, OUTK>;
+  constexpr int lds_loop = kNBuf * 256 * kStepBytes, lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
   static bool configured = false;
   if (!configured) {
@@ -527,22 +458,15 @@ cq_status launch_large(const LargeArgs& a, int max_tiles, hipStream_t s) {
       return CQ_ERR_HIP;
     configured = true;
   }
-  if (max_tiles <= 0) return CQ_OK;
-  const int grid = ((max_tiles * a.row_tiles + 7) / 8) * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a);
-  return cq_check_launch();
-}
-
-template <bool F16, int EPI, int OUTK>
-cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, const int32_t* counts, int max256,
-                      int max128, hipStream_t s) {
   a.tiles = t256;
+  a.tiles128 = t128;
   a.n_tiles = counts;
-  cq_status st = launch_large<F16, EPI, OUTK, 8>(a, max256, s);
-  if (st != CQ_OK) return st;
-  a.tiles = t128;
-  a.n_tiles = counts + 1;
-  return launch_large<F16, EPI, OUTK, 4>(a, max128, s);
+  // worst case of the kernel's per-XCD shares: ceil(n256/8) + ceil(n128/8) slots on each of 8 XCDs
+  const long w256 = (long)max256 * a.row_tiles, w128 = (long)max128 * a.row_tiles;
+  const long grid = ((w256 + 7) / 8 + (w128 + 7) / 8) * 8;
+  if (grid <= 0) return CQ_OK;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, a);
+  return cq_check_launch();
 }
 
 template <bool F16>
@@ -603,6 +527,7 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
   a.out = out;
   a.out_ld = epilogue == CQ_EPI_SWIGLU ? W->N / 2 : W->N;
   a.tiles = nullptr;
+  a.tiles128 = nullptr;
   a.n_tiles = nullptr;
   a.row_tiles = W->N / kLargeRows;
   if (a_kind == CQ_A_INT8_CODES || a_kind == CQ_A_F32) {
