@@ -172,6 +172,15 @@ def main():
         B.cq_stream_read(probe)
     torch.cuda.synchronize()
     read_gbps = probe.numel() * 10 / (time.perf_counter() - t0) / 1e9
+    # measured dense bf16 MFMA ceiling: bare matrix-core loop, 8 workgroups per CU
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    B.cq_mfma_loop(info["cu_count"] * 8, 200)
+    torch.cuda.synchronize()
+    e0.record()
+    mfma_flops = B.cq_mfma_loop(info["cu_count"] * 8, 2000)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_tflops = mfma_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
     # a plain copy of known size (1 GiB read + 1 GiB written): the yardstick the HBM counters of a
     # profiled run are scaled by
     dst = torch.empty_like(probe)
@@ -193,7 +202,8 @@ def main():
                           "frac_of_hbm_peak": (gu_bytes + dn_bytes) / (gu_s + dn_s) / 1e9 / HBM_PEAK_GBPS,
                           "measured_stream_read_GBps": read_gbps},
         "mfma": {"gate_up_plus_down_TFLOPs": (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12,
-                 "frac_of_bf16_peak": (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+                 "frac_of_bf16_peak": (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                 "measured_mfma_loop_TFLOPs": mfma_tflops},
         "device": info, "setup_s": t_gen,
     }
     if not args.no_cpu_baseline:

@@ -199,6 +199,12 @@ cq_status cq_device_info(int* cu_count, int* clock_khz, int* mem_clock_khz, int*
  * read ceiling next to the nominal one; the 16-byte XOR of everything read lands in sink[0..3]. */
 cq_status cq_stream_read(const void* src, size_t bytes, uint32_t* sink, cq_stream stream);
 
+/* Bare matrix-core loop used to measure the achievable dense bf16 MFMA ceiling next to the nominal
+ * one: `workgroups` workgroups of 4 wavefronts, each wavefront issuing iters x 16 independent
+ * v_mfma_f32_32x32x16_bf16 (32768 flops each) on register operands.  sink[workgroups * 256] f32
+ * receives one value per thread (keeps the loop alive).  Flops = workgroups * 4 * iters * 16 * 32768. */
+cq_status cq_mfma_loop(int workgroups, int iters, float* sink, cq_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = [
     "cq_route_permute_workspace_bytes", "cq_route_permute", "cq_grouped_gemm_workspace_bytes",
     "cq_codebook_grouped_gemm", "cq_combine", "cq_moe_workspace_bytes", "cq_moe_workspace_layout",
     "cq_moe_forward", "cq_moe_forward_timed", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
-    "cq_stream_read",
+    "cq_stream_read", "cq_mfma_loop",
 ]
 
 
@@ -98,6 +98,8 @@ def load_library() -> ctypes.CDLL:
     lib.cq_device_info.argtypes = [ctypes.POINTER(ci)] * 5
     lib.cq_stream_read.restype = ci
     lib.cq_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.cq_mfma_loop.restype = ci
+    lib.cq_mfma_loop.argtypes = [ci, ci, vp, vp]
     _lib = lib
     return lib
 
@@ -364,3 +366,12 @@ def cq_stream_read(buf):
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     _check(lib.cq_stream_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()))
     return sink
+
+
+def cq_mfma_loop(workgroups: int, iters: int):
+    """Launch the bare MFMA loop; returns its flop count (time it with events around the call)."""
+    torch = _torch()
+    lib = load_library()
+    sink = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    _check(lib.cq_mfma_loop(workgroups, iters, _ptr(sink), _stream()))
+    return workgroups * 4 * iters * 16 * 32768.0

@@ -71,6 +71,25 @@ __global__ __launch_bounds__(256) void decode_dense_kernel(const uint8_t* __rest
   }
 }
 
+// 16 independent accumulators per wavefront: the matrix pipe never waits for a result
+__global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, float* __restrict__ sink) {
+  cq_v16f acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  const cq_v4u av = {0x3f803f80u + threadIdx.x, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // ~1.0 in bf16 pairs
+  const cq_v8bf16 a = __builtin_bit_cast(cq_v8bf16, av);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, a, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += acc[i][i];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
                                                           uint32_t* __restrict__ sink) {
   uint4 acc = make_uint4(0u, 0u, 0u, 0u);
@@ -162,6 +181,13 @@ extern "C" cq_status cq_device_info(int* cu_count, int* clock_khz, int* mem_cloc
     if (e.dst) *e.dst = v;
   }
   return CQ_OK;
+}
+
+extern "C" cq_status cq_mfma_loop(int workgroups, int iters, float* sink, cq_stream stream) {
+  if (!sink) return CQ_ERR_NULL;
+  if (workgroups <= 0 || iters <= 0) return CQ_ERR_SHAPE;
+  hipLaunchKernelGGL(mfma_loop_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, iters, sink);
+  return cq_check_launch();
 }
 
 extern "C" cq_status cq_stream_read(const void* src, size_t bytes, uint32_t* sink, cq_stream stream) {

@@ -75,6 +75,7 @@ def test_argument_validation_happens_before_any_device_call():
     assert lib.cq_prepack(ctypes.byref(W), one, 8, None) == 4
     assert lib.cq_decode_dense(ctypes.byref(W), 5, one, None) == 2
     assert lib.cq_stream_read(one, 24, one, None) == 2
+    assert lib.cq_mfma_loop(8, 10, None, None) == 1 and lib.cq_mfma_loop(0, 10, one, None) == 2
 
 
 def test_workspace_sizes_are_pure_and_monotone():
