@@ -30,9 +30,13 @@
 
 namespace {
 
-constexpr int kSmallMaxRows = 32;     // one token block: beyond this the large-tile kernel is better
+#ifndef CQ_SMALL_MAX_ROWS
+#define CQ_SMALL_MAX_ROWS 32
+#endif
+constexpr int kSmallMaxRows = CQ_SMALL_MAX_ROWS;  // groups with more rows go to the large-tile kernel
 constexpr int kTableBytes = 65536;   // 256 entries x 64 row slots x 4 bytes
 constexpr int kSlabBytes = 65536;    // activation slab
+constexpr int kListedWorkgroups = 512;  // grid of a launch that runs off the device-built group list
 constexpr int kRedBytes = 32768;     // K partials of up to 16 token columns: 8 wavefronts x 32 registers x 32 lanes
 #ifndef CQ_GEMM_WAVES
 #define CQ_GEMM_WAVES 8
@@ -61,6 +65,10 @@ struct GemmArgs {
   int ksplit;               // number of K splits; > 1: scaled fp32 partial sums go to `partials`
   float* partials;          // [ksplit][M_total][N]
   size_t part_stride;       // M_total * N
+  // device-built work list (launches that also use the large-tile kernel), else NULL: blockIdx.y is
+  // the group and blockIdx.x * upw the first unit
+  const int32_t* small_hdr; // {number of listed groups, units per workgroup, workgroups per group}
+  const int32_t* small_ids; // the listed groups
 };
 
 __device__ __forceinline__ uint32_t f32_to_f16_bits_sat(float x) {
@@ -109,14 +117,25 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   float* redc = reinterpret_cast<float*>(lds + kTableBytes + kSlabBytes);  // kRedBytes: partials of <= 16 tokens
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int grp = blockIdx.y;
+  const int N = p.N, K = p.K;
+  const int nUnits = N >> 6;
+  int grp, u0, upw;
+  if (p.small_hdr) {
+    const int chunks = p.small_hdr[2];
+    if ((int)blockIdx.x >= p.small_hdr[0] * chunks) return;
+    const int gi = blockIdx.x / chunks;
+    grp = p.small_ids[gi];
+    upw = p.small_hdr[1];
+    u0 = (blockIdx.x - gi * chunks) * upw;
+  } else {
+    grp = blockIdx.y;
+    upw = p.upw;
+    u0 = blockIdx.x * upw;
+  }
   const int m0 = p.group_offsets[grp];
   const int Me = p.group_offsets[grp + 1] - m0;
   if (Me <= 0 || Me > p.max_rows) return;
-  const int N = p.N, K = p.K;
-  const int nUnits = N >> 6;
-  const int u0 = blockIdx.x * p.upw;
-  const int u1 = min(nUnits, u0 + p.upw);
+  const int u1 = min(nUnits, u0 + upw);
   if (u0 >= u1) return;
   const size_t rowbytes = (size_t)K >> 1;
   const uint8_t* gbase = p.idx + (size_t)grp * N * rowbytes;
@@ -446,8 +465,9 @@ cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
     configured = true;
   }
   const int n_units = a.N / 64;
-  hipLaunchKernelGGL(kern, dim3((n_units + a.upw - 1) / a.upw, G, a.ksplit), dim3(64 * kWaves),
-                     kTableBytes + kSlabBytes + kRedBytes, s, a);
+  const dim3 grid = a.small_hdr ? dim3(G > kListedWorkgroups ? G : kListedWorkgroups, 1, a.ksplit)
+                                : dim3((n_units + a.upw - 1) / a.upw, G, a.ksplit);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * kWaves), kTableBytes + kSlabBytes + kRedBytes, s, a);
   return cq_check_launch();
 }
 
@@ -544,7 +564,18 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   // the row count allows its 256-row tiles), which runs off a device-built tile list.
   const bool large = cq_gemm_large_supported(W) && M_total > kSmallMaxRows;
   a.max_rows = large ? kSmallMaxRows : 0x7fffffff;
+  a.small_hdr = nullptr;
+  a.small_ids = nullptr;
+  void* large_ws = (char*)workspace + cq_gemm_partials_bytes(W, M_total, epilogue);
   cq_status st;
+  if (large) {
+    // the host does not know which groups are small: a device-built list spreads exactly those over
+    // the grid (a grid over all groups would leave most workgroups without work)
+    st = cq_gemm_build_lists(W, group_offsets, M_total, kSmallMaxRows,
+                             W->G > kListedWorkgroups ? W->G : kListedWorkgroups, large_ws, &a.small_hdr,
+                             &a.small_ids, s);
+    if (st != CQ_OK) return st;
+  }
   switch (a_kind) {
     case CQ_A_INT8_CODES: st = dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s); break;
     case CQ_A_F16: st = dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s); break;
@@ -568,7 +599,6 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     }
   }
   if (!large) return st;
-  void* large_ws = (char*)workspace + cq_gemm_partials_bytes(W, M_total, epilogue);
   return cq_gemm_large_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, kSmallMaxRows, epilogue,
                               out, out_kind, large_ws, s);
 }

@@ -386,18 +386,23 @@ __global__ __launch_bounds__(256) void convert_rows_kernel(const void* __restric
 }
 
 // One workgroup: cut every group with more than `small_max` rows into token tiles of 256 (while more
-// than 128 rows remain) and 128, in group order (deterministic).  lists: [0] = 256-wide, [1] = 128-wide.
+// than 128 rows remain) and 128, in group order (deterministic), and list the non-empty groups with up
+// to `small_max` rows for the streaming kernel, together with a split of their 64-row units over
+// `small_wgs` workgroups.  counts: [0] 256-wide tiles, [1] 128-wide tiles, [2] small groups,
+// [3] units per workgroup, [4] workgroups per small group.
 __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __restrict__ offsets, int G, int small_max,
+                                                           int n_units, int small_wgs,
                                                            int32_t* __restrict__ tiles256, int32_t* __restrict__ tiles128,
+                                                           int32_t* __restrict__ small_groups,
                                                            int32_t* __restrict__ counts) {
-  __shared__ int n256[1024], n128[1024];
-  __shared__ int base256, base128;
+  __shared__ int n256[1024], n128[1024], nsm[1024];
+  __shared__ int base256, base128, basesm;
   const int tid = threadIdx.x;
-  if (tid == 0) { base256 = 0; base128 = 0; }
+  if (tid == 0) { base256 = 0; base128 = 0; basesm = 0; }
   __syncthreads();
   for (int g0 = 0; g0 < G; g0 += 1024) {
     const int g = g0 + tid;
-    int a = 0, b = 0, m0 = 0, me = 0;
+    int a = 0, b = 0, c = 0, m0 = 0, me = 0;
     if (g < G) {
       m0 = offsets[g];
       me = offsets[g + 1] - m0;
@@ -405,20 +410,23 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
         a = me / 256;
         const int rem = me - a * 256;
         if (rem > 128) ++a; else if (rem > 0) b = 1;
+      } else if (me > 0) {
+        c = 1;
       }
     }
     n256[tid] = a;
     n128[tid] = b;
+    nsm[tid] = c;
     __syncthreads();
     if (tid == 0) {  // exclusive prefix in group order
-      int s256 = base256, s128 = base128;
+      int s256 = base256, s128 = base128, ssm = basesm;
       const int n = min(1024, G - g0);
       for (int i = 0; i < n; ++i) {
-        const int x = n256[i], y = n128[i];
-        n256[i] = s256; n128[i] = s128;
-        s256 += x; s128 += y;
+        const int x = n256[i], y = n128[i], z = nsm[i];
+        n256[i] = s256; n128[i] = s128; nsm[i] = ssm;
+        s256 += x; s128 += y; ssm += z;
       }
-      base256 = s256; base128 = s128;
+      base256 = s256; base128 = s128; basesm = ssm;
     }
     __syncthreads();
     if (g < G && me > small_max) {
@@ -437,9 +445,23 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
         tiles128[at2 * 4 + 3] = 0;
       }
     }
+    if (c) small_groups[nsm[tid]] = g;
     __syncthreads();
   }
-  if (tid == 0) { counts[0] = base256; counts[1] = base128; }
+  if (tid == 0) {
+    counts[0] = base256;
+    counts[1] = base128;
+    counts[2] = basesm;
+    // fewest units per workgroup such that all small groups fit into small_wgs workgroups
+    int upw = 1, chunks = n_units;
+    if (basesm > 0) {
+      const int per_group = max(1, small_wgs / basesm);       // workgroups a group may take
+      upw = (n_units + per_group - 1) / per_group;
+      chunks = (n_units + upw - 1) / upw;
+    }
+    counts[3] = upw;
+    counts[4] = chunks;
+  }
 }
 
 template <bool F16, int EPI, int OUTK>
@@ -482,7 +504,7 @@ cq_status dispatch_large(const LargeArgs& a, int epilogue, int out_kind, const i
 size_t tile_list_bytes(int G, int M_total) {
   int c256, c128;
   cq_large_tile_caps(G, M_total, &c256, &c128);
-  return cq_align_up(256 + (size_t)(c256 + c128) * 4 * sizeof(int32_t), 256);
+  return cq_align_up(256 + ((size_t)(c256 + c128) * 4 + (size_t)G) * sizeof(int32_t), 256);
 }
 
 }  // namespace
@@ -505,6 +527,26 @@ bool cq_gemm_large_supported(const cq_codebook_weights* W) {
   return W->N % kLargeRows == 0 && W->K % (2 * kStepK) == 0;
 }
 
+// Builds the work lists of both kernels in `workspace` (first step of a mixed launch).  Returns the list
+// of small groups for the streaming kernel: header {count, units per workgroup, workgroups per group,
+// unused} followed by the group ids... as two pointers: *small_hdr -> counts + 2, *small_ids -> ids.
+cq_status cq_gemm_build_lists(const cq_codebook_weights* W, const int32_t* group_offsets, int M_total, int small_max,
+                              int small_wgs, void* workspace, const int32_t** small_hdr, const int32_t** small_ids,
+                              hipStream_t s) {
+  int cap256, cap128;
+  cq_large_tile_caps(W->G, M_total, &cap256, &cap128);
+  int32_t* counts = (int32_t*)workspace;
+  int32_t* t256 = counts + 64;
+  int32_t* t128 = t256 + (size_t)cap256 * 4;
+  int32_t* small = t128 + (size_t)cap128 * 4;
+  hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, s, group_offsets, W->G, small_max, W->N / 64, small_wgs,
+                     t256, t128, small, counts);
+  *small_hdr = counts + 2;
+  *small_ids = small;
+  return cq_check_launch();
+}
+
+// the lists must have been built by cq_gemm_build_lists in the same workspace
 cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                                const int32_t* row_gather, const int32_t* group_offsets, int M_total, int small_max,
                                int epilogue, void* out, int out_kind, void* workspace, hipStream_t s) {
@@ -513,7 +555,6 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
   int32_t* counts = (int32_t*)workspace;
   int32_t* t256 = counts + 64;
   int32_t* t128 = t256 + (size_t)cap256 * 4;
-  hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, s, group_offsets, W->G, small_max, t256, t128, counts);
   LargeArgs a;
   a.idx = W->prepacked ? (const uint8_t*)W->prepacked : W->idx;
   a.cent = W->cent;

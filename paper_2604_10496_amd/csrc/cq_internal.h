@@ -66,6 +66,11 @@ bool cq_gemm_large_supported(const cq_codebook_weights* W);
 // with_conversion: include room for a 16-bit copy of the activation rows (needed for CQ_A_INT8_CODES
 // and CQ_A_F32 operands; bf16 / f16 operands are read in place)
 size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion);
+// work lists of a launch that uses both kernels (device-built: group sizes are device data); small_hdr:
+// {number of small groups, 64-row units per workgroup, workgroups per small group}, small_ids: their ids
+cq_status cq_gemm_build_lists(const cq_codebook_weights* W, const int32_t* group_offsets, int M_total, int small_max,
+                              int small_wgs, void* workspace, const int32_t** small_hdr, const int32_t** small_ids,
+                              hipStream_t s);
 cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                                const int32_t* row_gather, const int32_t* group_offsets, int M_total, int small_max,
                                int epilogue, void* out, int out_kind, void* workspace, hipStream_t s);
