@@ -43,7 +43,8 @@ struct LargeArgs {
   int out_ld;
   const int32_t* tiles;    // 256-token tiles [cap][4]: group, first row (absolute sorted row), row count, unused
   const int32_t* tiles128; // 128-token tiles, same layout
-  const int32_t* n_tiles;  // [2]: number of entries in tiles, tiles128
+  const int32_t* tiles64;  // 64-token tiles, same layout
+  const int32_t* n_tiles;  // the builder's counts: [0] entries in tiles, [1] in tiles128, [5] in tiles64
   int row_tiles;          // N / 256
 };
 
@@ -223,7 +224,9 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int cur = jj & 1, nxt = cur ^ 1;
-        fetch_tile(s3, (par + 3) & 3, jj * (C / 4), C / 4);  // spread over the step: no LDS write bursts
+        // the C tile loads are spread over the step: no LDS write bursts
+        if constexpr (C >= 4) fetch_tile(s3, (par + 3) & 3, jj * (C / 4), C / 4);
+        else if (jj < C) fetch_tile(s3, (par + 3) & 3, jj, 1);
         // next sub-step: jj + 1 of this step, or the first one of the next step
         const int nbuf = jj < 3 ? par : (par + 1) & 3, njj = (jj + 1) & 3;
         af[nxt][0] = decode8(wq[nbuf][0][njj], t0);
@@ -328,28 +331,41 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   }
 }
 
-// Work items = (token tile, row tile), 256-token tiles and 128-token tiles in ONE launch so that the
-// short list does not leave most of the chip idle.  XCD-aware remap of the linear workgroup id (ids go
+// Work items = (token tile, row tile); tiles of 256, 128 and 64 tokens in ONE launch so that the
+// short lists do not leave most of the chip idle.  XCD-aware remap of the linear workgroup id (ids go
 // round-robin over the 8 XCDs): XCD x takes a contiguous share of the 256-token work and then a
-// contiguous share of the 128-token work (neighbours share activations in its L2; equal mix on every
-// XCD).  The grid is sized for the worst case; the lists are usually much shorter.
+// contiguous share of the 128-token and of the 64-token work (neighbours share activations in its L2;
+// equal mix on every XCD).  The grid is sized for the worst case; the lists are usually much shorter.
 template <bool F16, int EPI, int OUTK>
 __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
-  const int n256 = p.n_tiles[0] * p.row_tiles, n128 = p.n_tiles[1] * p.row_tiles;
-  const int per256 = (n256 + 7) >> 3, per128 = (n128 + 7) >> 3;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int n256 = p.n_tiles[0] * p.row_tiles, n128 = p.n_tiles[1] * p.row_tiles, n64 = p.n_tiles[5] * p.row_tiles;
+  const int per256 = (n256 + 7) >> 3, per128 = (n128 + 7) >> 3, per64 = (n64 + 7) >> 3;
+  const int xcd = blockIdx.x & 7;
+  int slot = blockIdx.x >> 3;
   if (slot < per256) {
     const int work = xcd * per256 + slot;
     if (work >= n256) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles + tile * 4;
     large_tile<F16, EPI, OUTK, 8>(p, t[0], t[1], t[2], rt);
-  } else if (slot < per256 + per128) {
-    const int work = xcd * per128 + (slot - per256);
+    return;
+  }
+  slot -= per256;
+  if (slot < per128) {
+    const int work = xcd * per128 + slot;
     if (work >= n128) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles128 + tile * 4;
     large_tile<F16, EPI, OUTK, 4>(p, t[0], t[1], t[2], rt);
+    return;
+  }
+  slot -= per128;
+  if (slot < per64) {
+    const int work = xcd * per64 + slot;
+    if (work >= n64) return;
+    const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
+    const int32_t* t = p.tiles64 + tile * 4;
+    large_tile<F16, EPI, OUTK, 2>(p, t[0], t[1], t[2], rt);
   }
 }
 
@@ -386,47 +402,49 @@ __global__ __launch_bounds__(256) void convert_rows_kernel(const void* __restric
 }
 
 // One workgroup: cut every group with more than `small_max` rows into token tiles of 256 (while more
-// than 128 rows remain) and 128, in group order (deterministic), and list the non-empty groups with up
+// than 128 rows remain), then one of 128 or (up to 64 rows left) 64, in group order (deterministic), and list the non-empty groups with up
 // to `small_max` rows for the streaming kernel, together with a split of their 64-row units over
 // `small_wgs` workgroups.  counts: [0] 256-wide tiles, [1] 128-wide tiles, [2] small groups,
-// [3] units per workgroup, [4] workgroups per small group.
+// [3] units per workgroup, [4] workgroups per small group, [5] 64-wide tiles.
 __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __restrict__ offsets, int G, int small_max,
                                                            int n_units, int small_wgs,
                                                            int32_t* __restrict__ tiles256, int32_t* __restrict__ tiles128,
+                                                           int32_t* __restrict__ tiles64,
                                                            int32_t* __restrict__ small_groups,
                                                            int32_t* __restrict__ counts) {
-  __shared__ int n256[1024], n128[1024], nsm[1024];
-  __shared__ int base256, base128, basesm;
+  __shared__ int n256[1024], n128[1024], n64[1024], nsm[1024];
+  __shared__ int base256, base128, base64, basesm;
   const int tid = threadIdx.x;
-  if (tid == 0) { base256 = 0; base128 = 0; basesm = 0; }
+  if (tid == 0) { base256 = 0; base128 = 0; base64 = 0; basesm = 0; }
   __syncthreads();
   for (int g0 = 0; g0 < G; g0 += 1024) {
     const int g = g0 + tid;
-    int a = 0, b = 0, c = 0, m0 = 0, me = 0;
+    int a = 0, b = 0, b64 = 0, c = 0, m0 = 0, me = 0;
     if (g < G) {
       m0 = offsets[g];
       me = offsets[g + 1] - m0;
       if (me > small_max) {
         a = me / 256;
         const int rem = me - a * 256;
-        if (rem > 128) ++a; else if (rem > 0) b = 1;
+        if (rem > 128) ++a; else if (rem > 64) b = 1; else if (rem > 0) b64 = 1;
       } else if (me > 0) {
         c = 1;
       }
     }
     n256[tid] = a;
     n128[tid] = b;
+    n64[tid] = b64;
     nsm[tid] = c;
     __syncthreads();
     if (tid == 0) {  // exclusive prefix in group order
-      int s256 = base256, s128 = base128, ssm = basesm;
+      int s256 = base256, s128 = base128, s64 = base64, ssm = basesm;
       const int n = min(1024, G - g0);
       for (int i = 0; i < n; ++i) {
-        const int x = n256[i], y = n128[i], z = nsm[i];
-        n256[i] = s256; n128[i] = s128; nsm[i] = ssm;
-        s256 += x; s128 += y; ssm += z;
+        const int x = n256[i], y = n128[i], y2 = n64[i], z = nsm[i];
+        n256[i] = s256; n128[i] = s128; n64[i] = s64; nsm[i] = ssm;
+        s256 += x; s128 += y; s64 += y2; ssm += z;
       }
-      base256 = s256; base128 = s128; basesm = ssm;
+      base256 = s256; base128 = s128; base64 = s64; basesm = ssm;
     }
     __syncthreads();
     if (g < G && me > small_max) {
@@ -437,12 +455,12 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
         tiles256[(at + i) * 4 + 2] = min(256, me - i * 256);
         tiles256[(at + i) * 4 + 3] = 0;
       }
-      if (b) {
-        const int at2 = n128[tid];
-        tiles128[at2 * 4 + 0] = g;
-        tiles128[at2 * 4 + 1] = m0 + a * 256;
-        tiles128[at2 * 4 + 2] = me - a * 256;
-        tiles128[at2 * 4 + 3] = 0;
+      if (b || b64) {
+        int32_t* t = b ? tiles128 + n128[tid] * 4 : tiles64 + n64[tid] * 4;
+        t[0] = g;
+        t[1] = m0 + a * 256;
+        t[2] = me - a * 256;
+        t[3] = 0;
       }
     }
     if (c) small_groups[nsm[tid]] = g;
@@ -452,6 +470,7 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
     counts[0] = base256;
     counts[1] = base128;
     counts[2] = basesm;
+    counts[5] = base64;
     // fewest units per workgroup such that all small groups fit into small_wgs workgroups
     int upw = 1, chunks = n_units;
     if (basesm > 0) {
@@ -482,10 +501,12 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
   }
   a.tiles = t256;
   a.tiles128 = t128;
+  a.tiles64 = t128 + (size_t)max128 * 4;
   a.n_tiles = counts;
-  // worst case of the kernel's per-XCD shares: ceil(n256/8) + ceil(n128/8) slots on each of 8 XCDs
+  // worst case of the kernel's per-XCD shares (a group ends in at most one 128- or 64-token tile, but the
+  // two lists round up separately): ceil(n256/8) + ceil(n128/8) + ceil(n64/8) slots on each of 8 XCDs
   const long w256 = (long)max256 * a.row_tiles, w128 = (long)max128 * a.row_tiles;
-  const long grid = ((w256 + 7) / 8 + (w128 + 7) / 8) * 8;
+  const long grid = ((w256 + 7) / 8 + (w128 + 7) / 8 + 1) * 8;
   if (grid <= 0) return CQ_OK;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, a);
   return cq_check_launch();
@@ -504,7 +525,7 @@ cq_status dispatch_large(const LargeArgs& a, int epilogue, int out_kind, const i
 size_t tile_list_bytes(int G, int M_total) {
   int c256, c128;
   cq_large_tile_caps(G, M_total, &c256, &c128);
-  return cq_align_up(256 + ((size_t)(c256 + c128) * 4 + (size_t)G) * sizeof(int32_t), 256);
+  return cq_align_up(256 + ((size_t)(c256 + 2 * c128) * 4 + (size_t)G) * sizeof(int32_t), 256);
 }
 
 }  // namespace
@@ -538,9 +559,10 @@ cq_status cq_gemm_build_lists(const cq_codebook_weights* W, const int32_t* group
   int32_t* counts = (int32_t*)workspace;
   int32_t* t256 = counts + 64;
   int32_t* t128 = t256 + (size_t)cap256 * 4;
-  int32_t* small = t128 + (size_t)cap128 * 4;
+  int32_t* t64 = t128 + (size_t)cap128 * 4;
+  int32_t* small = t64 + (size_t)cap128 * 4;
   hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, s, group_offsets, W->G, small_max, W->N / 64, small_wgs,
-                     t256, t128, small, counts);
+                     t256, t128, t64, small, counts);
   *small_hdr = counts + 2;
   *small_ids = small;
   return cq_check_launch();
@@ -569,6 +591,7 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
   a.out_ld = epilogue == CQ_EPI_SWIGLU ? W->N / 2 : W->N;
   a.tiles = nullptr;
   a.tiles128 = nullptr;
+  a.tiles64 = nullptr;
   a.n_tiles = nullptr;
   a.row_tiles = W->N / kLargeRows;
   if (a_kind == CQ_A_INT8_CODES || a_kind == CQ_A_F32) {
