@@ -28,7 +28,7 @@ namespace {
 constexpr int kLargeRows = 256;  // weight rows per workgroup
 constexpr int kStepK = 64;       // K per pipeline step
 constexpr int kStepBytes = kStepK * 2;  // one token's share of a step in LDS and in global memory
-constexpr int kNBuf = 4;         // activation tiles in LDS
+constexpr int kLdsTileBytes = 4 * 256 * kStepBytes;  // activation tile rings: 4 x 256, 8 x 128 or 8 x 64 tokens
 
 struct LargeArgs {
   const uint8_t* idx;
@@ -107,8 +107,9 @@ constexpr int epilogue_row_stride(int epi, int outk) {
 }
 
 // One tile: 256 weight rows (row tile rt) x up to 32*C tokens (rows mrow0 .. mrow0+mcnt-1 of group grp).
-// F16: the activations are f16 (else bf16); C = CT/32 token blocks (8 or 4).
-template <bool F16, int EPI, int OUTK, int C>
+// F16: the activations are f16 (else bf16); C = CT/32 token blocks (8, 4 or 2); D = depth of the load
+// pipeline in K steps (a power of two; narrow tiles spend less matrix time per step and need more).
+template <bool F16, int EPI, int OUTK, int C, int D>
 __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, const int mrow0, const int mcnt,
                                            const int rt) {
   constexpr int CT = 32 * C;
@@ -183,22 +184,23 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
 
-  // Pipeline: at the start of step s the weights and the activation tile of step s+3 are requested
-  // (weights: ring of four register pairs; tiles: ring of four LDS buffers, tile s in buffer s%4).
-  // At the end of step s every wavefront waits for its own share of tile s+2 (the C+2 loads requested
-  // during step s may stay in flight), then the workgroup barrier publishes it; the last sub-step of
-  // step s+1 already reads from it.  The barrier also retires tile s, which the requests of step s+1
-  // overwrite.  Loads thus have two full steps (about 2 us) to arrive.
+  // Pipeline: at the start of step s the weights and the activation tile of step s+D-1 are requested
+  // (weights: ring of D register pairs; tiles: ring of D LDS buffers, tile s in buffer s%D).  At the
+  // end of step s every wavefront waits for its own share of tile s+2 (the loads of the D-3 steps
+  // requested after it may stay in flight), then the workgroup barrier publishes it; the last sub-step
+  // of step s+1 already reads from it.  The barrier also retires tile s, which the requests of step
+  // s+1 overwrite.  Loads thus have D-2 full steps to arrive (two steps = about 2 us for 256 tokens).
   // vector-memory loads a wavefront issues per step: the wait counts below depend on it
   constexpr int kPerStep = C + 2;  // C tile loads + 2 weight loads
-  cq_v4u wq[kNBuf][2];
-  fetch_weights(wq[0], 0);
-  fetch_tile(0, 0, 0, C);
-  fetch_weights(wq[1], min(1, nS - 1));
-  fetch_tile(min(1, nS - 1), 1, 0, C);
-  fetch_weights(wq[2], min(2, nS - 1));
-  fetch_tile(min(2, nS - 1), 2, 0, C);
-  vm_wait<kPerStep>(wq[0][0], wq[0][1], wq[1][0], wq[1][1]);
+  constexpr int kInFlight = (D - 3) * kPerStep;
+  static_assert(D >= 4 && (D & (D - 1)) == 0 && kInFlight < 64, "ring depth / vmcnt range");
+  cq_v4u wq[D][2];
+#pragma unroll
+  for (int i = 0; i < D - 1; ++i) {
+    fetch_weights(wq[i], min(i, nS - 1));
+    fetch_tile(min(i, nS - 1), i, 0, C);
+  }
+  vm_wait<kInFlight>(wq[0][0], wq[0][1], wq[1][0], wq[1][1]);
   __syncthreads();
 
   // Software pipeline over the 16-wide K sub-steps.  While the matrix cores work through the 2*C MFMAs
@@ -217,18 +219,18 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   int s0 = 0;
   do {  // at least two steps exist (no zero-trip path: the accumulators stay in their AGPRs throughout)
 #pragma unroll
-    for (int par = 0; par < 4; ++par) {  // step s0 + par uses weights wq[par] and tile buffer par
-      if (par == 2 && s0 + 2 >= nS) break;  // K is a multiple of 128: steps come in pairs
-      const int s3 = min(s0 + par + 3, nS - 1);
-      fetch_weights(wq[(par + 3) & 3], s3);
+    for (int par = 0; par < D; ++par) {  // step s0 + par uses weights wq[par] and tile buffer par
+      if (par > 0 && (par & 1) == 0 && s0 + par >= nS) break;  // K is a multiple of 128: steps come in pairs
+      const int s3 = min(s0 + par + D - 1, nS - 1);
+      fetch_weights(wq[(par + D - 1) & (D - 1)], s3);
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int cur = jj & 1, nxt = cur ^ 1;
         // the C tile loads are spread over the step: no LDS write bursts
-        if constexpr (C >= 4) fetch_tile(s3, (par + 3) & 3, jj * (C / 4), C / 4);
-        else if (jj < C) fetch_tile(s3, (par + 3) & 3, jj, 1);
+        if constexpr (C >= 4) fetch_tile(s3, (par + D - 1) & (D - 1), jj * (C / 4), C / 4);
+        else if (jj < C) fetch_tile(s3, (par + D - 1) & (D - 1), jj, 1);
         // next sub-step: jj + 1 of this step, or the first one of the next step
-        const int nbuf = jj < 3 ? par : (par + 1) & 3, njj = (jj + 1) & 3;
+        const int nbuf = jj < 3 ? par : (par + 1) & (D - 1), njj = (jj + 1) & 3;
         af[nxt][0] = decode8(wq[nbuf][0][njj], t0);
         af[nxt][1] = decode8(wq[nbuf][1][njj], t1);
 #pragma unroll
@@ -246,10 +248,10 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      vm_wait<kPerStep>(wq[(par + 2) & 3][0], wq[(par + 2) & 3][1]);
+      vm_wait<kInFlight>(wq[(par + 2) & (D - 1)][0], wq[(par + 2) & (D - 1)][1]);
       __syncthreads();
     }
-    s0 += 4;
+    s0 += D;
   } while (s0 < nS);
   // nothing of this workgroup may still be on its way into LDS when the workgroup ends
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -347,7 +349,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n256) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles + tile * 4;
-    large_tile<F16, EPI, OUTK, 8>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 8, 4>(p, t[0], t[1], t[2], rt);
     return;
   }
   slot -= per256;
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n128) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles128 + tile * 4;
-    large_tile<F16, EPI, OUTK, 4>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 4, 8>(p, t[0], t[1], t[2], rt);
     return;
   }
   slot -= per128;
@@ -365,7 +367,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n64) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles64 + tile * 4;
-    large_tile<F16, EPI, OUTK, 2>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 2, 8>(p, t[0], t[1], t[2], rt);
   }
 }
 
@@ -487,7 +489,7 @@ template <bool F16, int EPI, int OUTK>
 cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, const int32_t* counts, int max256,
                       int max128, hipStream_t s) {
   auto kern = gemm_large_kernel<F16, EPI, OUTK>;
-  constexpr int lds_loop = kNBuf * 256 * kStepBytes, lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
+  constexpr int lds_loop = kLdsTileBytes, lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
   static bool configured = false;
   if (!configured) {
