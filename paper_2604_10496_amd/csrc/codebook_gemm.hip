@@ -291,6 +291,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         cq_v16f acc0, acc1;
 #pragma unroll
         for (int i = 0; i < 16; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
+        uint4 bf = make_uint4(0u, 0u, 0u, 0u);  // B operand; lanes of padding columns stay zero
 
         // Ring loads are issued unconditionally (address clamped to step 0 when the step does not exist)
         // so that the number of loads in flight is the same on every path and the wait before a slot
@@ -344,7 +345,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
               const uint4* bsrc = slab + (size_t)(ls * 8 + g2 * 4) * Mpad + tj;
 #pragma unroll
               for (int jj = 0; jj < 4; ++jj) {
-                const uint4 bf = bsrc[(size_t)jj * Mpad];
+                // only the lanes of real token columns fetch their fragment (the others keep zeros)
+                if (r32 < Mpad) bf = bsrc[(size_t)jj * Mpad];
                 cq_v4u a0, a1;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
