@@ -619,7 +619,7 @@ extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, cons
                                               const int32_t* group_offsets, int M_total, int epilogue, void* out,
                                               int out_kind, void* workspace, size_t workspace_bytes,
                                               cq_stream stream) {
-  if (!W || !A || !group_offsets || !out) return CQ_ERR_NULL;
+  if (!W || !A || !group_offsets || (!out && M_total > 0)) return CQ_ERR_NULL;
   if ((!W->idx && !W->prepacked) || !W->cent) return CQ_ERR_NULL;
   if (W->G <= 0 || W->N <= 0 || W->K <= 0 || M_total < 0) return CQ_ERR_SHAPE;
   if (W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;

@@ -148,6 +148,45 @@ def test_route_exact_ties_and_empty_experts(B):
     assert np.allclose(got["w"].cpu().numpy().sum(axis=1), 1.0, atol=1e-6)
 
 
+@pytest.mark.parametrize("T,E,k", [(3, 1024, 64), (1, 1, 1), (257, 1024, 1), (40, 64, 64)])
+def test_route_limits(B, T, E, k):
+    """The documented limits of the entry point: E up to 1024, top_k up to min(E, 64), a single token,
+    a single expert; all logits equal in one row (every tie goes to the lower expert id)."""
+    rng = np.random.default_rng(13 + T + E)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[0, :] = 0.5
+    ids, w = O.route_topk(logits, k)
+    off, perm, inv = O.permute_by_expert(ids, E)
+    got = B.cq_route_permute(None, None, None, k, logits_in=_dev(logits))
+    _check_routing(got, ids, w, off, perm, inv, T, k, 0)
+    assert np.array_equal(got["ids"].cpu().numpy()[0], np.arange(k))
+
+
+def test_gemm_degenerate_launches(B):
+    """No rows at all, and groups that are all empty: nothing is written, CQ_OK is returned."""
+    rng = np.random.default_rng(17)
+    G, N, K = 3, 128, 256
+    idx, cent = _rand_weights(rng, G, N, K)
+    W = B.DeviceCodebook(idx, cent)
+    codes = rng.integers(-7, 8, size=(4, K)).astype(np.int8)
+    out = B.cq_codebook_grouped_gemm(W, _dev(codes), B.CQ_A_INT8_CODES, None, None, _dev(np.zeros(G + 1, np.int32)), 0,
+                                     B.CQ_EPI_NONE, B.CQ_OUT_F32)
+    assert out.shape[0] == 0
+    # all four rows in the last group, the others empty
+    off = np.array([0, 0, 0, 4], dtype=np.int32)
+    out = B.cq_codebook_grouped_gemm(W, _dev(codes), B.CQ_A_INT8_CODES, None, None, _dev(off), 4, B.CQ_EPI_NONE,
+                                     B.CQ_OUT_F32).cpu().numpy()
+    ref = O.codebook_matmul(codes.astype(np.float64), idx[2], cent[2])
+    assert Hp.row_rel_l2(out, ref).max() < 1e-6
+
+
+def test_mfma_loop_hook_runs(B):
+    import torch
+    flops = B.cq_mfma_loop(64, 10)
+    torch.cuda.synchronize()
+    assert flops == 64 * 4 * 10 * 16 * 32768.0
+
+
 # ---------------------------------------------------------------------------------------------
 # codebook grouped GEMM
 # ---------------------------------------------------------------------------------------------
