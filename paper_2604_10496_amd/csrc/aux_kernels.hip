@@ -10,28 +10,31 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
                                                       const float* __restrict__ w,
                                                       const int32_t* __restrict__ inv_perm, int T, int H, int k,
                                                       int S, float* __restrict__ Y) {
+  // one thread per (token, 4 columns): blockIdx.x = token, blockIdx.y = block of 1024 columns
   const int t = blockIdx.x;
-  auto row_of = [&](size_t row, int c) {
-    float4 o = *reinterpret_cast<const float4*>(O + row * H + c);
+  const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (c >= H) return;
+  auto row_of = [&](size_t row) {
+    const float* src = O + row * H + c;
+    float4 o = *reinterpret_cast<const float4*>(src);
+#pragma unroll 4
     for (int q = 1; q < slices; ++q) {
-      const float4 v = *reinterpret_cast<const float4*>(O + (size_t)q * slice_stride + row * H + c);
+      const float4 v = *reinterpret_cast<const float4*>(src + (size_t)q * slice_stride);
       o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
     }
     return o;
   };
-  for (int c = threadIdx.x * 4; c < H; c += 256 * 4) {
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j = 0; j < k; ++j) {
-      const float wt = w[(size_t)t * k + j];
-      const float4 o = row_of((size_t)inv_perm[(size_t)t * k + j], c);
-      acc.x += wt * o.x; acc.y += wt * o.y; acc.z += wt * o.z; acc.w += wt * o.w;
-    }
-    for (int s = 0; s < S; ++s) {
-      const float4 o = row_of((size_t)T * k + (size_t)s * T + t, c);
-      acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
-    }
-    *reinterpret_cast<float4*>(Y + (size_t)t * H + c) = acc;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int j = 0; j < k; ++j) {
+    const float wt = w[(size_t)t * k + j];
+    const float4 o = row_of((size_t)inv_perm[(size_t)t * k + j]);
+    acc.x += wt * o.x; acc.y += wt * o.y; acc.z += wt * o.z; acc.w += wt * o.w;
   }
+  for (int s = 0; s < S; ++s) {
+    const float4 o = row_of((size_t)T * k + (size_t)s * T + t);
+    acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+  }
+  *reinterpret_cast<float4*>(Y + (size_t)t * H + c) = acc;
 }
 
 // canonical [rows, K/2] -> tiles of 32 rows x 64 weights (1 KiB): lane l of a tile owns the 16 bytes
@@ -126,8 +129,8 @@ extern "C" const char* cq_status_string(cq_status st) {
 
 cq_status cq_combine_launch(const float* O, int slices, size_t slice_stride, const float* topk_w,
                             const int32_t* inv_perm, int T, int H, int top_k, int n_shared, float* Y, hipStream_t s) {
-  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, O, slices, slice_stride, topk_w, inv_perm, T, H, top_k,
-                     n_shared, Y);
+  hipLaunchKernelGGL(combine_kernel, dim3(T, (H + 1023) / 1024), dim3(256), 0, s, O, slices, slice_stride, topk_w,
+                     inv_perm, T, H, top_k, n_shared, Y);
   return cq_check_launch();
 }
 

@@ -182,37 +182,58 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
       const int m = m0 + 32 * tb + st;
       srow = (p.row_gather ? (size_t)p.row_gather[m] : (size_t)m) * K;
     }
+    // Four chunks per pass, all loads issued before the first conversion (unconditional, clamped to the
+    // last chunk; rows of padding tokens read row 0 and store zeros): one memory latency per pass
+    // instead of one per chunk.
     auto stage = [&](int sl) {
       const int k0 = sl * KSfull;
       const int nC = min(KSfull, Kl - k0) >> 3;
-      for (int c = sc0; c < nC; c += cstep) {
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (svalid) {
-          const size_t e0 = srow + (size_t)sb * 64 + k0 + c * 8;
-          if constexpr (AK == CQ_A_INT8_CODES) {
-            const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0);
-            const uint32_t rw[2] = {raw.x, raw.y};
-            uint32_t o[4];
+      const size_t ebase = srow + (size_t)sb * 64 + k0;
+      constexpr int kBatch = 4;
+      for (int c = sc0; c < nC; c += kBatch * cstep) {
+        uint4 raw[kBatch], raw2[kBatch];
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-              const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
-              const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
-              o[2 * h] = code_to_bf16_bits(b0) | (code_to_bf16_bits(b1) << 16);
-              o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
-            }
-            v = make_uint4(o[0], o[1], o[2], o[3]);
+        for (int i = 0; i < kBatch; ++i) {
+          const size_t e0 = ebase + (size_t)min(c + i * cstep, nC - 1) * 8;
+          if constexpr (AK == CQ_A_INT8_CODES) {
+            const uint2 r = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0);
+            raw[i] = make_uint4(r.x, r.y, 0u, 0u);
           } else if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
-            v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0);
+            raw[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0);
           } else {
-            const float4 f0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0);
-            const float4 f1 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.A) + e0 + 4);
-            v.x = f32_to_f16_bits_sat(f0.x) | (f32_to_f16_bits_sat(f0.y) << 16);
-            v.y = f32_to_f16_bits_sat(f0.z) | (f32_to_f16_bits_sat(f0.w) << 16);
-            v.z = f32_to_f16_bits_sat(f1.x) | (f32_to_f16_bits_sat(f1.y) << 16);
-            v.w = f32_to_f16_bits_sat(f1.z) | (f32_to_f16_bits_sat(f1.w) << 16);
+            raw[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.A) + e0);
+            raw2[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.A) + e0 + 4);
           }
         }
-        slab[c * Mpad + st] = v;
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+          const int ci = c + i * cstep;
+          if (ci >= nC) break;
+          uint4 v = make_uint4(0u, 0u, 0u, 0u);
+          if (svalid) {
+            if constexpr (AK == CQ_A_INT8_CODES) {
+              const uint32_t rw[2] = {raw[i].x, raw[i].y};
+              uint32_t o[4];
+#pragma unroll
+              for (int h = 0; h < 2; ++h) {
+                const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
+                const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
+                o[2 * h] = code_to_bf16_bits(b0) | (code_to_bf16_bits(b1) << 16);
+                o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
+              }
+              v = make_uint4(o[0], o[1], o[2], o[3]);
+            } else if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
+              v = raw[i];
+            } else {
+              const uint4 f0 = raw[i], f1 = raw2[i];
+              v.x = f32_to_f16_bits_sat(__uint_as_float(f0.x)) | (f32_to_f16_bits_sat(__uint_as_float(f0.y)) << 16);
+              v.y = f32_to_f16_bits_sat(__uint_as_float(f0.z)) | (f32_to_f16_bits_sat(__uint_as_float(f0.w)) << 16);
+              v.z = f32_to_f16_bits_sat(__uint_as_float(f1.x)) | (f32_to_f16_bits_sat(__uint_as_float(f1.y)) << 16);
+              v.w = f32_to_f16_bits_sat(__uint_as_float(f1.z)) | (f32_to_f16_bits_sat(__uint_as_float(f1.w)) << 16);
+            }
+          }
+          slab[ci * Mpad + st] = v;
+        }
       }
     };
 
