@@ -37,7 +37,7 @@ constexpr int kSmallMaxRows = CQ_SMALL_MAX_ROWS;  // groups with more rows go to
 constexpr int kTableBytes = 65536;   // 256 entries x 64 row slots x 4 bytes
 constexpr int kSlabBytes = 65536;    // activation slab
 constexpr int kListedWorkgroups = 512;  // grid of a launch that runs off the device-built group list
-constexpr int kRedBytes = 32768;     // K partials of up to 16 token columns: 8 wavefronts x 32 registers x 32 lanes
+constexpr int kRedBytes = 32768;     // K partials of up to 16 token columns: 8 wavefronts x 16 registers x 64 lanes
 #ifndef CQ_GEMM_WAVES
 #define CQ_GEMM_WAVES 8
 #endif
@@ -170,8 +170,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     const int qPerSlab = (KSfull >> 6) / NW;               // wavefront steps per slab
     const bool multi = KSfull < Kl;                        // activations do not fit: restage per slab
     const int tj = r32 < Mpad ? r32 : 0;                   // token column this lane feeds to the B operand
-    const bool sep = Mpad <= 16;                           // partial sums get a region of their own
-    const int lane_c = (g2 << 4) + r32;                    // compact numbering of up to 16 real columns
+    const bool sep = Mpad <= 16;                           // 16x16x32 MFMA path, partial sums in their own region
 
     // ---- this thread's staging duty: token st, 8-wide k chunks sc0, sc0 + cstep, ... ----
     const int st = tid & (Mpad - 1);
@@ -280,28 +279,27 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     }
     cent_load(u0);
     __builtin_amdgcn_sched_barrier(0);  // keep the centroid loads older than the ring loads
-    uint4 ring[kRing][2];
-    {
-      const uint8_t* wb = gbase + (size_t)u0 * 64 * rowbytes;
-#pragma unroll
-      for (int j = 0; j < kRing; ++j) {
-        const int gs = wave + NW * j;
-        const size_t off = (size_t)(gs < nS ? gs : 0) * sstride;
-        ring[j][0] = *reinterpret_cast<const uint4*>(wb + lane_off0 + off);
-        ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off1 + off);
-      }
-    }
 
     // The unit loop exists in two instantiations.  When the block's activations fit in LDS for the whole
     // of K (the decode case) they are staged once, up front, and the loop body contains no conditional
     // loads at all: the number of loads in flight is then the same on every path, which lets each wait
     // cover exactly one ring slot.  Otherwise the slab is restaged inside the loop.
-    auto run_units = [&](auto multi_tag, auto sep_tag) {
+    auto run_units = [&](auto multi_tag) {
       constexpr bool MULTI = decltype(multi_tag)::value;
-      constexpr bool SEP = decltype(sep_tag)::value;  // partials in their own region, 32 lanes per register row
-      float* rbase = SEP ? redc : red;
-      constexpr int rw = SEP ? 32 : 64;
-      const int rl = SEP ? lane_c : lane;
+      float* rbase = red;  // the K partials alias the table (17..32 token columns: no room elsewhere)
+      constexpr int rw = 64;
+      const int rl = lane;
+      uint4 ring[kRing][2];
+      {
+        const uint8_t* wb = gbase + (size_t)u0 * 64 * rowbytes;
+#pragma unroll
+        for (int j = 0; j < kRing; ++j) {
+          const int gs = wave + NW * j;
+          const size_t off = (size_t)(gs < nS ? gs : 0) * sstride;
+          ring[j][0] = *reinterpret_cast<const uint4*>(wb + lane_off0 + off);
+          ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off1 + off);
+        }
+      }
       for (int u = u0; u < u1; ++u) {
         const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
         const bool has_next = u + 1 < u1;
@@ -393,12 +391,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         }
 
         // ---- reduce the K partials (fixed order) through the table's LDS and finish ----
-        // Only the lanes of real token columns carry results.  Up to 16 tokens their partials fit a
-        // region of their own (compact: 32 lanes per register), which needs one barrier per unit:
-        // a wavefront can only reach the next unit's partial writes after that unit's table barrier,
-        // which every wavefront passes after its reads here.  Beyond that the partials alias the table
-        // and two more barriers fence them from the lookups.
-        if (!SEP) __syncthreads();
+        // Only the lanes of real token columns carry results.  The partials alias the table, so
+        // barriers fence them from the lookups on both sides.
+        __syncthreads();
         if (r32 < Mpad) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
@@ -423,7 +418,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
 #pragma unroll
           for (int i = 0; i < RPW; ++i) val[i] = 0.f;
         }
-        if (!SEP) __syncthreads();  // the next unit's table overwrites this region
+        __syncthreads();  // the next unit's table overwrites this region
         if (r32 < Mb) {
           const int m = m0 + 32 * tb + r32;
 #pragma unroll
@@ -462,13 +457,196 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         }
       }
     };
+
+    // ---- up to 16 tokens: the same loop on v_mfma_f32_16x16x32 ----
+    // With at most 16 real token columns the 32x32x16 shape spends half its matrix-pipe time on padding.
+    // MFMA lane (i = lane%16, g = lane/16) supplies row i, k group g (8 k) of a 16-row x 32-k block, so a
+    // 32-row x 64-k step of a row block is four MFMAs: piece m = h + 2c (row half h, k half c).  The 16
+    // bytes a lane loads (row lane%32, k half lane/32: dword d = k group d of that half) hold, seen as a
+    // 4x4 matrix over (16-lane row m, dword d), exactly the transpose of what the MFMAs want (lane row g,
+    // piece m): two v_permlane16_swap and two v_permlane32_swap per row block turn one into the other.
+    // Output register v of lane (n, q): row 4q + v, token n.
+    auto run_units16 = [&](auto multi_tag) {
+      constexpr bool MULTI = decltype(multi_tag)::value;
+      const int i16 = lane & 15, g4 = lane >> 4;
+      const int tj16 = i16 < Mpad ? i16 : 0;
+      uint32_t lbase[2][2];  // byte offset of this lane's row slot within a table entry
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) lbase[rb][h] = (uint32_t)((rb * 32 + h * 16 + i16) * 4);
+      float sc16 = 1.f;
+      if (p.row_scale && i16 < Mb) {
+        const int m = m0 + 32 * tb + i16;
+        sc16 = p.row_scale[p.row_gather ? p.row_gather[m] : m];
+      }
+      uint4 ring[kRing][2];
+      {
+        const uint8_t* wb = gbase + (size_t)u0 * 64 * rowbytes;
+#pragma unroll
+        for (int j = 0; j < kRing; ++j) {
+          const int gs = wave + NW * j;
+          const size_t off = (size_t)(gs < nS ? gs : 0) * sstride;
+          ring[j][0] = *reinterpret_cast<const uint4*>(wb + lane_off0 + off);
+          ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off1 + off);
+        }
+      }
+      typedef __attribute__((ext_vector_type(2))) unsigned pair_u32;
+      // (lane row m, dword d) -> (lane row d, register m)
+      auto transpose4 = [](const uint4 w, uint32_t (&piece)[4]) {
+        const pair_u32 ab = __builtin_amdgcn_permlane16_swap(w.x, w.y, false, false);
+        const pair_u32 ce = __builtin_amdgcn_permlane16_swap(w.z, w.w, false, false);
+        const pair_u32 p02 = __builtin_amdgcn_permlane32_swap(ab[0], ce[0], false, false);
+        const pair_u32 p13 = __builtin_amdgcn_permlane32_swap(ab[1], ce[1], false, false);
+        piece[0] = p02[0];
+        piece[2] = p02[1];
+        piece[1] = p13[0];
+        piece[3] = p13[1];
+      };
+      for (int u = u0; u < u1; ++u) {
+        const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
+        const bool has_next = u + 1 < u1;
+        const uint8_t* wb_next = has_next ? wb + 64 * rowbytes : wb;
+        build_table();
+        __syncthreads();
+
+        cq_v4f acc[2][2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int h = 0; h < 2; ++h) acc[rb][h] = cq_v4f{0.f, 0.f, 0.f, 0.f};
+        uint4 bf = make_uint4(0u, 0u, 0u, 0u);  // B operand; lanes of padding columns stay zero
+
+        auto ring_round = [&](const int q0) {
+#pragma unroll
+          for (int j = 0; j < kRing; ++j) {
+            const int q = q0 + j;
+            if constexpr (MULTI) {
+              if (j % kSlabCheck == 0) {
+                if (q < Qmax && q % qPerSlab == 0) {  // slab boundary: restage the activations
+                  __syncthreads();
+                  stage(q / qPerSlab);
+                  __syncthreads();
+                }
+              }
+            }
+            const int gs = wave + NW * q;
+            // table addresses first, so that the slot is dead before its refill
+            uint32_t o[2][16];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+              uint32_t piece[4];
+              transpose4(ring[j][rb], piece);
+#pragma unroll
+              for (int m = 0; m < 4; ++m)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                  o[rb][m * 4 + i] = __builtin_amdgcn_perm(piece[m], lbase[rb][m & 1], 0x0c0c0400u + (i << 8));
+                  asm volatile("" : "+v"(o[rb][m * 4 + i]));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            {
+              const int qq = q + kRing;  // the step that reuses this ring slot
+              const bool same = qq < Qpad;
+              const int gn = wave + NW * (same ? qq : qq - Qpad);
+              const uint8_t* base = same ? wb : wb_next;
+              const size_t off = (gn < nS && (same || has_next)) ? (size_t)gn * sstride : 0;
+              ring[j][0] = *reinterpret_cast<const uint4*>(base + lane_off0 + off);
+              ring[j][1] = *reinterpret_cast<const uint4*>(base + lane_off1 + off);
+            }
+            if (gs < nS) {
+              const int ls = gs - (q / qPerSlab) * (qPerSlab * NW);
+              const uint4* bsrc = slab + (size_t)(ls * 8 + g4) * Mpad + tj16;  // chunk ls*8 + 4c + g
+#pragma unroll
+              for (int c = 0; c < 2; ++c) {
+                if (i16 < Mpad) bf = bsrc[(size_t)(4 * c) * Mpad];
+                const cq_v4u bv = {bf.x, bf.y, bf.z, bf.w};
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                  for (int h = 0; h < 2; ++h) {
+                    const int m = h + 2 * c;
+                    cq_v4u a;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) a[i] = lds_read_u32(o[rb][m * 4 + i]);
+                    if constexpr (F16)
+                      acc[rb][h] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                          __builtin_bit_cast(cq_v8f16, a), __builtin_bit_cast(cq_v8f16, bv), acc[rb][h], 0, 0, 0);
+                    else
+                      acc[rb][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                          __builtin_bit_cast(cq_v8bf16, a), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][h], 0, 0, 0);
+                  }
+              }
+            }
+          }
+        };
+        for (int q0 = 0; q0 < Qpad; q0 += kRing) {
+          if (MULTI ? (q0 + kRing >= Qpad) : true) {  // next unit's centroid rows, ahead of the ring loads
+            cent_load(has_next ? u + 1 : u);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          ring_round(q0);
+        }
+
+        // ---- K partials through their own LDS region: register r = rb*8 + h*4 + v of wavefront w at
+        // (w*16 + r)*64 + lane; wavefront w then finishes registers 2w and 2w+1 (rows 4q+v, 4q+v+1 of one
+        // 16-row block: a gate/up pair).  One barrier per unit is enough: a wavefront can only reach the
+        // next unit's partial writes after that unit's table barrier, which every wavefront passes after
+        // its reads here. ----
+        if (i16 < Mpad) {
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+              for (int v = 0; v < 4; ++v) redc[(wave * 16 + rb * 8 + h * 4 + v) * 64 + lane] = acc[rb][h][v];
+        }
+        __syncthreads();
+        float val[2] = {0.f, 0.f};
+        if (i16 < Mpad) {
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            const int r = 2 * wave + i;
+            float sum = redc[r * 64 + lane];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) sum += redc[(w * 16 + r) * 64 + lane];
+            val[i] = sum;
+          }
+        }
+        if (i16 < Mb) {
+          const int m = m0 + 32 * tb + i16;
+          const int r = 2 * wave;
+          const int row = u * 64 + (r >> 3) * 32 + ((r >> 2) & 1) * 16 + g4 * 4 + (r & 3);
+          const float x0 = sc16 * val[0], x1 = sc16 * val[1];
+          if (p.ksplit > 1) {  // partial sum of this K range (CQ_EPI_NONE only)
+            float* dst = p.partials + (size_t)blockIdx.z * p.part_stride + (size_t)m * N + row;
+            *reinterpret_cast<float2*>(dst) = make_float2(x0, x1);
+          } else if constexpr (EPI == CQ_EPI_SWIGLU) {
+            const float h0 = x0 / (1.f + __expf(-x0)) * x1;
+            const size_t o = (size_t)m * p.out_ld + (row >> 1);
+            if constexpr (OUTK == CQ_OUT_F16)
+              reinterpret_cast<uint16_t*>(p.out)[o] = (uint16_t)f32_to_f16_bits_sat(h0);
+            else
+              reinterpret_cast<float*>(p.out)[o] = h0;
+          } else {
+            const size_t o = (size_t)m * p.out_ld + row;
+            if constexpr (OUTK == CQ_OUT_F16)
+              *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + o) =
+                  f32_to_f16_bits_sat(x0) | (f32_to_f16_bits_sat(x1) << 16);
+            else
+              *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + o) = make_float2(x0, x1);
+          }
+        }
+      }
+    };
     if (multi) {
-      if (sep) run_units(std::true_type{}, std::true_type{});
-      else run_units(std::true_type{}, std::false_type{});
+      if (sep) run_units16(std::true_type{});
+      else run_units(std::true_type{});
     } else {
       stage(0);
-      if (sep) run_units(std::false_type{}, std::true_type{});
-      else run_units(std::false_type{}, std::false_type{});
+      if (sep) run_units16(std::false_type{});
+      else run_units(std::false_type{});
     }
     __syncthreads();  // the slab is restaged for the next token block
   }
