@@ -41,11 +41,9 @@ constexpr int kRedBytes = 32768;     // K partials of up to 16 token columns: 8 
 #ifndef CQ_GEMM_WAVES
 #define CQ_GEMM_WAVES 8
 #endif
-#ifndef CQ_GEMM_RING
-#define CQ_GEMM_RING 4
-#endif
 constexpr int kWaves = CQ_GEMM_WAVES;  // wavefronts per workgroup: they split K (step s -> wavefront s % kWaves)
-constexpr int kRing = CQ_GEMM_RING;    // K steps prefetched per wavefront
+// K steps a wavefront keeps in flight: 4 (64 KiB per CU) or, when its step count is a multiple of 8,
+// 8 (the per-unit phases in which nothing is consumed then find more data already on its way)
 constexpr int kSlabCheck = 16 / kWaves;  // smallest number of wavefront steps in a slab (Mpad = 32)
 
 struct GemmArgs {
@@ -104,7 +102,7 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
 }
 
 
-template <int AK, int EPI, int OUTK>
+template <int AK, int EPI, int OUTK, int kRing>
 __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmArgs p) {
   constexpr bool F16 = (AK == CQ_A_F16 || AK == CQ_A_F32);
   constexpr int NW = kWaves;
@@ -652,9 +650,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   }
 }
 
-template <int AK, int EPI, int OUTK>
-cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
-  auto kern = gemm_small_kernel<AK, EPI, OUTK>;
+template <int AK, int EPI, int OUTK, int RING>
+cq_status launch_small_ring(const GemmArgs& a, int G, hipStream_t s) {
+  auto kern = gemm_small_kernel<AK, EPI, OUTK, RING>;
   static bool configured = false;
   if (!configured) {
     hipFuncAttributes fa;
@@ -670,6 +668,12 @@ cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
                                 : dim3((n_units + a.upw - 1) / a.upw, G, a.ksplit);
   hipLaunchKernelGGL(kern, grid, dim3(64 * kWaves), kTableBytes + kSlabBytes + kRedBytes, s, a);
   return cq_check_launch();
+}
+
+template <int AK, int EPI, int OUTK>
+cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
+  const int per_wave = (a.ksteps + kWaves - 1) / kWaves;  // steps of a wavefront in the (first) K range
+  return per_wave % 8 == 0 ? launch_small_ring<AK, EPI, OUTK, 8>(a, G, s) : launch_small_ring<AK, EPI, OUTK, 4>(a, G, s);
 }
 
 // out[m, :] = sum over the K splits of partials[s][m, :] in the order s = 0, 1, ... for the rows of the
