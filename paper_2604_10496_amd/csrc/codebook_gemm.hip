@@ -459,20 +459,19 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     // ---- up to 16 tokens: the same loop on v_mfma_f32_16x16x32 ----
     // With at most 16 real token columns the 32x32x16 shape spends half its matrix-pipe time on padding.
     // MFMA lane (i = lane%16, g = lane/16) supplies row i, k group g (8 k) of a 16-row x 32-k block, so a
-    // 32-row x 64-k step of a row block is four MFMAs: piece m = h + 2c (row half h, k half c).  The 16
-    // bytes a lane loads (row lane%32, k half lane/32: dword d = k group d of that half) hold, seen as a
-    // 4x4 matrix over (16-lane row m, dword d), exactly the transpose of what the MFMAs want (lane row g,
-    // piece m): two v_permlane16_swap and two v_permlane32_swap per row block turn one into the other.
+    // 32-row x 64-k step of a row block is four MFMAs (row half h, k half c).  Were the lookups issued in
+    // that arrangement, the four lanes of a row would hit the same LDS bank with different entries (a
+    // two-way conflict in each half wavefront, measured at 1.5x the time of a conflict-free read).  So
+    // every lane looks up the row it loaded (row lane%32 of the block: 32 different banks per half
+    // wavefront) and one v_permlane16_swap per pair of looked-up dwords then sorts the results: of the
+    // swap of (dword 2c, dword 2c+1), the first result holds rows 0..15 and the second rows 16..31, lane
+    // row g carrying k group 2c + g%2 + 4*(g/2) of the step -- the B operand is read in that same order.
     // Output register v of lane (n, q): row 4q + v, token n.
     auto run_units16 = [&](auto multi_tag) {
       constexpr bool MULTI = decltype(multi_tag)::value;
       const int i16 = lane & 15, g4 = lane >> 4;
       const int tj16 = i16 < Mpad ? i16 : 0;
-      uint32_t lbase[2][2];  // byte offset of this lane's row slot within a table entry
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) lbase[rb][h] = (uint32_t)((rb * 32 + h * 16 + i16) * 4);
+      const uint32_t lbase[2] = {lanebase0, lanebase1};  // byte offset of this lane's row slot in a table entry
       float sc16 = 1.f;
       if (p.row_scale && i16 < Mb) {
         const int m = m0 + 32 * tb + i16;
@@ -490,17 +489,6 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         }
       }
       typedef __attribute__((ext_vector_type(2))) unsigned pair_u32;
-      // (lane row m, dword d) -> (lane row d, register m)
-      auto transpose4 = [](const uint4 w, uint32_t (&piece)[4]) {
-        const pair_u32 ab = __builtin_amdgcn_permlane16_swap(w.x, w.y, false, false);
-        const pair_u32 ce = __builtin_amdgcn_permlane16_swap(w.z, w.w, false, false);
-        const pair_u32 p02 = __builtin_amdgcn_permlane32_swap(ab[0], ce[0], false, false);
-        const pair_u32 p13 = __builtin_amdgcn_permlane32_swap(ab[1], ce[1], false, false);
-        piece[0] = p02[0];
-        piece[2] = p02[1];
-        piece[1] = p13[0];
-        piece[3] = p13[1];
-      };
       for (int u = u0; u < u1; ++u) {
         const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
         const bool has_next = u + 1 < u1;
@@ -533,14 +521,14 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
             uint32_t o[2][16];
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
-              uint32_t piece[4];
-              transpose4(ring[j][rb], piece);
+              const uint4 w = ring[j][rb];
+              const uint32_t wd[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-              for (int m = 0; m < 4; ++m)
+              for (int d = 0; d < 4; ++d)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                  o[rb][m * 4 + i] = __builtin_amdgcn_perm(piece[m], lbase[rb][m & 1], 0x0c0c0400u + (i << 8));
-                  asm volatile("" : "+v"(o[rb][m * 4 + i]));
+                  o[rb][d * 4 + i] = __builtin_amdgcn_perm(wd[d], lbase[rb], 0x0c0c0400u + (i << 8));
+                  asm volatile("" : "+v"(o[rb][d * 4 + i]));
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -555,26 +543,35 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
             }
             if (gs < nS) {
               const int ls = gs - (q / qPerSlab) * (qPerSlab * NW);
-              const uint4* bsrc = slab + (size_t)(ls * 8 + g4) * Mpad + tj16;  // chunk ls*8 + 4c + g
+              // chunk ls*8 + 2c + g%2 + 4*(g/2)
+              const uint4* bsrc = slab + (size_t)(ls * 8 + (g4 & 1) + 4 * (g4 >> 1)) * Mpad + tj16;
 #pragma unroll
               for (int c = 0; c < 2; ++c) {
-                if (i16 < Mpad) bf = bsrc[(size_t)(4 * c) * Mpad];
+                if (i16 < Mpad) bf = bsrc[(size_t)(2 * c) * Mpad];
                 const cq_v4u bv = {bf.x, bf.y, bf.z, bf.w};
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
+                for (int rb = 0; rb < 2; ++rb) {
+                  cq_v4u a0, a1;
 #pragma unroll
-                  for (int h = 0; h < 2; ++h) {
-                    const int m = h + 2 * c;
-                    cq_v4u a;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) a[i] = lds_read_u32(o[rb][m * 4 + i]);
-                    if constexpr (F16)
-                      acc[rb][h] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                          __builtin_bit_cast(cq_v8f16, a), __builtin_bit_cast(cq_v8f16, bv), acc[rb][h], 0, 0, 0);
-                    else
-                      acc[rb][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                          __builtin_bit_cast(cq_v8bf16, a), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][h], 0, 0, 0);
+                  for (int i = 0; i < 4; ++i) {
+                    const uint32_t x = lds_read_u32(o[rb][(2 * c) * 4 + i]);
+                    const uint32_t y = lds_read_u32(o[rb][(2 * c + 1) * 4 + i]);
+                    const pair_u32 sw = __builtin_amdgcn_permlane16_swap(x, y, false, false);
+                    a0[i] = sw[0];
+                    a1[i] = sw[1];
                   }
+                  if constexpr (F16) {
+                    acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                        __builtin_bit_cast(cq_v8f16, a0), __builtin_bit_cast(cq_v8f16, bv), acc[rb][0], 0, 0, 0);
+                    acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                        __builtin_bit_cast(cq_v8f16, a1), __builtin_bit_cast(cq_v8f16, bv), acc[rb][1], 0, 0, 0);
+                  } else {
+                    acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(cq_v8bf16, a0), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][0], 0, 0, 0);
+                    acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(cq_v8bf16, a1), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][1], 0, 0, 0);
+                  }
+                }
               }
             }
           }
