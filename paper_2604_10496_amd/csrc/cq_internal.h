@@ -42,6 +42,13 @@ cq_status cq_rotate_quant_ex(const float* X, const float* R, int T, int H, int a
                              int8_t* Q_out, uint16_t* Q16_out, float* scale_out, void* workspace,
                              size_t workspace_bytes, cq_stream stream);
 
+// Decode-sized batches: quantization of the rotated rows (given as K-split partial sums) and the router
+// logits in one launch.  Supported sizes also fit the one-workgroup routing kernel that follows.
+bool cq_front_small_supported(int T, int H, int E, int top_k);
+cq_status cq_front_small_launch(const float* partials, int ksplit, int T, int H, int act_bits, const float* Wr,
+                                const float* bias, int E, float* XR, int8_t* Q, uint16_t* Q16, float* scale,
+                                float* logits, hipStream_t s);
+
 cq_status cq_topk_launch(const float* logit_partials, int ksplit, const float* bias, int T, int E, int top_k,
                          float* logits_out, int32_t* topk_ids, float* topk_w, hipStream_t s);
 size_t cq_permute_workspace_bytes(int T, int E, int top_k);

@@ -113,13 +113,30 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
   if (!mark(0)) return CQ_ERR_HIP;
   const bool bf16_codes = use_bf16_codes(L, T);
   uint16_t* Q16 = bf16_codes ? (uint16_t*)(ws + lay.Q16) : nullptr;
-  st = cq_rotate_quant_ex(X, L->R, T, L->H, L->act_bits, XR, Q, Q16, scale, scratch, scratch_bytes, stream);
-  if (st != CQ_OK) return st;
-  if (!mark(1)) return CQ_ERR_HIP;
-  st = cq_route_permute(XR, L->Wr, L->bias, nullptr, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets, perm,
-                        inv_perm, src_token, scratch, scratch_bytes, stream);
-  if (st != CQ_OK) return st;
-  if (!mark(2)) return CQ_ERR_HIP;
+  if (cq_front_small_supported(T, L->H, L->E, L->top_k)) {
+    // decode-sized batch: the rotation; one launch for quantization and logits; one for top-k and grouping
+    // (the second stage boundary therefore falls between the rotation and everything else)
+    const cq_gemm_f32_plan p = cq_gemm_f32_make_plan(T, L->H, L->H);
+    float* part = p.ksplit > 1 ? (float*)scratch : XR;
+    st = cq_gemm_f32_launch(X, L->R, 0, T, L->H, L->H, p, part, nullptr, 0, hs);
+    if (st != CQ_OK) return st;
+    if (!mark(1)) return CQ_ERR_HIP;
+    st = cq_front_small_launch(part, p.ksplit, T, L->H, L->act_bits, L->Wr, L->bias, L->E, XR, Q, Q16, scale, logits,
+                               hs);
+    if (st != CQ_OK) return st;
+    st = cq_route_permute(nullptr, nullptr, nullptr, logits, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets,
+                          perm, inv_perm, src_token, scratch, scratch_bytes, stream);
+    if (st != CQ_OK) return st;
+    if (!mark(2)) return CQ_ERR_HIP;
+  } else {
+    st = cq_rotate_quant_ex(X, L->R, T, L->H, L->act_bits, XR, Q, Q16, scale, scratch, scratch_bytes, stream);
+    if (st != CQ_OK) return st;
+    if (!mark(1)) return CQ_ERR_HIP;
+    st = cq_route_permute(XR, L->Wr, L->bias, nullptr, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets, perm,
+                          inv_perm, src_token, scratch, scratch_bytes, stream);
+    if (st != CQ_OK) return st;
+    if (!mark(2)) return CQ_ERR_HIP;
+  }
   // (internal launcher: the layer was validated above and the scratch area is sized for 16-bit operands)
   st = cq_gemm_codebook_launch(&L->gate_up, bf16_codes ? (const void*)Q16 : (const void*)Q,
                                bf16_codes ? CQ_A_BF16 : CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU,
