@@ -84,6 +84,7 @@ typedef struct {
   const float* bias;  /* [E] or NULL                                                    */
   cq_codebook_weights gate_up; /* G = E+S, N = 2I (gate/up interleaved), K = H          */
   cq_codebook_weights down;    /* G = E+S, N = H, K = I                                 */
+  const void* R_split; /* optional: copy of R written by cq_rotation_split(); NULL if absent */
 } cq_layer;
 
 const char* cq_status_string(cq_status st);
@@ -100,6 +101,27 @@ size_t cq_rotate_quant_workspace_bytes(int T, int H);
 cq_status cq_rotate_quant(const float* X, const float* R, int T, int H, int act_bits,
                           float* XR_out, int8_t* Q_out, float* scale_out,
                           void* workspace, size_t workspace_bytes, cq_stream stream);
+
+/*
+ * a1 for many tokens: a copy of R (AOS section) as two f16 planes, R = Rh + 2^-11 Rl, in the order the
+ * matrix-core fragments are loaded in.  With it cq_moe_forward computes X R (for T >= 256, H % 256 == 0)
+ * as Xh Rh + 2^-11 (Xh Rl + Xl Rh) on the f16 matrix cores with fp32 accumulation: every operand is
+ * represented to 2^-23 of its size and only the 2^-22 Xl Rl term is dropped, so the result is as accurate
+ * as the fp32 product and the codes still differ from an exact evaluation only at rounding ties.
+ *   R [H,H] f32 device, H % 32 == 0; out: cq_rotation_split_bytes(H) bytes of device memory, owned by
+ *   the caller, read by every later cq_moe_forward on a layer whose R_split points to it.
+ */
+size_t cq_rotation_split_bytes(int H);
+cq_status cq_rotation_split(const float* R, int H, void* out, size_t out_bytes, cq_stream stream);
+/*
+ * cq_rotate_quant on that copy (the path cq_moe_forward takes when the batch fills enough 128-token x
+ * 256-column tiles): same outputs, same accuracy statement.  T >= 256, H % 256 == 0, T*H < 2^31;
+ * other sizes return CQ_ERR_SHAPE.  workspace: cq_rotate_quant_split_workspace_bytes(T, H) bytes.
+ */
+size_t cq_rotate_quant_split_workspace_bytes(int T, int H);
+cq_status cq_rotate_quant_split(const float* X, const void* R_split, int T, int H, int act_bits,
+                                float* XR_out, int8_t* Q_out, float* scale_out,
+                                void* workspace, size_t workspace_bytes, cq_stream stream);
 
 /*
  * a3 + a4 + a5: router logits L = X_R Wr^T (+bias) in fp32, top-k by descending logit (equal

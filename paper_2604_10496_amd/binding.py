@@ -24,7 +24,8 @@ EXPORTS = [
     "cq_route_permute_workspace_bytes", "cq_route_permute", "cq_grouped_gemm_workspace_bytes",
     "cq_codebook_grouped_gemm", "cq_combine", "cq_moe_workspace_bytes", "cq_moe_workspace_layout",
     "cq_moe_forward", "cq_moe_forward_timed", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
-    "cq_stream_read", "cq_mfma_loop",
+    "cq_stream_read", "cq_mfma_loop", "cq_rotation_split_bytes", "cq_rotation_split",
+    "cq_rotate_quant_split_workspace_bytes", "cq_rotate_quant_split",
 ]
 
 
@@ -37,7 +38,7 @@ class Layer(ctypes.Structure):
     _fields_ = [("H", ctypes.c_int), ("I", ctypes.c_int), ("E", ctypes.c_int), ("top_k", ctypes.c_int),
                 ("S", ctypes.c_int), ("act_bits", ctypes.c_int),
                 ("R", ctypes.c_void_p), ("Wr", ctypes.c_void_p), ("bias", ctypes.c_void_p),
-                ("gate_up", CodebookWeights), ("down", CodebookWeights)]
+                ("gate_up", CodebookWeights), ("down", CodebookWeights), ("R_split", ctypes.c_void_p)]
 
 
 class MoeLayout(ctypes.Structure):
@@ -88,6 +89,14 @@ def load_library() -> ctypes.CDLL:
     lib.cq_moe_forward.argtypes = [ctypes.POINTER(Layer), vp, ci, vp, vp, sz, vp]
     lib.cq_moe_forward_timed.restype = ci
     lib.cq_moe_forward_timed.argtypes = [ctypes.POINTER(Layer), vp, ci, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]
+    lib.cq_rotation_split_bytes.restype = sz
+    lib.cq_rotation_split_bytes.argtypes = [ci]
+    lib.cq_rotation_split.restype = ci
+    lib.cq_rotation_split.argtypes = [vp, ci, vp, sz, vp]
+    lib.cq_rotate_quant_split_workspace_bytes.restype = sz
+    lib.cq_rotate_quant_split_workspace_bytes.argtypes = [ci, ci]
+    lib.cq_rotate_quant_split.restype = ci
+    lib.cq_rotate_quant_split.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     lib.cq_prepack_bytes.restype = sz
     lib.cq_prepack_bytes.argtypes = [ctypes.POINTER(CodebookWeights)]
     lib.cq_prepack.restype = ci
@@ -175,6 +184,19 @@ def cq_prepack(W: DeviceCodebook):
     return dst
 
 
+def cq_rotation_split(R):
+    """Split copy of R [H, H] (device fp32) for the f16 matrix cores; returns a device byte buffer."""
+    torch = _torch()
+    lib = load_library()
+    H = R.shape[0]
+    n = lib.cq_rotation_split_bytes(H)
+    if n == 0:
+        raise CqError(2)
+    out = torch.empty(n, dtype=torch.uint8, device="cuda")
+    _check(lib.cq_rotation_split(_ptr(R), H, _ptr(out), n, _stream()))
+    return out
+
+
 def cq_decode_dense(W: DeviceCodebook, g: int, use_prepacked: bool = True):
     torch = _torch()
     lib = load_library()
@@ -198,6 +220,19 @@ def cq_rotate_quant(X, R, act_bits: int) -> Dict[str, object]:
     ws = _ws(n)
     _check(lib.cq_rotate_quant(_ptr(X), _ptr(R), T, H, act_bits, _ptr(XR), _ptr(Q), _ptr(scale), _ptr(ws), ws.numel(),
                                _stream()))
+    return {"XR": XR, "Q": Q, "scale": scale}
+
+
+def cq_rotate_quant_split(X, R_split, act_bits: int) -> Dict[str, object]:
+    torch = _torch()
+    lib = load_library()
+    T, H = X.shape
+    XR = torch.empty((T, H), dtype=torch.float32, device="cuda")
+    Q = torch.empty((T, H), dtype=torch.int8, device="cuda")
+    scale = torch.empty((T,), dtype=torch.float32, device="cuda")
+    ws = _ws(lib.cq_rotate_quant_split_workspace_bytes(T, H))
+    _check(lib.cq_rotate_quant_split(_ptr(X), _ptr(R_split), T, H, act_bits, _ptr(XR), _ptr(Q), _ptr(scale), _ptr(ws),
+                                     ws.numel(), _stream()))
     return {"XR": XR, "Q": Q, "scale": scale}
 
 
@@ -265,13 +300,16 @@ class DeviceLayer:
         self.bias = None if bias is None else torch.as_tensor(bias).to("cuda").contiguous()
         self.gate_up, self.down = gate_up, down
         self.use_prepacked = use_prepacked
+        # set-up work, like prepacking the indices: the split copy of R for the f16 matrix cores
+        self.R_split = cq_rotation_split(self.R) if use_prepacked and cfg.H % 32 == 0 else None
         self._ws = None
         self._ws_T = -1
 
     def struct(self) -> Layer:
         c = self.cfg
         return Layer(c.H, c.I, c.E, c.top_k, c.S, c.act_bits, _ptr(self.R), _ptr(self.Wr), _ptr(self.bias),
-                     self.gate_up.struct(self.use_prepacked), self.down.struct(self.use_prepacked))
+                     self.gate_up.struct(self.use_prepacked), self.down.struct(self.use_prepacked),
+                     _ptr(self.R_split))
 
     def workspace(self, T: int):
         if self._ws is None or self._ws_T != T:

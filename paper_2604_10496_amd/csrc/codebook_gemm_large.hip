@@ -19,6 +19,7 @@
 #include <type_traits>
 
 #include "cq_internal.h"
+#include "cq_async.h"
 #include "cq_decode.h"
 
 void cq_large_tile_caps(int G, int M_total, int* cap256, int* cap128);
@@ -65,38 +66,7 @@ __device__ __forceinline__ cq_v16f mfma_large(const cq_v4u a, const cq_v4u b, cq
                                                    __builtin_bit_cast(cq_v8bf16, b), c, 0, 0, 0);
 }
 
-// ---- memory operations the compiler must not track -------------------------------------------------
-// The pipeline keeps loads in flight across several K steps.  The compiler's own wait insertion would
-// drain them (it treats an LDS read after a direct-to-LDS load as dependent on it), so the loop's
-// global loads are issued from inline assembly and waited for by explicit vmcnt counts.  The kernel has
-// no static LDS (verified by the launcher): dynamic LDS starts at address 0 and byte offsets are LDS
-// addresses.
-
-// 16 bytes per lane from global memory into the registers `dst`; valid only after a vm_wait that
-// names `dst`
-__device__ __forceinline__ void load_global_async(cq_v4u& dst, const uint8_t* src) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(src) : "memory");
-}
-// (m0 is a reserved register: the compiler loads it right before each use of its own and does not
-// keep values in it, which is what clobbering it here relies on)
-#pragma clang diagnostic ignored "-Winline-asm"
-// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base uniform)
-__device__ __forceinline__ void load_global_to_lds(uint32_t lds_base, const uint8_t* src) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory", "m0");
-}
-// wait until at most N of this wavefront's vector-memory loads are outstanding; the registers passed
-// through become usable only after it
-template <int N>
-__device__ __forceinline__ void vm_wait(cq_v4u& a, cq_v4u& b) {
-  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void vm_wait(cq_v4u& a, cq_v4u& b, cq_v4u& c, cq_v4u& d) {
-  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
-}
-__device__ __forceinline__ cq_v4u lds_read_u128(uint32_t byte_offset) {
-  return *reinterpret_cast<const __attribute__((address_space(3))) cq_v4u*>((uintptr_t)byte_offset);
-}
+using namespace cq_async;
 
 // LDS row stride (bytes) of the epilogue's staging tile of 64 tokens x the workgroup's output columns
 constexpr int epilogue_row_stride(int epi, int outk) {

@@ -49,6 +49,13 @@ cq_status cq_front_small_launch(const float* partials, int ksplit, int T, int H,
                                 const float* bias, int E, float* XR, int8_t* Q, uint16_t* Q16, float* scale,
                                 float* logits, hipStream_t s);
 
+// X_R = X R on f16 matrix cores from a split copy of R (cq_rotation_split), accurate to about fp32
+bool cq_rotate_split_supported(int T, int H);
+bool cq_rotate_split_preferred(int T, int H);  // supported, and enough tiles to beat the fp32 kernel
+size_t cq_rotate_split_workspace_bytes(int T, int H);
+cq_status cq_rotate_split_launch(const float* X, const void* R_split, int T, int H, float* XR_out, void* workspace,
+                                 hipStream_t s);
+
 cq_status cq_topk_launch(const float* logit_partials, int ksplit, const float* bias, int T, int E, int top_k,
                          float* logits_out, int32_t* topk_ids, float* topk_w, hipStream_t s);
 size_t cq_permute_workspace_bytes(int T, int E, int top_k);

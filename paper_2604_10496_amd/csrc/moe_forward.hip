@@ -18,6 +18,9 @@ cq_status validate_layer(const cq_layer* L, int T) {
   return CQ_OK;
 }
 
+// Many tokens and a split copy of R at hand: the rotation runs on the f16 matrix cores.
+bool use_split_rotation(const cq_layer* L, int T) { return L->R_split && cq_rotate_split_preferred(T, L->H); }
+
 // Batches large enough for the large-tile product get the codes a second time as bf16, so that staging
 // them into LDS is a plain copy.
 bool use_bf16_codes(const cq_layer* L, int T) {
@@ -48,6 +51,10 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   size_t scratch = cq_rotate_quant_workspace_bytes(T, L->H);
   const size_t r = cq_route_permute_workspace_bytes(T, L->H, L->E, L->top_k);
   if (r > scratch) scratch = r;
+  if (use_split_rotation(L, T)) {
+    const size_t x = cq_rotate_split_workspace_bytes(T, L->H);
+    if (x > scratch) scratch = x;
+  }
   // the layer feeds both products 16-bit operands (bf16 codes, f16 h): tile lists only
   if (use_bf16_codes(L, T)) {
     const size_t g1 = cq_gemm_large_workspace_bytes(L->gate_up.G, (int)M, L->gate_up.K, false);
@@ -129,7 +136,13 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
     if (st != CQ_OK) return st;
     if (!mark(2)) return CQ_ERR_HIP;
   } else {
-    st = cq_rotate_quant_ex(X, L->R, T, L->H, L->act_bits, XR, Q, Q16, scale, scratch, scratch_bytes, stream);
+    if (use_split_rotation(L, T)) {
+      st = cq_rotate_split_launch(X, L->R_split, T, L->H, XR, scratch, hs);
+      if (st != CQ_OK) return st;
+      st = cq_quantize_launch(XR, 1, T, L->H, L->act_bits, XR, Q, Q16, scale, nullptr, hs);
+    } else {
+      st = cq_rotate_quant_ex(X, L->R, T, L->H, L->act_bits, XR, Q, Q16, scale, scratch, scratch_bytes, stream);
+    }
     if (st != CQ_OK) return st;
     if (!mark(1)) return CQ_ERR_HIP;
     st = cq_route_permute(XR, L->Wr, L->bias, nullptr, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets, perm,

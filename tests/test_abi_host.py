@@ -76,6 +76,17 @@ def test_argument_validation_happens_before_any_device_call():
     assert lib.cq_decode_dense(ctypes.byref(W), 5, one, None) == 2
     assert lib.cq_stream_read(one, 24, one, None) == 2
     assert lib.cq_mfma_loop(8, 10, None, None) == 1 and lib.cq_mfma_loop(0, 10, one, None) == 2
+    # split copy of R and the rotation that uses it
+    assert lib.cq_rotation_split_bytes(256) == 256 * 256 * 4 and lib.cq_rotation_split_bytes(100) == 0
+    assert lib.cq_rotation_split(None, 256, one, 1 << 30, None) == 1
+    assert lib.cq_rotation_split(one, 100, one, 1 << 30, None) == 2
+    assert lib.cq_rotation_split(one, 256, one, 16, None) == 4
+    assert lib.cq_rotate_quant_split(one, None, 256, 256, 8, one, one, one, one, 1 << 30, None) == 1
+    assert lib.cq_rotate_quant_split(one, one, 100, 256, 8, one, one, one, one, 1 << 30, None) == 2   # too few tokens
+    assert lib.cq_rotate_quant_split(one, one, 256, 192, 8, one, one, one, one, 1 << 30, None) == 2   # H % 256
+    assert lib.cq_rotate_quant_split(one, one, 256, 256, 5, one, one, one, one, 1 << 30, None) == 3
+    assert lib.cq_rotate_quant_split(one, one, 256, 256, 8, one, one, one, one, 64, None) == 4
+    assert lib.cq_rotate_quant_split_workspace_bytes(256, 256) >= 2 * 256 * 256 * 2 + 256 * 4
 
 
 def test_workspace_sizes_are_pure_and_monotone():

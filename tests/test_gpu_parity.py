@@ -85,6 +85,33 @@ def test_rotate_quant(B, T, H, bits):
     assert n_tie <= max(2, T * H // 500)
 
 
+@pytest.mark.parametrize("T,H,bits,xscale", [(256, 256, 8, 1.0), (300, 512, 4, 1.0), (644, 256, 8, 3e4),
+                                             (257, 1024, 4, 1e-6)])
+def test_rotate_quant_split(B, T, H, bits, xscale):
+    """The rotation as three f16 matrix-core products on the split copy of R: ragged last token tile, several
+    column tiles, activations far outside and far below the f16 range (rows are rescaled by powers of two)."""
+    cfg = synth.small_variant(synth.CONFIGS["tiny"], T=T, H=H, act_bits=bits, outlier_channels=(3, 41))
+    L = synth.make_layer(cfg, with_experts=False)
+    X = (L.X * np.float32(xscale)).astype(np.float32)
+    X[T // 2] = 0                                     # an all-zero row: codes 0, scale 1
+    _say(f"rotate_quant_split T={T} H={H} bits={bits} xscale={xscale}")
+    Rs = B.cq_rotation_split(_dev(L.R))
+    out = B.cq_rotate_quant_split(_dev(X), Rs, bits)
+    XR_ref = O.rotate(X, L.R)
+    q_ref, s_ref = O.quantize(XR_ref, bits)
+    XR = out["XR"].cpu().numpy().astype(np.float64)
+    err = np.abs(XR - XR_ref).max(axis=1) / np.maximum(np.abs(XR_ref).max(axis=1), 1e-300)
+    _say(f"  max |error| / row max = {err.max():.2e}")
+    assert err.max() <= 4e-6
+    assert np.allclose(out["scale"].cpu().numpy(), s_ref, rtol=1e-5)
+    n_tie = Hp.check_codes(out["Q"].cpu().numpy(), q_ref, XR_ref, s_ref)
+    _say(f"  codes differing at ties: {n_tie} of {T * H}")
+    assert n_tie <= max(2, T * H // 500)
+    # the fp32 matrix-core path on the same input: the same codes except at ties
+    base = B.cq_rotate_quant(_dev(X), _dev(L.R), bits)
+    assert np.abs(base["Q"].cpu().numpy().astype(np.int32) - out["Q"].cpu().numpy().astype(np.int32)).max() <= 1
+
+
 def test_rotate_quant_identity_and_grid(B):
     """R = I returns X bit-exactly, and rows on the quantization grid return their integers exactly."""
     rng = np.random.default_rng(5)
@@ -331,6 +358,12 @@ def _check_layer(B, cfg, only_tokens=None, label=""):
     torch.cuda.synchronize()
     mid = B.moe_intermediates(layer, cfg.T)
     n_tie = Hp.check_codes(mid["Q"].cpu().numpy(), ref["q"], ref["XR"], ref["scale"])
+    # the rotation itself (fp32 matrix cores, or the split f16 product for many tokens): fp32-class error,
+    # measured against the largest entry of the row
+    xr_err = np.abs(mid["XR"].cpu().numpy().astype(np.float64) - ref["XR"]).max(axis=1)
+    xr_err = xr_err / np.maximum(np.abs(ref["XR"]).max(axis=1), 1e-30)
+    _say(f"  rotation: max |error| / row max = {xr_err.max():.2e}")
+    assert xr_err.max() <= 4e-6
     assert np.allclose(mid["scale"].cpu().numpy(), ref["scale"], rtol=1e-5)
     assert np.array_equal(mid["ids"].cpu().numpy(), ref["ids"])
     assert np.allclose(mid["w"].cpu().numpy(), ref["w"], rtol=W_RTOL, atol=1e-7)
