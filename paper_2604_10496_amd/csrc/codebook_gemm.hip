@@ -298,6 +298,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
           ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off1 + off);
         }
       }
+      // single slab: the activations are staged here, behind the first ring requests, so that their
+      // memory latency and the ring's overlap (the barrier after the first table build publishes them)
+      if constexpr (!MULTI) stage(0);
       for (int u = u0; u < u1; ++u) {
         const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
         const bool has_next = u + 1 < u1;
@@ -488,6 +491,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
           ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off1 + off);
         }
       }
+      // single slab: the activations are staged here, behind the first ring requests, so that their
+      // memory latency and the ring's overlap (the barrier after the first table build publishes them)
+      if constexpr (!MULTI) stage(0);
       typedef __attribute__((ext_vector_type(2))) unsigned pair_u32;
       for (int u = u0; u < u1; ++u) {
         const uint8_t* wb = gbase + (size_t)u * 64 * rowbytes;
@@ -639,7 +645,6 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
       if (sep) run_units16(std::true_type{});
       else run_units(std::true_type{});
     } else {
-      stage(0);
       if (sep) run_units16(std::false_type{});
       else run_units(std::false_type{});
     }
