@@ -19,6 +19,7 @@ What follows which passage of the paper
   decode_*          W_c[i,j] = sum_k C[i,k] A[i,j,k]   ACCF section (Eq. W_c)
   expert_ffn        (phi(X W_gate) . X W_up) W_down    AOS section (rotation-invariance equation)
   moe_forward       sum_i Pi_i X_R W_c (+ shared)      ACCF section (Eq. L, MoE case), appendix (shared expert)
+  hadamard_*        online Hadamard transform          evaluation section (the "had" variant)
 
 Readings taken where the paper is silent (each is also listed in the design notes):
   * quantization is symmetric and per token: s_t = max_j |X_R[t,j]| / qmax, qmax = 2^(b-1)-1,
@@ -27,7 +28,9 @@ Readings taken where the paper is silent (each is also listed in the design note
   * routing weights are the softmax over the k selected logits (they sum to 1); ids are in
     descending logit order and equal logits go to the lower expert id;
   * tokens are grouped by expert with a stable sort of the assignment number a = t*k + j;
-  * the intermediate h is not re-quantized before the down projection;
+  * the intermediate h is not re-quantized before the down projection, except in the online-Hadamard
+    variant (h_bits > 0): there h is multiplied by H_I / sqrt(I), H_I = H_m (x) H_{2^k} with a Paley matrix
+    of order m in {12, 28, 44} when I is not a power of two, and quantized per row exactly like X_R;
   * phi is SiLU; the output stays in the rotated basis (no R^T is applied);
   * shared experts see every token with weight 1 and are added after the routed sum.
 
@@ -183,11 +186,105 @@ def silu(x: np.ndarray) -> np.ndarray:
     return x / (1.0 + np.exp(-x))
 
 
-def expert_ffn(a_rows: np.ndarray, expert: Dict[str, Tuple[np.ndarray, np.ndarray]]) -> Dict[str, np.ndarray]:
-    """SwiGLU expert on de-quantized rows a = s*q: returns g, u, h, o (all float64)."""
+# ------------------------------------------------------------------------------------------
+# online Hadamard transform of the intermediate (the "had" variant of the evaluation section:
+# an online Hadamard rotation in front of the down projection, whose input is then quantized
+# like any other activation)
+# ------------------------------------------------------------------------------------------
+def _legendre(x: int, q: int) -> int:
+    """Quadratic character of x modulo the odd prime q: 0, +1 (non-zero square) or -1."""
+    x %= q
+    if x == 0:
+        return 0
+    return 1 if any((y * y) % q == x for y in range(1, q)) else -1
+
+
+def paley_hadamard(n: int) -> np.ndarray:
+    """Hadamard matrix of order 12 or 44 (Paley's first construction, q = n-1 = 3 mod 4) or 28
+    (Paley's second construction, q = 13 = 1 mod 4), entries +-1, int64.
+
+    First construction: H = I + S with the skew matrix S = [[0, 1^T], [-1, Q]], Q[i,j] = chi(j - i).
+    Second: H = S (x) [[1,1],[1,-1]] + I (x) [[1,-1],[-1,-1]] with the symmetric 14 x 14 matrix
+    S = [[0, 1^T], [1, Q]], Q[i,j] = chi(i - j).
+    """
+    if n in (12, 44):
+        q = n - 1
+        S = np.zeros((n, n), dtype=np.int64)
+        S[0, 1:] = 1
+        S[1:, 0] = -1
+        for i in range(q):
+            for j in range(q):
+                S[1 + i, 1 + j] = _legendre(j - i, q)
+        return np.eye(n, dtype=np.int64) + S
+    if n == 28:
+        q = 13
+        S = np.zeros((q + 1, q + 1), dtype=np.int64)
+        S[0, 1:] = 1
+        S[1:, 0] = 1
+        for i in range(q):
+            for j in range(q):
+                S[1 + i, 1 + j] = _legendre(i - j, q)
+        A = np.array([[1, 1], [1, -1]], dtype=np.int64)
+        B = np.array([[1, -1], [-1, -1]], dtype=np.int64)
+        return np.kron(S, A) + np.kron(np.eye(q + 1, dtype=np.int64), B)
+    raise ValueError("no Paley matrix of that order here")
+
+
+def sylvester_hadamard(n: int) -> np.ndarray:
+    """H[i,j] = (-1)^popcount(i & j) for n a power of two (Sylvester's construction, natural order)."""
+    assert n >= 1 and n & (n - 1) == 0
+    i = np.arange(n)
+    bits = i[:, None] & i[None, :]
+    par = np.zeros((n, n), dtype=np.int64)
+    while np.any(bits):
+        par ^= bits & 1
+        bits >>= 1
+    return 1 - 2 * par
+
+
+def hadamard_split(n: int) -> Tuple[int, int]:
+    """n = m * 2^k with m in {1, 12, 28, 44}: m is 1 for a power of two, else four times the odd part."""
+    odd = n
+    while odd % 2 == 0:
+        odd //= 2
+    if odd == 1:
+        return 1, n
+    m = 4 * odd
+    if m not in (12, 28, 44) or n % m != 0:
+        raise ValueError(f"no Hadamard matrix of order {n} here")
+    return m, n // m
+
+
+def hadamard_matrix(n: int) -> np.ndarray:
+    """H_m (x) H_{2^k} (Kronecker product: index i = a*2^k + b), entries +-1."""
+    m, p = hadamard_split(n)
+    Hm = np.ones((1, 1), dtype=np.int64) if m == 1 else paley_hadamard(m)
+    return np.kron(Hm, sylvester_hadamard(p))
+
+
+def hadamard_rows(h: np.ndarray) -> np.ndarray:
+    """h' = h H_n / sqrt(n) for every row of h (n = row length): an orthogonal change of basis."""
+    h = np.asarray(h, dtype=np.float64)
+    n = h.shape[1]
+    return (h @ hadamard_matrix(n).astype(np.float64)) / np.sqrt(float(n))
+
+
+def expert_ffn(a_rows: np.ndarray, expert: Dict[str, Tuple[np.ndarray, np.ndarray]],
+               h_bits: int = 0) -> Dict[str, np.ndarray]:
+    """SwiGLU expert on de-quantized rows a = s*q: returns g, u, h, o (all float64).
+
+    h_bits = 4 or 8: the online-Hadamard variant.  The intermediate is rotated, h' = h H / sqrt(I),
+    quantized per row to h_bits like the layer's input, and the down projection (whose weights are
+    clustered in that rotated basis) reads the de-quantized codes; hq, hs are returned too.
+    """
     g = codebook_matmul(a_rows, *expert["gate"])
     u = codebook_matmul(a_rows, *expert["up"])
     h = silu(g) * u
+    if h_bits:
+        hr = hadamard_rows(h)
+        hq, hs = quantize(hr, h_bits)
+        o = codebook_matmul(hs[:, None] * hq.astype(np.float64), *expert["down"])
+        return {"g": g, "u": u, "h": h, "hr": hr, "hq": hq, "hs": hs, "o": o}
     o = codebook_matmul(h, *expert["down"])
     return {"g": g, "u": u, "h": h, "o": o}
 
@@ -199,11 +296,13 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
                 experts: Sequence[Dict[str, Tuple[np.ndarray, np.ndarray]]],
                 n_routed: int, top_k: int, act_bits: int,
                 only_tokens: Optional[np.ndarray] = None,
-                keep_expert_outputs: bool = False) -> Dict[str, np.ndarray]:
+                keep_expert_outputs: bool = False, h_bits: int = 0) -> Dict[str, np.ndarray]:
     """Forward pass of one layer.  experts = n_routed routed experts followed by shared experts.
 
     only_tokens: if given, expert FFNs and Y are evaluated for these token rows only (the front
     end -- rotation, codes, routing, permutation -- is always computed for every token).
+    h_bits: 0, or the bit width of the online-Hadamard variant's second quantization (see expert_ffn);
+    with keep_expert_outputs the rotated intermediates and their codes come back per sorted row.
     """
     T = X.shape[0]
     XR = rotate(X, R)
@@ -221,6 +320,12 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
     Y = np.zeros((T, X.shape[1]), dtype=np.float64)
     n_assign = T * top_k
     o_sorted = np.zeros((n_assign, X.shape[1]), dtype=np.float64) if keep_expert_outputs else None
+    n_shared = len(experts) - n_routed
+    keep_h = keep_expert_outputs and h_bits
+    I = experts[0]["down"][0].shape[1] * 2 if experts else 0
+    hr_sorted = np.zeros((n_assign + n_shared * T, I), dtype=np.float64) if keep_h else None
+    hq_sorted = np.zeros((n_assign + n_shared * T, I), dtype=np.int32) if keep_h else None
+    hs_sorted = np.ones(n_assign + n_shared * T, dtype=np.float64) if keep_h else None
     # routed experts, in the order j = 0..k-1 per token (fixed summation order)
     contrib = np.zeros((T, top_k, X.shape[1]), dtype=np.float64)
     for e in range(n_routed):
@@ -230,17 +335,22 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
         keep = tok_mask[toks]
         if not np.any(keep):
             continue
-        res = expert_ffn(a[toks[keep]], experts[e])
+        res = expert_ffn(a[toks[keep]], experts[e], h_bits)
         contrib[toks[keep], assign[keep] % top_k] = res["o"]
         if keep_expert_outputs:
             o_sorted[pos[keep]] = res["o"]
+        if keep_h:
+            hr_sorted[pos[keep]], hq_sorted[pos[keep]], hs_sorted[pos[keep]] = res["hr"], res["hq"], res["hs"]
     for j in range(top_k):
         Y += w[:, j:j + 1] * contrib[:, j]
     shared_o = []
     for s in range(n_routed, len(experts)):
         rows = np.nonzero(tok_mask)[0]
-        res = expert_ffn(a[rows], experts[s])
+        res = expert_ffn(a[rows], experts[s], h_bits)
         Y[rows] += res["o"]
+        if keep_h:
+            base = n_assign + (s - n_routed) * T
+            hr_sorted[base + rows], hq_sorted[base + rows], hs_sorted[base + rows] = res["hr"], res["hq"], res["hs"]
         if keep_expert_outputs:
             full = np.zeros((T, X.shape[1]), dtype=np.float64)
             full[rows] = res["o"]
@@ -251,6 +361,8 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
     if keep_expert_outputs:
         out["o_sorted"] = o_sorted
         out["o_shared"] = shared_o
+    if keep_h:
+        out["hr_sorted"], out["hq_sorted"], out["hs_sorted"] = hr_sorted, hq_sorted, hs_sorted
     return out
 
 

@@ -47,6 +47,7 @@ class LayerConfig:
     n_outliers: int
     outlier_scale: float
     zipf_s: float = 0.0  # > 0: router bias makes expert popularity follow Zipf(s)
+    h_bits: int = 0      # 4 or 8: online-Hadamard variant (the intermediate is rotated and quantized)
 
     @property
     def seed(self) -> int:

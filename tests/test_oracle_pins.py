@@ -356,6 +356,115 @@ def test_moe_forward_against_token_loop(shared, bits, k):
     assert not sub["Y"][[0, 2, 3]].any()
 
 
+# ------------------------------------------------------------------------------------------
+# online Hadamard variant
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [12, 28, 44])
+def test_paley_matrices_are_hadamard(n):
+    """Defining property H H^T = n I in exact integers; Paley I gives I + skew, Paley II a symmetric matrix."""
+    H = O.paley_hadamard(n)
+    assert H.shape == (n, n) and set(np.unique(H).tolist()) == {-1, 1}
+    assert np.array_equal(H @ H.T, n * np.eye(n, dtype=np.int64))
+    S = H - np.eye(n, dtype=np.int64)
+    if n == 28:
+        assert np.array_equal(H, H.T)
+    else:
+        assert np.array_equal(S, -S.T) and np.all(H[0] == 1)
+
+
+def test_sylvester_matches_library_and_recursion():
+    for n in (1, 2, 8, 64, 512):
+        H = O.sylvester_hadamard(n)
+        assert np.array_equal(H, scipy.linalg.hadamard(n))          # library routine
+        if n > 1:
+            h = O.sylvester_hadamard(n // 2)
+            assert np.array_equal(H, np.block([[h, h], [h, -h]]))    # textbook recursion
+
+
+@pytest.mark.parametrize("n,split", [(512, (1, 512)), (768, (12, 64)), (1408, (44, 32)), (14336, (28, 512))])
+def test_hadamard_split_and_kronecker_structure(n, split):
+    assert O.hadamard_split(n) == split
+    if n <= 1408:
+        H = O.hadamard_matrix(n)
+        assert np.array_equal(H @ H.T, n * np.eye(n, dtype=np.int64))
+        m, p = split
+        a, b, a2, b2 = 3 % m, 5 % p, 7 % m, 11 % p
+        Hm = np.ones((1, 1), dtype=np.int64) if m == 1 else O.paley_hadamard(m)
+        assert H[a * p + b, a2 * p + b2] == Hm[a, a2] * (-1) ** bin(b & b2).count("1")
+    with pytest.raises(ValueError):
+        O.hadamard_split(5 * 64)
+
+
+def _fwht_loop(v):
+    """Fast Walsh-Hadamard transform written as the textbook butterfly loop (power-of-two length)."""
+    v = [float(x) for x in v]
+    h = 1
+    while h < len(v):
+        for i in range(0, len(v), 2 * h):
+            for j in range(i, i + h):
+                v[j], v[j + h] = v[j] + v[j + h], v[j] - v[j + h]
+        h *= 2
+    return v
+
+
+def test_hadamard_rows_against_butterfly_and_orthogonality():
+    rng = np.random.default_rng(11)
+    h = rng.standard_normal((3, 64))
+    got = O.hadamard_rows(h)
+    for r in range(3):
+        assert np.allclose(got[r], np.asarray(_fwht_loop(h[r])) / 8.0, rtol=0, atol=1e-12)
+    assert np.allclose(O.hadamard_rows(got), h, atol=1e-12)              # symmetric orthogonal: an involution
+    for n in (768, 1408):
+        x = rng.standard_normal((2, n))
+        y = O.hadamard_rows(x)
+        assert np.allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=1e-12)
+        # mixed order: block a of the result = sum_a' Hm[a', a] * FWHT(block a') / sqrt(n)
+        m, p = O.hadamard_split(n)
+        Hm = O.paley_hadamard(m)
+        blocks = np.stack([np.asarray(_fwht_loop(x[0, a * p:(a + 1) * p])) for a in range(m)])
+        want = (Hm.T.astype(np.float64) @ blocks).reshape(-1) / math.sqrt(n)
+        assert np.allclose(y[0], want, atol=1e-10)
+    e = np.zeros((1, 768)); e[0, 5] = 1.0                                  # a unit vector picks out a row of H
+    assert np.allclose(O.hadamard_rows(e)[0] * math.sqrt(768), O.hadamard_matrix(768)[5])
+
+
+def test_online_hadamard_ffn_reduces_to_plain_ffn_without_rounding():
+    """With a down projection whose dense weights are W H / sqrt(I) the rotation cancels (orthogonality):
+    the had variant evaluated without the second rounding equals the plain FFN on W."""
+    rng = np.random.default_rng(12)
+    I, H, n = 64, 8, 5
+    h = rng.standard_normal((n, I))
+    W = rng.standard_normal((H, I))
+    Wrot = O.hadamard_rows(W)                 # rows of W in the rotated basis
+    assert np.allclose(O.hadamard_rows(h) @ Wrot.T, h @ W.T, atol=1e-12)
+
+
+@pytest.mark.parametrize("h_bits", [4, 8])
+def test_online_hadamard_expert_and_layer_consistency(h_bits):
+    cfg = synth.small_variant(synth.CONFIGS["tiny"], T=6, H=64, I=96, E=3, top_k=2, outlier_channels=(3, 41))   # I = 12 * 8
+    L = synth.make_layer(cfg)
+    a = np.random.default_rng(13).standard_normal((4, cfg.H))
+    res = O.expert_ffn(a, L.experts[0], h_bits)
+    plain = O.expert_ffn(a, L.experts[0])
+    assert np.array_equal(res["h"], plain["h"])
+    hq, hs = O.quantize(O.hadamard_rows(plain["h"]), h_bits)
+    assert np.array_equal(res["hq"], hq) and np.array_equal(res["hs"], hs)
+    W = O.decode_weights(*L.experts[0]["down"])
+    assert np.allclose(res["o"], (hs[:, None] * hq) @ W.T, rtol=1e-12, atol=1e-12)
+    qmax = 2 ** (h_bits - 1) - 1
+    assert np.abs(hq).max() == qmax
+    # the layer: token-by-token evaluation with the same functions
+    out = O.moe_forward(L.X, L.R, L.Wr, L.bias, L.experts, cfg.E, cfg.top_k, cfg.act_bits, h_bits=h_bits,
+                        keep_expert_outputs=True)
+    aq = out["scale"][:, None] * out["q"]
+    for t in range(cfg.T):
+        y = np.zeros(cfg.H)
+        for j in range(cfg.top_k):
+            y += out["w"][t, j] * O.expert_ffn(aq[t:t + 1], L.experts[out["ids"][t, j]], h_bits)["o"][0]
+        assert np.allclose(out["Y"][t], y, rtol=1e-12, atol=1e-12)
+    assert out["hq_sorted"].shape == (cfg.T * cfg.top_k, cfg.I) and np.abs(out["hq_sorted"]).max() == qmax
+
+
 def test_generator_properties():
     cfg = synth.CONFIGS["tiny"]
     L = synth.make_layer(cfg)
