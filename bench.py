@@ -74,7 +74,7 @@ def cpu_baseline(L, budget_s):
     t1 = time.perf_counter()
     for e in active:
         toks = perm[offsets[e]:offsets[e + 1]] // cfg.top_k if e < cfg.E else np.arange(cfg.T)
-        O.expert_ffn(a[toks], L.experts[e])
+        O.expert_ffn(a[toks], L.experts[e], getattr(cfg, "h_bits", 0))
         done += 1
         rows_done += len(toks)
         t_exp = time.perf_counter() - t1
@@ -193,7 +193,9 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name} (E={cfg.E} top-{cfg.top_k} S={cfg.S} H={cfg.H} I={cfg.I} T={cfg.T} "
-                               f"A{cfg.act_bits}W4, 16 bf16 centroids per weight row)",
+                               f"A{cfg.act_bits}W4, 16 bf16 centroids per weight row"
+                               + (f", online Hadamard + A{cfg.h_bits} in front of the down projection)"
+                                  if getattr(cfg, "h_bits", 0) else ")"),
                    "active_experts": active, "rows": rows,
                    "max_tokens_per_expert": int(counts.max()), "mean_tokens_per_expert": float(counts.mean())},
         "roofline": roofline,

@@ -85,6 +85,9 @@ typedef struct {
   cq_codebook_weights gate_up; /* G = E+S, N = 2I (gate/up interleaved), K = H          */
   cq_codebook_weights down;    /* G = E+S, N = H, K = I                                 */
   const void* R_split; /* optional: copy of R written by cq_rotation_split(); NULL if absent */
+  int h_bits;          /* 0, or 4 / 8: online-Hadamard variant -- the intermediate h is multiplied by
+                          H_I / sqrt(I) and quantized per row to h_bits before the down projection,
+                          whose weights are then clustered in that rotated basis (cq_hadamard_quant) */
 } cq_layer;
 
 const char* cq_status_string(cq_status st);
@@ -166,6 +169,19 @@ cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W,
                                    void* workspace, size_t workspace_bytes, cq_stream stream);
 
 /*
+ * Online-Hadamard variant (evaluation section, the "had" setting): rows h [M, I] f32 -> h' = h H_I / sqrt(I)
+ * and its per-row symmetric integer quantization (same rule as cq_rotate_quant).  H_I = H_m (x) H_{2^k}
+ * (Kronecker product, index i = a*2^k + b) with the Sylvester matrix H_{2^k}[b,b'] = (-1)^popcount(b & b')
+ * and m = 1 when I is a power of two, else m = 4 * (odd part of I) in {12, 28, 44} with Paley's matrices:
+ * m = 12, 44: H_m = I + S, S = [[0, 1^T], [-1, Q]], Q[i,j] = chi(j - i) mod m-1; m = 28:
+ * H_m = S (x) [[1,1],[1,-1]] + I (x) [[1,-1],[-1,-1]], S = [[0, 1^T], [1, Q]], Q[i,j] = chi(i - j) mod 13.
+ *   HR_out [M, I] f32 or NULL (the rotated rows), Q_out [M, I] int8, scale_out [M] f32.
+ *   I % 4 == 0, I <= 16384, I of the form above (else CQ_ERR_SHAPE); bits in {4, 8}; M = 0 is allowed.
+ */
+cq_status cq_hadamard_quant(const float* Hrows, int M, int I, int bits, float* HR_out, int8_t* Q_out,
+                            float* scale_out, cq_stream stream);
+
+/*
  * a8: weighted combine (MoE weighted sum; shared expert per the appendix on DeepSeek-V2-Lite):
  *   Y[t,:] = sum_{j<k} topk_w[t,j] * O[inv_perm[t*k+j], :] + sum_{s<S} O[T*k + s*T + t, :]
  * summed in the fixed order j = 0..k-1, then s = 0..S-1 (deterministic).  O [T*(k+S), H] f32.
@@ -182,6 +198,8 @@ cq_status cq_combine(const float* O, const float* topk_w, const int32_t* inv_per
 typedef struct {
   size_t total;
   size_t XR, Q, Q16, scale, logits, topk_ids, topk_w, offsets, perm, inv_perm, src_token, Hbuf, Obuf, scratch;
+  size_t HQ, HQ16, hscale; /* online-Hadamard variant: codes of the rotated intermediate [T*(k+S), I] i8,
+                              the same as bf16 (large batches), their scales [T*(k+S)] f32; Hbuf is f32 then */
 } cq_moe_layout;
 size_t cq_moe_workspace_bytes(const cq_layer* L, int T);
 cq_status cq_moe_workspace_layout(const cq_layer* L, int T, cq_moe_layout* out);

@@ -323,6 +323,7 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
     n_shared = len(experts) - n_routed
     keep_h = keep_expert_outputs and h_bits
     I = experts[0]["down"][0].shape[1] * 2 if experts else 0
+    h_sorted = np.zeros((n_assign + n_shared * T, I), dtype=np.float64) if keep_h else None
     hr_sorted = np.zeros((n_assign + n_shared * T, I), dtype=np.float64) if keep_h else None
     hq_sorted = np.zeros((n_assign + n_shared * T, I), dtype=np.int32) if keep_h else None
     hs_sorted = np.ones(n_assign + n_shared * T, dtype=np.float64) if keep_h else None
@@ -341,6 +342,7 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
             o_sorted[pos[keep]] = res["o"]
         if keep_h:
             hr_sorted[pos[keep]], hq_sorted[pos[keep]], hs_sorted[pos[keep]] = res["hr"], res["hq"], res["hs"]
+            h_sorted[pos[keep]] = res["h"]
     for j in range(top_k):
         Y += w[:, j:j + 1] * contrib[:, j]
     shared_o = []
@@ -351,6 +353,7 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
         if keep_h:
             base = n_assign + (s - n_routed) * T
             hr_sorted[base + rows], hq_sorted[base + rows], hs_sorted[base + rows] = res["hr"], res["hq"], res["hs"]
+            h_sorted[base + rows] = res["h"]
         if keep_expert_outputs:
             full = np.zeros((T, X.shape[1]), dtype=np.float64)
             full[rows] = res["o"]
@@ -363,6 +366,7 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
         out["o_shared"] = shared_o
     if keep_h:
         out["hr_sorted"], out["hq_sorted"], out["hs_sorted"] = hr_sorted, hq_sorted, hs_sorted
+        out["h_sorted"] = h_sorted
     return out
 
 

@@ -25,7 +25,7 @@ EXPORTS = [
     "cq_codebook_grouped_gemm", "cq_combine", "cq_moe_workspace_bytes", "cq_moe_workspace_layout",
     "cq_moe_forward", "cq_moe_forward_timed", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
     "cq_stream_read", "cq_mfma_loop", "cq_rotation_split_bytes", "cq_rotation_split",
-    "cq_rotate_quant_split_workspace_bytes", "cq_rotate_quant_split",
+    "cq_rotate_quant_split_workspace_bytes", "cq_rotate_quant_split", "cq_hadamard_quant",
 ]
 
 
@@ -38,13 +38,14 @@ class Layer(ctypes.Structure):
     _fields_ = [("H", ctypes.c_int), ("I", ctypes.c_int), ("E", ctypes.c_int), ("top_k", ctypes.c_int),
                 ("S", ctypes.c_int), ("act_bits", ctypes.c_int),
                 ("R", ctypes.c_void_p), ("Wr", ctypes.c_void_p), ("bias", ctypes.c_void_p),
-                ("gate_up", CodebookWeights), ("down", CodebookWeights), ("R_split", ctypes.c_void_p)]
+                ("gate_up", CodebookWeights), ("down", CodebookWeights), ("R_split", ctypes.c_void_p),
+                ("h_bits", ctypes.c_int)]
 
 
 class MoeLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
                 ("total", "XR", "Q", "Q16", "scale", "logits", "topk_ids", "topk_w", "offsets", "perm", "inv_perm",
-                 "src_token", "Hbuf", "Obuf", "scratch")]
+                 "src_token", "Hbuf", "Obuf", "scratch", "HQ", "HQ16", "hscale")]
 
 
 _lib = None
@@ -97,6 +98,8 @@ def load_library() -> ctypes.CDLL:
     lib.cq_rotate_quant_split_workspace_bytes.argtypes = [ci, ci]
     lib.cq_rotate_quant_split.restype = ci
     lib.cq_rotate_quant_split.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.cq_hadamard_quant.restype = ci
+    lib.cq_hadamard_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     lib.cq_prepack_bytes.restype = sz
     lib.cq_prepack_bytes.argtypes = [ctypes.POINTER(CodebookWeights)]
     lib.cq_prepack.restype = ci
@@ -236,6 +239,18 @@ def cq_rotate_quant_split(X, R_split, act_bits: int) -> Dict[str, object]:
     return {"XR": XR, "Q": Q, "scale": scale}
 
 
+def cq_hadamard_quant(Hrows, bits: int) -> Dict[str, object]:
+    """h' = h H / sqrt(I) per row (device fp32 [M, I]) and its integer codes and scales."""
+    torch = _torch()
+    lib = load_library()
+    M, I = Hrows.shape
+    HR = torch.empty((M, I), dtype=torch.float32, device="cuda")
+    Q = torch.empty((M, I), dtype=torch.int8, device="cuda")
+    scale = torch.empty((M,), dtype=torch.float32, device="cuda")
+    _check(lib.cq_hadamard_quant(_ptr(Hrows), M, I, bits, _ptr(HR), _ptr(Q), _ptr(scale), _stream()))
+    return {"HR": HR, "Q": Q, "scale": scale}
+
+
 def cq_route_permute(XR, Wr, bias, top_k: int, n_shared: int = 0, logits_in=None) -> Dict[str, object]:
     torch = _torch()
     lib = load_library()
@@ -309,7 +324,7 @@ class DeviceLayer:
         c = self.cfg
         return Layer(c.H, c.I, c.E, c.top_k, c.S, c.act_bits, _ptr(self.R), _ptr(self.Wr), _ptr(self.bias),
                      self.gate_up.struct(self.use_prepacked), self.down.struct(self.use_prepacked),
-                     _ptr(self.R_split))
+                     _ptr(self.R_split), getattr(c, "h_bits", 0))
 
     def workspace(self, T: int):
         if self._ws is None or self._ws_T != T:
@@ -376,8 +391,11 @@ def moe_intermediates(layer: DeviceLayer, T: int) -> Dict[str, object]:
         "perm": view(lay.perm, A * 4, torch.int32, (A,)),
         "inv_perm": view(lay.inv_perm, A * 4, torch.int32, (A,)),
         "src_token": view(lay.src_token, M * 4, torch.int32, (M,)),
-        "h": view(lay.Hbuf, M * c.I * 2, torch.float16, (M, c.I)),
+        "h": (view(lay.Hbuf, M * c.I * 4, torch.float32, (M, c.I)) if getattr(c, "h_bits", 0)
+              else view(lay.Hbuf, M * c.I * 2, torch.float16, (M, c.I))),
         "o": view(lay.Obuf, M * c.H * 4, torch.float32, (M, c.H)),
+        "hq": view(lay.HQ, M * c.I, torch.int8, (M, c.I)) if getattr(c, "h_bits", 0) else None,
+        "hscale": view(lay.hscale, M * 4, torch.float32, (M,)) if getattr(c, "h_bits", 0) else None,
     }
 
 

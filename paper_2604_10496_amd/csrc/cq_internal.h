@@ -56,6 +56,11 @@ size_t cq_rotate_split_workspace_bytes(int T, int H);
 cq_status cq_rotate_split_launch(const float* X, const void* R_split, int T, int H, float* XR_out, void* workspace,
                                  hipStream_t s);
 
+// online-Hadamard variant: h' = h H / sqrt(I) per row, then integer codes (int8 and/or bf16 copies) and scales
+bool cq_hadamard_supported(int I);
+cq_status cq_hadamard_quant_launch(const float* Hin, int M, int I, int bits, int8_t* Q, uint16_t* Q16, float* scale,
+                                   float* HR, hipStream_t s);
+
 cq_status cq_topk_launch(const float* logit_partials, int ksplit, const float* bias, int T, int E, int top_k,
                          float* logits_out, int32_t* topk_ids, float* topk_w, hipStream_t s);
 size_t cq_permute_workspace_bytes(int T, int E, int top_k);

@@ -12,6 +12,8 @@ cq_status validate_layer(const cq_layer* L, int T) {
   if (L->H % 64 != 0 || L->I % 64 != 0 || L->top_k > L->E || L->top_k > 64 || L->E > 1024) return CQ_ERR_SHAPE;
   if ((long)T * (L->top_k + L->S) > 0x7fffffffL) return CQ_ERR_SHAPE;
   if (L->act_bits != 4 && L->act_bits != 8) return CQ_ERR_UNSUPPORTED;
+  if (L->h_bits != 0 && L->h_bits != 4 && L->h_bits != 8) return CQ_ERR_UNSUPPORTED;
+  if (L->h_bits != 0 && !cq_hadamard_supported(L->I)) return CQ_ERR_SHAPE;
   const int G = L->E + L->S;
   if (L->gate_up.G != G || L->gate_up.N != 2 * L->I || L->gate_up.K != L->H) return CQ_ERR_SHAPE;
   if (L->down.G != G || L->down.N != L->H || L->down.K != L->I) return CQ_ERR_SHAPE;
@@ -46,8 +48,12 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   o->perm = take(A * 4);
   o->inv_perm = take(A * 4);
   o->src_token = take(M * 4);
-  o->Hbuf = take(M * L->I * 2);
+  o->Hbuf = take(M * L->I * (L->h_bits ? 4 : 2));  // f16, or fp32 when it is rotated and quantized next
   o->Obuf = take(M * L->H * 4);
+  const bool hq16 = L->h_bits && M > 32 && cq_gemm_large_supported(&L->down);
+  o->HQ = take(L->h_bits ? M * L->I : 0);
+  o->HQ16 = take(hq16 ? M * L->I * 2 : 0);
+  o->hscale = take(L->h_bits ? M * 4 : 0);
   size_t scratch = cq_rotate_quant_workspace_bytes(T, L->H);
   const size_t r = cq_route_permute_workspace_bytes(T, L->H, L->E, L->top_k);
   if (r > scratch) scratch = r;
@@ -62,7 +68,7 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   }
   {
     size_t g2 = cq_gemm_partials_bytes(&L->down, (int)M, CQ_EPI_NONE);
-    if (M > 32 && cq_gemm_large_supported(&L->down))
+    if (M > 32 && cq_gemm_large_supported(&L->down))  // (16-bit operands in either variant: f16 h or bf16 codes)
       g2 += cq_gemm_large_workspace_bytes(L->down.G, (int)M, L->down.K, false);
     if (g2 > scratch) scratch = g2;
   }
@@ -153,12 +159,26 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
   // (internal launcher: the layer was validated above and the scratch area is sized for 16-bit operands)
   st = cq_gemm_codebook_launch(&L->gate_up, bf16_codes ? (const void*)Q16 : (const void*)Q,
                                bf16_codes ? CQ_A_BF16 : CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU,
-                               Hbuf, CQ_OUT_F16, scratch, hs, nullptr);
+                               Hbuf, L->h_bits ? CQ_OUT_F32 : CQ_OUT_F16, scratch, hs, nullptr);
   if (st != CQ_OK) return st;
   if (!mark(3)) return CQ_ERR_HIP;
   int down_splits = 1;  // > 1: the down projection left K-split partial sums in the scratch area
-  st = cq_gemm_codebook_launch(&L->down, Hbuf, CQ_A_F16, nullptr, nullptr, offsets, M, CQ_EPI_NONE, Obuf, CQ_OUT_F32,
-                               scratch, hs, &down_splits);
+  if (L->h_bits) {
+    // online-Hadamard variant: rotate and quantize the intermediate (counted in the down stage), then the
+    // down projection reads integer codes and per-row scales like the gate/up projection does
+    int8_t* HQ = (int8_t*)(ws + lay.HQ);
+    float* hscale = (float*)(ws + lay.hscale);
+    const bool hq16 = M > 32 && cq_gemm_large_supported(&L->down);
+    uint16_t* HQ16 = hq16 ? (uint16_t*)(ws + lay.HQ16) : nullptr;
+    st = cq_hadamard_quant_launch((const float*)Hbuf, M, L->I, L->h_bits, HQ, HQ16, hscale, nullptr, hs);
+    if (st != CQ_OK) return st;
+    st = cq_gemm_codebook_launch(&L->down, hq16 ? (const void*)HQ16 : (const void*)HQ,
+                                 hq16 ? CQ_A_BF16 : CQ_A_INT8_CODES, hscale, nullptr, offsets, M, CQ_EPI_NONE, Obuf,
+                                 CQ_OUT_F32, scratch, hs, &down_splits);
+  } else {
+    st = cq_gemm_codebook_launch(&L->down, Hbuf, CQ_A_F16, nullptr, nullptr, offsets, M, CQ_EPI_NONE, Obuf, CQ_OUT_F32,
+                                 scratch, hs, &down_splits);
+  }
   if (st != CQ_OK) return st;
   if (!mark(4)) return CQ_ERR_HIP;
   st = down_splits > 1 ? cq_combine_launch((const float*)scratch, down_splits, (size_t)M * L->H, tw, inv_perm, T,

@@ -71,6 +71,11 @@ CONFIGS: Dict[str, LayerConfig] = {
                     outlier_channels=(), n_outliers=8, outlier_scale=100.0),
         LayerConfig("qwen3_zipf", 4, E=128, top_k=8, S=0, H=2048, I=768, T=2048, act_bits=4,
                     outlier_channels=(), n_outliers=4, outlier_scale=100.0, zipf_s=1.1),
+        # online-Hadamard variants of the two Mixtral-shaped workloads (same inputs as configurations 1, 2)
+        LayerConfig("mixtral_decode_had", 1, E=8, top_k=2, S=0, H=4096, I=14336, T=16, act_bits=8,
+                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, h_bits=8),
+        LayerConfig("mixtral_prefill_had", 2, E=8, top_k=2, S=0, H=4096, I=14336, T=4096, act_bits=4,
+                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, h_bits=4),
     ]
 }
 

@@ -87,6 +87,12 @@ def test_argument_validation_happens_before_any_device_call():
     assert lib.cq_rotate_quant_split(one, one, 256, 256, 5, one, one, one, one, 1 << 30, None) == 3
     assert lib.cq_rotate_quant_split(one, one, 256, 256, 8, one, one, one, one, 64, None) == 4
     assert lib.cq_rotate_quant_split_workspace_bytes(256, 256) >= 2 * 256 * 256 * 2 + 256 * 4
+    # online-Hadamard transform of rows
+    assert lib.cq_hadamard_quant(None, 4, 512, 8, None, one, one, None) == 1
+    assert lib.cq_hadamard_quant(one, 4, 320, 8, None, one, one, None) == 2       # 5 * 64: no such matrix here
+    assert lib.cq_hadamard_quant(one, 4, 1 << 15, 8, None, one, one, None) == 2   # row longer than LDS holds
+    assert lib.cq_hadamard_quant(one, 4, 768, 5, None, one, one, None) == 3
+    assert lib.cq_hadamard_quant(None, 0, 768, 8, None, None, None, None) == 0
 
 
 def test_workspace_sizes_are_pure_and_monotone():

@@ -346,17 +346,75 @@ def test_gemm_swiglu_epilogue(B, out_kind, I, counts):
 # ---------------------------------------------------------------------------------------------
 # the whole layer
 # ---------------------------------------------------------------------------------------------
+H_TOL = 2e-3   # intermediate h against the oracle, relative to the row maximum
+
+
+def _check_had_codes(mid, ref, bits, rows=None):
+    """Online-Hadamard variant, per sorted row.  The gate/up product accumulates on bf16 matrix cores, whose
+    sums of cancelling terms carry errors far above fp32 rounding of the result (seen: 8e-4 of a row's
+    maximum), so the codes of the rotated intermediate cannot be compared with codes computed from the
+    oracle's own h.  Instead (a) h itself is compared with the oracle's, to the tolerance of this path, and
+    (b) the new step is checked exactly: the codes must be those of the oracle's transform + quantization
+    applied to the SAME h (the one the GPU produced), equal except +-1 at rounding ties."""
+    sel = slice(None) if rows is None else rows
+    h = mid["h"].cpu().numpy().astype(np.float64)[sel]
+    h_ref = ref["h_sorted"][sel]
+    herr = np.abs(h - h_ref).max(axis=1) / np.maximum(np.abs(h_ref).max(axis=1), 1e-300)
+    hr = O.hadamard_rows(h)
+    q_ref, s_ref = O.quantize(hr, bits)
+    n = Hp.check_codes(mid["hq"].cpu().numpy()[sel], q_ref, hr, s_ref)
+    assert np.allclose(mid["hscale"].cpu().numpy()[sel], s_ref, rtol=1e-5)
+    _say(f"  intermediate: max |h error| / row max = {herr.max():.2e}; rotated codes differing at ties: {n} of {hr.size}")
+    assert herr.max() <= H_TOL
+    assert n <= max(2, hr.size // 500)
+
+
+HAD_END_TO_END_TOL = 2e-2   # online-Hadamard variant against the pure oracle (see _had_reference_output)
+
+
+def _had_reference_output(L, ref, mid, toks):
+    """Online-Hadamard variant: the layer output the oracle's functions give for the codes and scales the GPU
+    produced (down projection by the dense definition, weighted sum in the fixed order).  The second
+    quantizer turns the accumulation error of the gate/up product into code flips, so the output is compared
+    (to the usual tolerance) with this reference, and with the pure oracle only to a bound that allows for
+    those flips."""
+    cfg = L.cfg
+    hq = mid["hq"].cpu().numpy().astype(np.float64)
+    hs = mid["hscale"].cpu().numpy().astype(np.float64)
+    Y = np.zeros((len(toks), cfg.H))
+    inv = ref["inv_perm"].reshape(cfg.T, cfg.top_k)
+    offsets = ref["offsets"]
+    dense = {}
+    for n, t in enumerate(toks):
+        for j in range(cfg.top_k):
+            e = int(ref["ids"][t, j])
+            if e not in dense:
+                dense[e] = O.decode_weights(*L.experts[e]["down"])
+            m = int(inv[t, j])
+            assert offsets[e] <= m < offsets[e + 1]
+            Y[n] += ref["w"][t, j] * (hs[m] * (dense[e] @ hq[m]))
+        for s_ in range(cfg.S):
+            e = cfg.E + s_
+            if e not in dense:
+                dense[e] = O.decode_weights(*L.experts[e]["down"])
+            m = cfg.T * cfg.top_k + s_ * cfg.T + t
+            Y[n] += hs[m] * (dense[e] @ hq[m])
+    return Y
+
+
 def _check_layer(B, cfg, only_tokens=None, label=""):
     import torch
     L = Hp.make_inputs(cfg)
     _say(f"layer {label or cfg.name}: T={cfg.T} H={cfg.H} I={cfg.I} E={cfg.E} k={cfg.top_k} S={cfg.S} "
          f"bits={cfg.act_bits} redrawn={L.redrawn_rows}")
-    ref = Hp.oracle_forward(L, only_tokens=only_tokens)
+    ref = Hp.oracle_forward(L, only_tokens=only_tokens, keep_expert_outputs=bool(cfg.h_bits))
     _say("  oracle done")
     layer = B.device_layer_from_inputs(L)
     Y = B.cq_moe_forward(layer, _dev(L.X))
     torch.cuda.synchronize()
     mid = B.moe_intermediates(layer, cfg.T)
+    if cfg.h_bits and only_tokens is None:
+        _check_had_codes(mid, ref, cfg.h_bits)
     n_tie = Hp.check_codes(mid["Q"].cpu().numpy(), ref["q"], ref["XR"], ref["scale"])
     # the rotation itself (fp32 matrix cores, or the split f16 product for many tokens): fp32-class error,
     # measured against the largest entry of the row
@@ -375,6 +433,10 @@ def _check_layer(B, cfg, only_tokens=None, label=""):
     err = Hp.row_rel_l2(Yh[rows], ref["Y"][rows])
     _say(f"  tie codes={n_tie} max row rel L2={err.max():.3e} mean={err.mean():.3e}")
     assert np.all(np.isfinite(Yh))
+    if cfg.h_bits:
+        assert err.max() <= HAD_END_TO_END_TOL
+        err = Hp.row_rel_l2(Yh[rows], _had_reference_output(L, ref, mid, rows))
+        _say(f"  against the oracle on the GPU's codes of the rotated intermediate: max row rel L2={err.max():.3e}")
     assert err.max() <= OUT_TOL
     # run twice: bit-identical (no atomics anywhere on the path)
     Y2 = B.cq_moe_forward(layer, _dev(L.X)).cpu().numpy()
@@ -395,6 +457,43 @@ def test_layer_tiny(B):
 def test_layer_reduced_shapes(B, name, over):
     cfg = synth.small_variant(synth.CONFIGS[name], **over)
     _check_layer(B, cfg, label=f"{name}-reduced")
+
+
+@pytest.mark.parametrize("name,over", [
+    ("tiny", dict(h_bits=8)),                                              # I = 512: a power of two
+    ("mixtral_decode", dict(H=512, I=1792, T=16, h_bits=8)),               # I = 28 * 64
+    ("mixtral_prefill", dict(H=256, I=768, T=300, h_bits=4)),              # I = 12 * 64, large-tile down product
+    ("dsv2lite", dict(H=256, I=704, T=100, E=16, h_bits=8)),               # I = 44 * 16, shared experts
+])
+def test_layer_online_hadamard(B, name, over):
+    cfg = synth.small_variant(synth.CONFIGS[name], **over)
+    _check_layer(B, cfg, label=f"{name}-had")
+
+
+@pytest.mark.parametrize("M,I,bits", [(5, 512, 8), (33, 768, 4), (7, 1408, 8), (4, 14336, 8), (3, 4096, 4),
+                                      (2, 64, 8), (0, 512, 8)])
+def test_hadamard_quant(B, M, I, bits):
+    """h H_I / sqrt(I) against the dense definition: powers of two and the three Paley orders, one row with an
+    outlier, one all-zero row."""
+    rng = np.random.default_rng(100 + I + M)
+    h = rng.standard_normal((M, I)).astype(np.float32)
+    if M > 1:
+        h[0, I // 3] = 300.0
+        h[1] = 0.0
+    _say(f"hadamard_quant M={M} I={I} bits={bits}")
+    out = B.cq_hadamard_quant(_dev(h), bits)
+    if M == 0:
+        return
+    ref = O.hadamard_rows(h)
+    q_ref, s_ref = O.quantize(ref, bits)
+    HR = out["HR"].cpu().numpy().astype(np.float64)
+    err = np.abs(HR - ref).max(axis=1) / np.maximum(np.abs(ref).max(axis=1), 1e-300)
+    _say(f"  max |error| / row max = {err.max():.2e}")
+    assert err.max() <= 4e-6
+    assert np.allclose(np.linalg.norm(HR, axis=1), np.linalg.norm(h.astype(np.float64), axis=1), rtol=1e-5)
+    assert np.allclose(out["scale"].cpu().numpy(), s_ref, rtol=1e-5)
+    n_tie = Hp.check_codes(out["Q"].cpu().numpy(), q_ref, ref, s_ref)
+    assert n_tie <= max(2, M * I // 500)
 
 
 def test_layer_without_prepack(B):
@@ -420,9 +519,12 @@ def _full_size(B, name, n_sample):
     _say("  gpu done; oracle front end + sampled tokens")
     rng = np.random.default_rng(7)
     toks = np.sort(rng.choice(cfg.T, size=min(n_sample, cfg.T), replace=False))
-    ref = Hp.oracle_forward(L, only_tokens=toks)
+    ref = Hp.oracle_forward(L, only_tokens=toks, keep_expert_outputs=bool(cfg.h_bits))
     mid = B.moe_intermediates(layer, cfg.T)
     n_tie = Hp.check_codes(mid["Q"].cpu().numpy(), ref["q"], ref["XR"], ref["scale"])
+    if cfg.h_bits:   # sorted rows that belong to the sampled tokens
+        a_rows = ref["inv_perm"].reshape(cfg.T, cfg.top_k)[toks].reshape(-1)
+        _check_had_codes(mid, ref, cfg.h_bits, rows=np.sort(a_rows))
     assert np.array_equal(mid["ids"].cpu().numpy(), ref["ids"])
     assert np.array_equal(mid["offsets"].cpu().numpy()[:cfg.E + 1], ref["offsets"])
     assert np.array_equal(mid["perm"].cpu().numpy(), ref["perm"])
@@ -434,12 +536,20 @@ def _full_size(B, name, n_sample):
     counts = np.diff(ref["offsets"])
     _say(f"  {name}: redrawn={L.redrawn_rows} tie codes={n_tie} sampled rows={toks.size} "
          f"max row rel L2={err.max():.3e} expert load min/mean/max={counts.min()}/{counts.mean():.1f}/{counts.max()}")
+    if cfg.h_bits:
+        assert err.max() <= HAD_END_TO_END_TOL
+        err = Hp.row_rel_l2(Yh[toks], _had_reference_output(L, ref, mid, toks))
+        _say(f"  against the oracle on the GPU's codes of the rotated intermediate: max row rel L2={err.max():.3e}")
     assert err.max() <= OUT_TOL
     return counts
 
 
 def test_full_mixtral_decode(B):
     _full_size(B, "mixtral_decode", 16)
+
+
+def test_full_mixtral_decode_online_hadamard(B):
+    _full_size(B, "mixtral_decode_had", 16)
 
 
 def test_full_dsv2lite(B):
