@@ -10,6 +10,7 @@ this machine's host cores on a bounded sample of the same workload.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -62,7 +63,8 @@ def cpu_baseline(L, budget_s):
         threads = os.cpu_count() or 1
     cfg = L.cfg
     t0 = time.perf_counter()
-    XR = O.rotate(L.X, L.R)
+    R = L.R if L.R is not None else O.hadamard_matrix(cfg.H) / math.sqrt(cfg.H)   # Hadamard rotation variant
+    XR = O.rotate(L.X, R)
     q, scale = O.quantize(XR, cfg.act_bits)
     logits = O.router_logits(XR, L.Wr, L.bias)
     ids, w = O.route_topk(logits, cfg.top_k)
@@ -194,6 +196,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name} (E={cfg.E} top-{cfg.top_k} S={cfg.S} H={cfg.H} I={cfg.I} T={cfg.T} "
                                f"A{cfg.act_bits}W4, 16 bf16 centroids per weight row"
+                               + (", Hadamard rotation" if getattr(cfg, "r_hadamard", False) else "")
                                + (f", online Hadamard + A{cfg.h_bits} in front of the down projection)"
                                   if getattr(cfg, "h_bits", 0) else ")"),
                    "active_experts": active, "rows": rows,

@@ -88,6 +88,8 @@ typedef struct {
   int h_bits;          /* 0, or 4 / 8: online-Hadamard variant -- the intermediate h is multiplied by
                           H_I / sqrt(I) and quantized per row to h_bits before the down projection,
                           whose weights are then clustered in that rotated basis (cq_hadamard_quant) */
+  int r_hadamard;      /* non-zero: the rotation is R = H_H / sqrt(H) (same matrices as cq_hadamard_quant) and a1
+                          runs as a fast transform; R is then not read and may be NULL                       */
 } cq_layer;
 
 const char* cq_status_string(cq_status st);

@@ -39,7 +39,7 @@ class Layer(ctypes.Structure):
                 ("S", ctypes.c_int), ("act_bits", ctypes.c_int),
                 ("R", ctypes.c_void_p), ("Wr", ctypes.c_void_p), ("bias", ctypes.c_void_p),
                 ("gate_up", CodebookWeights), ("down", CodebookWeights), ("R_split", ctypes.c_void_p),
-                ("h_bits", ctypes.c_int)]
+                ("h_bits", ctypes.c_int), ("r_hadamard", ctypes.c_int)]
 
 
 class MoeLayout(ctypes.Structure):
@@ -310,13 +310,15 @@ class DeviceLayer:
     def __init__(self, cfg, R, Wr, bias, gate_up: DeviceCodebook, down: DeviceCodebook, use_prepacked: bool = True):
         torch = _torch()
         self.cfg = cfg
-        self.R = torch.as_tensor(R).to("cuda").contiguous()
+        self.R = None if R is None else torch.as_tensor(R).to("cuda").contiguous()
         self.Wr = torch.as_tensor(Wr).to("cuda").contiguous()
         self.bias = None if bias is None else torch.as_tensor(bias).to("cuda").contiguous()
         self.gate_up, self.down = gate_up, down
         self.use_prepacked = use_prepacked
         # set-up work, like prepacking the indices: the split copy of R for the f16 matrix cores
-        self.R_split = cq_rotation_split(self.R) if use_prepacked and cfg.H % 32 == 0 else None
+        self.R_split = (cq_rotation_split(self.R)
+                        if use_prepacked and cfg.H % 32 == 0 and self.R is not None
+                        and not getattr(cfg, "r_hadamard", False) else None)
         self._ws = None
         self._ws_T = -1
 
@@ -324,7 +326,7 @@ class DeviceLayer:
         c = self.cfg
         return Layer(c.H, c.I, c.E, c.top_k, c.S, c.act_bits, _ptr(self.R), _ptr(self.Wr), _ptr(self.bias),
                      self.gate_up.struct(self.use_prepacked), self.down.struct(self.use_prepacked),
-                     _ptr(self.R_split), getattr(c, "h_bits", 0))
+                     _ptr(self.R_split), getattr(c, "h_bits", 0), 1 if getattr(c, "r_hadamard", False) else 0)
 
     def workspace(self, T: int):
         if self._ws is None or self._ws_T != T:

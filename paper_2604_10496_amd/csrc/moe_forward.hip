@@ -6,7 +6,7 @@ namespace {
 
 cq_status validate_layer(const cq_layer* L, int T) {
   if (!L) return CQ_ERR_NULL;
-  if (!L->R || !L->Wr || !L->gate_up.cent || !L->down.cent) return CQ_ERR_NULL;
+  if ((!L->R && !L->r_hadamard) || !L->Wr || !L->gate_up.cent || !L->down.cent) return CQ_ERR_NULL;
   if ((!L->gate_up.idx && !L->gate_up.prepacked) || (!L->down.idx && !L->down.prepacked)) return CQ_ERR_NULL;
   if (T <= 0 || L->H <= 0 || L->I <= 0 || L->E <= 0 || L->top_k <= 0 || L->S < 0) return CQ_ERR_SHAPE;
   if (L->H % 64 != 0 || L->I % 64 != 0 || L->top_k > L->E || L->top_k > 64 || L->E > 1024) return CQ_ERR_SHAPE;
@@ -14,6 +14,7 @@ cq_status validate_layer(const cq_layer* L, int T) {
   if (L->act_bits != 4 && L->act_bits != 8) return CQ_ERR_UNSUPPORTED;
   if (L->h_bits != 0 && L->h_bits != 4 && L->h_bits != 8) return CQ_ERR_UNSUPPORTED;
   if (L->h_bits != 0 && !cq_hadamard_supported(L->I)) return CQ_ERR_SHAPE;
+  if (L->r_hadamard && !cq_hadamard_supported(L->H)) return CQ_ERR_SHAPE;
   const int G = L->E + L->S;
   if (L->gate_up.G != G || L->gate_up.N != 2 * L->I || L->gate_up.K != L->H) return CQ_ERR_SHAPE;
   if (L->down.G != G || L->down.N != L->H || L->down.K != L->I) return CQ_ERR_SHAPE;
@@ -126,7 +127,16 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
   if (!mark(0)) return CQ_ERR_HIP;
   const bool bf16_codes = use_bf16_codes(L, T);
   uint16_t* Q16 = bf16_codes ? (uint16_t*)(ws + lay.Q16) : nullptr;
-  if (cq_front_small_supported(T, L->H, L->E, L->top_k)) {
+  if (L->r_hadamard) {
+    // the rotation is a Hadamard matrix: transform and quantization in one launch, no matrix is read
+    st = cq_hadamard_quant_launch(X, T, L->H, L->act_bits, Q, Q16, scale, XR, hs);
+    if (st != CQ_OK) return st;
+    if (!mark(1)) return CQ_ERR_HIP;
+    st = cq_route_permute(XR, L->Wr, L->bias, nullptr, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets, perm,
+                          inv_perm, src_token, scratch, scratch_bytes, stream);
+    if (st != CQ_OK) return st;
+    if (!mark(2)) return CQ_ERR_HIP;
+  } else if (cq_front_small_supported(T, L->H, L->E, L->top_k)) {
     // decode-sized batch: the rotation; one launch for quantization and logits; one for top-k and grouping
     // (the second stage boundary therefore falls between the rotation and everything else)
     const cq_gemm_f32_plan p = cq_gemm_f32_make_plan(T, L->H, L->H);

@@ -48,6 +48,8 @@ class LayerConfig:
     outlier_scale: float
     zipf_s: float = 0.0  # > 0: router bias makes expert popularity follow Zipf(s)
     h_bits: int = 0      # 4 or 8: online-Hadamard variant (the intermediate is rotated and quantized)
+    r_hadamard: bool = False  # the rotation is the Hadamard matrix H/sqrt(H): no R is drawn (callers that
+                              # need the dense matrix build it themselves and pass it as R_override)
 
     @property
     def seed(self) -> int:
@@ -73,9 +75,9 @@ CONFIGS: Dict[str, LayerConfig] = {
                     outlier_channels=(), n_outliers=4, outlier_scale=100.0, zipf_s=1.1),
         # online-Hadamard variants of the two Mixtral-shaped workloads (same inputs as configurations 1, 2)
         LayerConfig("mixtral_decode_had", 1, E=8, top_k=2, S=0, H=4096, I=14336, T=16, act_bits=8,
-                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, h_bits=8),
+                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, h_bits=8, r_hadamard=True),
         LayerConfig("mixtral_prefill_had", 2, E=8, top_k=2, S=0, H=4096, I=14336, T=4096, act_bits=4,
-                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, h_bits=4),
+                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, h_bits=4, r_hadamard=True),
     ]
 }
 
@@ -173,7 +175,10 @@ def make_layer(cfg: LayerConfig, with_experts: bool = True,
     else:
         channels = np.sort(rng.permutation(cfg.H)[: cfg.n_outliers])
     X[:, channels] *= np.float32(cfg.outlier_scale)
-    R = draw_orthogonal(rng, cfg.H) if R_override is None else R_override.astype(np.float32)
+    if R_override is not None:
+        R = R_override.astype(np.float32)
+    else:
+        R = None if cfg.r_hadamard else draw_orthogonal(rng, cfg.H)
     Wr = (rng.standard_normal((cfg.E, cfg.H)) / math.sqrt(cfg.H)).astype(np.float32)
     bias = zipf_bias(cfg, rng) if cfg.zipf_s > 0 else None
     experts: List[Dict[str, Tuple[np.ndarray, np.ndarray]]] = []

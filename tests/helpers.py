@@ -32,7 +32,9 @@ def enforce_routing_margin(inputs, delta_rel=1e-3, max_iter=20):
 
 
 def make_inputs(cfg, with_experts=True):
-    inputs = synth.make_layer(cfg, with_experts=with_experts)
+    # Hadamard rotation variant: the dense matrix the oracle multiplies by is built here, by the oracle
+    R = O.hadamard_matrix(cfg.H) / np.sqrt(float(cfg.H)) if getattr(cfg, "r_hadamard", False) else None
+    inputs = synth.make_layer(cfg, with_experts=with_experts, R_override=R)
     enforce_routing_margin(inputs)
     return inputs
 

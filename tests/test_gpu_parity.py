@@ -464,6 +464,9 @@ def test_layer_reduced_shapes(B, name, over):
     ("mixtral_decode", dict(H=512, I=1792, T=16, h_bits=8)),               # I = 28 * 64
     ("mixtral_prefill", dict(H=256, I=768, T=300, h_bits=4)),              # I = 12 * 64, large-tile down product
     ("dsv2lite", dict(H=256, I=704, T=100, E=16, h_bits=8)),               # I = 44 * 16, shared experts
+    ("mixtral_decode", dict(H=512, I=1024, T=16, r_hadamard=True)),        # Hadamard rotation only
+    ("mixtral_prefill", dict(H=768, I=512, T=300, r_hadamard=True, h_bits=4, outlier_channels=(3, 41))),  # H = 12 * 64
+    ("qwen3_zipf", dict(H=256, I=128, T=260, E=32, r_hadamard=True)),
 ])
 def test_layer_online_hadamard(B, name, over):
     cfg = synth.small_variant(synth.CONFIGS[name], **over)
