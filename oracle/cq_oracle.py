@@ -16,7 +16,8 @@ What follows which passage of the paper
   router_logits     the router is a linear layer       AOS section
   route_topk        Top-K experts and weights Pi       ACCF section (MoE weighted sum), appendix (Top-K)
   permute_by_expert X_t = tokens assigned to expert    AOS section (definition of X_t)
-  decode_*          W_c[i,j] = sum_k C[i,k] A[i,j,k]   ACCF section (Eq. W_c)
+  decode_*          W_c[i,j] = sum_k C[i,k] A[i,j,k]   ACCF section (Eq. W_c); embedding-wise or block-wise
+                                                       tables (experimental setup, g = 1024)
   expert_ffn        (phi(X W_gate) . X W_up) W_down    AOS section (rotation-invariance equation)
   moe_forward       sum_i Pi_i X_R W_c (+ shared)      ACCF section (Eq. L, MoE case), appendix (shared expert)
   hadamard_*        online Hadamard transform          evaluation section (the "had" variant)
@@ -31,6 +32,8 @@ Readings taken where the paper is silent (each is also listed in the design note
   * the intermediate h is not re-quantized before the down projection, except in the online-Hadamard
     variant (h_bits > 0): there h is multiplied by H_I / sqrt(I), H_I = H_m (x) H_{2^k} with a Paley matrix
     of order m in {12, 28, 44} when I is not a power of two, and quantized per row exactly like X_R;
+  * block-wise clustering groups g consecutive weights of a row along d_in; when g does not divide d_in
+    the last group of the row is shorter;
   * phi is SiLU; the output stays in the rotated basis (no R^T is applied);
   * shared experts see every token with weight 1 and are added after the routed sum.
 
@@ -127,20 +130,38 @@ def permute_by_expert(ids: np.ndarray, n_experts: int) -> Tuple[np.ndarray, np.n
 # ------------------------------------------------------------------------------------------
 # a6 / a7: codebook weights
 # ------------------------------------------------------------------------------------------
-def decode_weights(idx_packed: np.ndarray, cent_bits: np.ndarray) -> np.ndarray:
+def centroid_per_weight(cent: np.ndarray, K: int, group_k: int = 0) -> np.ndarray:
+    """The table that serves every weight: [N, K, 16] view of the centroid array.
+
+    Embedding-wise (group_k = 0; cent [N, 16]): one table per output row over all of d_in.
+    Block-wise (group_k = g > 0; cent [N, ceil(K/g), 16]): weights are clustered in groups of g
+    consecutive values along d_in (experimental setup, g = 1024), so column j of row n uses table
+    j // g of that row; the last group of a row is shorter when g does not divide K.
+    """
+    cent = np.asarray(cent)
+    if group_k <= 0:
+        assert cent.ndim == 2 and cent.shape[1] == N_CENTROIDS
+        return np.broadcast_to(cent[:, None, :], (cent.shape[0], K, N_CENTROIDS))
+    nblk = -(-K // group_k)
+    assert cent.ndim == 3 and cent.shape[1] == nblk and cent.shape[2] == N_CENTROIDS
+    return cent[:, np.arange(K) // group_k, :]
+
+
+def decode_weights(idx_packed: np.ndarray, cent_bits: np.ndarray, group_k: int = 0) -> np.ndarray:
     """W_c [N, K] float64: every weight is the centroid its 4-bit index points at (Eq. W_c)."""
     idx = unpack_indices(idx_packed).astype(np.int64)
-    C = bf16_bits_to_f64(cent_bits)
-    return np.take_along_axis(C, idx, axis=1)
+    C = bf16_bits_to_f64(centroid_per_weight(cent_bits, idx.shape[1], group_k))
+    return np.take_along_axis(C, idx[:, :, None], axis=2)[:, :, 0]
 
 
-def decode_weights_bf16_bits(idx_packed: np.ndarray, cent_bits: np.ndarray) -> np.ndarray:
+def decode_weights_bf16_bits(idx_packed: np.ndarray, cent_bits: np.ndarray, group_k: int = 0) -> np.ndarray:
     """Same decode, returning the bf16 bit patterns (what a bit-exact decode check compares)."""
     idx = unpack_indices(idx_packed).astype(np.int64)
-    return np.take_along_axis(np.asarray(cent_bits, dtype=np.uint16), idx, axis=1)
+    C = centroid_per_weight(np.asarray(cent_bits, dtype=np.uint16), idx.shape[1], group_k)
+    return np.take_along_axis(C, idx[:, :, None], axis=2)[:, :, 0]
 
 
-def decode_weights_onehot(idx_packed: np.ndarray, cent_bits: np.ndarray) -> np.ndarray:
+def decode_weights_onehot(idx_packed: np.ndarray, cent_bits: np.ndarray, group_k: int = 0) -> np.ndarray:
     """Eq. W_c taken literally: build the one-hot assignment tensor A and contract it with C."""
     idx = unpack_indices(idx_packed)
     N, K = idx.shape
@@ -148,36 +169,45 @@ def decode_weights_onehot(idx_packed: np.ndarray, cent_bits: np.ndarray) -> np.n
     n, j = np.meshgrid(np.arange(N), np.arange(K), indexing="ij")
     A[n, j, idx] = 1.0
     assert np.all(A.sum(axis=2) == 1.0)
-    C = bf16_bits_to_f64(cent_bits)
-    return np.einsum("nk,njk->nj", C, A)
+    if group_k <= 0:
+        return np.einsum("nk,njk->nj", bf16_bits_to_f64(cent_bits), A)
+    # one contraction per clustering group of columns, each with its own centroid matrix
+    W = np.empty((N, K), dtype=np.float64)
+    for b, j0 in enumerate(range(0, K, group_k)):
+        j1 = min(K, j0 + group_k)
+        W[:, j0:j1] = np.einsum("nk,njk->nj", bf16_bits_to_f64(np.asarray(cent_bits)[:, b]), A[:, j0:j1])
+    return W
 
 
-def codebook_matmul(A_rows: np.ndarray, idx_packed: np.ndarray, cent_bits: np.ndarray) -> np.ndarray:
+def codebook_matmul(A_rows: np.ndarray, idx_packed: np.ndarray, cent_bits: np.ndarray,
+                    group_k: int = 0) -> np.ndarray:
     """[M, K] activations times W_c^T -> [M, N]."""
-    return np.asarray(A_rows, dtype=np.float64) @ decode_weights(idx_packed, cent_bits).T
+    return np.asarray(A_rows, dtype=np.float64) @ decode_weights(idx_packed, cent_bits, group_k).T
 
 
 def product_lut_matmul(codes: np.ndarray, idx_packed: np.ndarray, cent_bits: np.ndarray,
-                       act_bits: int = 4) -> np.ndarray:
+                       act_bits: int = 4, group_k: int = 0) -> np.ndarray:
     """The lookup formulation of the kernel section, for integer activation codes.
 
-    For one weight row the table has one sub-table per centroid holding centroid * v for every
-    representable activation value v; a (weight index, activation code) pair selects one product
-    and the products are accumulated.  Pure-Python loops: tiny inputs only.
+    For one weight group (a row, or g consecutive columns of a row) the table has one sub-table per
+    centroid holding centroid * v for every representable activation value v; a (weight index,
+    activation code) pair selects one product and the products are accumulated.  Pure-Python loops:
+    tiny inputs only.
     """
     idx = unpack_indices(idx_packed)
-    C = bf16_bits_to_f64(cent_bits)
     N, K = idx.shape
+    g = group_k if group_k > 0 else K
+    C = bf16_bits_to_f64(cent_bits).reshape(N, -1, N_CENTROIDS)   # [N, groups, 16]
     lo = -(2 ** (act_bits - 1))
     values = np.arange(lo, -lo, dtype=np.float64)            # all 2^b representable codes
     M = codes.shape[0]
     out = np.zeros((M, N), dtype=np.float64)
     for n in range(N):
-        lut = C[n][:, None] * values[None, :]                 # [16 sub-tables, 2^b entries]
+        luts = [C[n, b][:, None] * values[None, :] for b in range(C.shape[1])]  # [16 sub-tables, 2^b entries] each
         for m in range(M):
             acc = 0.0
             for j in range(K):
-                acc += lut[idx[n, j], int(codes[m, j]) - lo]
+                acc += luts[j // g][idx[n, j], int(codes[m, j]) - lo]
             out[m, n] = acc
     return out
 
@@ -270,22 +300,23 @@ def hadamard_rows(h: np.ndarray) -> np.ndarray:
 
 
 def expert_ffn(a_rows: np.ndarray, expert: Dict[str, Tuple[np.ndarray, np.ndarray]],
-               h_bits: int = 0) -> Dict[str, np.ndarray]:
+               h_bits: int = 0, group_k: int = 0) -> Dict[str, np.ndarray]:
     """SwiGLU expert on de-quantized rows a = s*q: returns g, u, h, o (all float64).
 
     h_bits = 4 or 8: the online-Hadamard variant.  The intermediate is rotated, h' = h H / sqrt(I),
     quantized per row to h_bits like the layer's input, and the down projection (whose weights are
     clustered in that rotated basis) reads the de-quantized codes; hq, hs are returned too.
+    group_k > 0: block-wise centroid tables for all three matrices (see centroid_per_weight).
     """
-    g = codebook_matmul(a_rows, *expert["gate"])
-    u = codebook_matmul(a_rows, *expert["up"])
+    g = codebook_matmul(a_rows, *expert["gate"], group_k)
+    u = codebook_matmul(a_rows, *expert["up"], group_k)
     h = silu(g) * u
     if h_bits:
         hr = hadamard_rows(h)
         hq, hs = quantize(hr, h_bits)
-        o = codebook_matmul(hs[:, None] * hq.astype(np.float64), *expert["down"])
+        o = codebook_matmul(hs[:, None] * hq.astype(np.float64), *expert["down"], group_k)
         return {"g": g, "u": u, "h": h, "hr": hr, "hq": hq, "hs": hs, "o": o}
-    o = codebook_matmul(h, *expert["down"])
+    o = codebook_matmul(h, *expert["down"], group_k)
     return {"g": g, "u": u, "h": h, "o": o}
 
 
@@ -296,13 +327,14 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
                 experts: Sequence[Dict[str, Tuple[np.ndarray, np.ndarray]]],
                 n_routed: int, top_k: int, act_bits: int,
                 only_tokens: Optional[np.ndarray] = None,
-                keep_expert_outputs: bool = False, h_bits: int = 0) -> Dict[str, np.ndarray]:
+                keep_expert_outputs: bool = False, h_bits: int = 0, group_k: int = 0) -> Dict[str, np.ndarray]:
     """Forward pass of one layer.  experts = n_routed routed experts followed by shared experts.
 
     only_tokens: if given, expert FFNs and Y are evaluated for these token rows only (the front
     end -- rotation, codes, routing, permutation -- is always computed for every token).
     h_bits: 0, or the bit width of the online-Hadamard variant's second quantization (see expert_ffn);
     with keep_expert_outputs the rotated intermediates and their codes come back per sorted row.
+    group_k: 0 (one centroid table per weight row) or the block-wise group size g.
     """
     T = X.shape[0]
     XR = rotate(X, R)
@@ -336,7 +368,7 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
         keep = tok_mask[toks]
         if not np.any(keep):
             continue
-        res = expert_ffn(a[toks[keep]], experts[e], h_bits)
+        res = expert_ffn(a[toks[keep]], experts[e], h_bits, group_k)
         contrib[toks[keep], assign[keep] % top_k] = res["o"]
         if keep_expert_outputs:
             o_sorted[pos[keep]] = res["o"]
@@ -348,7 +380,7 @@ def moe_forward(X: np.ndarray, R: np.ndarray, Wr: np.ndarray, bias: Optional[np.
     shared_o = []
     for s in range(n_routed, len(experts)):
         rows = np.nonzero(tok_mask)[0]
-        res = expert_ffn(a[rows], experts[s], h_bits)
+        res = expert_ffn(a[rows], experts[s], h_bits, group_k)
         Y[rows] += res["o"]
         if keep_h:
             base = n_assign + (s - n_routed) * T

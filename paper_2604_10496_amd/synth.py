@@ -16,7 +16,9 @@ Layouts produced (all numpy, host memory):
   bias     [E] or None   float32   router bias (only the Zipf-popularity config has one)
   experts[e]["gate"|"up"|"down"] = (idx, cent)
       idx  [N, K/2]      uint8     byte j of a row = index of weight 2j (bits 0-3) and 2j+1 (bits 4-7)
-      cent [N, 16]       uint16    bf16 bit patterns, ascending within a row
+      cent [N, 16]       uint16    bf16 bit patterns, ascending within a row (embedding-wise tables), or
+           [N, ceil(K/g), 16]      one table per group of g consecutive weights of the row (block-wise
+                                   setting of the experimental setup; LayerConfig.group_k = g)
   with (N, K) = (I, H) for gate and up and (H, I) for down.  Experts E .. E+S-1 are the
   always-on shared experts.
 """
@@ -48,6 +50,7 @@ class LayerConfig:
     outlier_scale: float
     zipf_s: float = 0.0  # > 0: router bias makes expert popularity follow Zipf(s)
     h_bits: int = 0      # 4 or 8: online-Hadamard variant (the intermediate is rotated and quantized)
+    group_k: int = 0     # > 0: block-wise centroid tables, one per group_k consecutive weights of a row
     r_hadamard: bool = False  # the rotation is the Hadamard matrix H/sqrt(H): no R is drawn (callers that
                               # need the dense matrix build it themselves and pass it as R_override)
 
@@ -78,6 +81,11 @@ CONFIGS: Dict[str, LayerConfig] = {
                     outlier_channels=(), n_outliers=8, outlier_scale=100.0, h_bits=8, r_hadamard=True),
         LayerConfig("mixtral_prefill_had", 2, E=8, top_k=2, S=0, H=4096, I=14336, T=4096, act_bits=4,
                     outlier_channels=(), n_outliers=8, outlier_scale=100.0, h_bits=4, r_hadamard=True),
+        # block-wise centroid tables (g = 1024) on the same two workloads
+        LayerConfig("mixtral_decode_blockwise", 1, E=8, top_k=2, S=0, H=4096, I=14336, T=16, act_bits=8,
+                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, group_k=1024),
+        LayerConfig("mixtral_prefill_blockwise", 2, E=8, top_k=2, S=0, H=4096, I=14336, T=4096, act_bits=4,
+                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, group_k=1024),
     ]
 }
 
@@ -119,7 +127,11 @@ def draw_orthogonal(rng: np.random.Generator, H: int) -> np.ndarray:
     return q.astype(np.float32)
 
 
-def draw_centroids(rng: np.random.Generator, N: int, outlier_row_frac: float = 0.01) -> np.ndarray:
+def draw_centroids(rng: np.random.Generator, N: int, outlier_row_frac: float = 0.01,
+                   n_blocks: int = 0) -> np.ndarray:
+    """[N, 16] tables, or [N, n_blocks, 16] when n_blocks > 0 (every table drawn like a row's)."""
+    if n_blocks > 0:
+        return draw_centroids(rng, N * n_blocks, outlier_row_frac).reshape(N, n_blocks, N_CENTROIDS)
     c = np.sort(rng.standard_normal((N, N_CENTROIDS)).astype(np.float32) * np.float32(0.02), axis=1)
     n_out = int(math.ceil(outlier_row_frac * N))
     rows = rng.permutation(N)[:n_out]
@@ -128,6 +140,11 @@ def draw_centroids(rng: np.random.Generator, N: int, outlier_row_frac: float = 0
     col = np.where(left_bigger, 0, N_CENTROIDS - 1)
     c[rows, col] *= np.float32(20.0)
     return f32_to_bf16_bits(c)
+
+
+def n_blocks(K: int, group_k: int) -> int:
+    """Tables per weight row: 0 stands for the embedding-wise layout [N, 16]."""
+    return -(-K // group_k) if group_k > 0 else 0
 
 
 def zipf_bias(cfg: LayerConfig, rng: np.random.Generator) -> np.ndarray:
@@ -187,9 +204,9 @@ def make_layer(cfg: LayerConfig, with_experts: bool = True,
             gi = rng.integers(0, 256, size=(cfg.I, cfg.H // 2), dtype=np.uint8)
             ui = rng.integers(0, 256, size=(cfg.I, cfg.H // 2), dtype=np.uint8)
             di = rng.integers(0, 256, size=(cfg.H, cfg.I // 2), dtype=np.uint8)
-            gc = draw_centroids(rng, cfg.I)
-            uc = draw_centroids(rng, cfg.I)
-            dc = draw_centroids(rng, cfg.H)
+            gc = draw_centroids(rng, cfg.I, n_blocks=n_blocks(cfg.H, cfg.group_k))
+            uc = draw_centroids(rng, cfg.I, n_blocks=n_blocks(cfg.H, cfg.group_k))
+            dc = draw_centroids(rng, cfg.H, n_blocks=n_blocks(cfg.I, cfg.group_k))
             experts.append({"gate": (gi, gc), "up": (ui, uc), "down": (di, dc)})
     return LayerInputs(cfg, X, channels, R, Wr, bias, experts)
 
@@ -218,14 +235,14 @@ def interleave_gate_up(gate: Tuple[np.ndarray, np.ndarray],
     idx = np.empty((2 * I, gi.shape[1]), dtype=np.uint8)
     idx[0::2] = gi
     idx[1::2] = ui
-    cent = np.empty((2 * I, N_CENTROIDS), dtype=np.uint16)
+    cent = np.empty((2 * I,) + gc.shape[1:], dtype=np.uint16)
     cent[0::2] = gc
     cent[1::2] = uc
     return idx, cent
 
 
 def stack_experts(inputs: LayerInputs) -> Dict[str, np.ndarray]:
-    """Stack per-expert matrices into the [G, N, K/2] / [G, N, 16] arrays the library takes."""
+    """Stack per-expert matrices into the [G, N, K/2] / [G, N, (blocks,) 16] arrays the library takes."""
     gu = [interleave_gate_up(e["gate"], e["up"]) for e in inputs.experts]
     return {
         "gate_up_idx": np.stack([g[0] for g in gu]),

@@ -237,6 +237,59 @@ def test_three_decode_formulations_agree():
     assert np.allclose(lut, gemm, rtol=1e-12, atol=1e-15)
 
 
+def test_blockwise_tables():
+    """Block-wise clustering (experimental setup): column j of a row uses that row's table j // g."""
+    rng = _rng(19)
+    N, K, M, g = 5, 40, 3, 16                    # three groups per row, the last one of 8 columns
+    idx = rng.integers(0, 16, size=(N, K), dtype=np.uint8)
+    packed = _pack(idx)
+    cent = synth.draw_centroids(rng, N, n_blocks=3)
+    assert cent.shape == (N, 3, 16)
+    C = O.bf16_bits_to_f64(cent)
+    brute = np.array([[C[n, j // g, idx[n, j]] for j in range(K)] for n in range(N)])
+    W = O.decode_weights(packed, cent, g)
+    assert np.array_equal(W, brute)
+    assert np.array_equal(O.decode_weights_onehot(packed, cent, g), brute)
+    assert np.array_equal(O.decode_weights_bf16_bits(packed, cent, g),
+                          np.array([[cent[n, j // g, idx[n, j]] for j in range(K)] for n in range(N)]))
+    # a block-wise product is the sum of embedding-wise products over the column groups
+    A = rng.standard_normal((M, K))
+    parts = sum(O.codebook_matmul(A[:, j0:j0 + g], packed[:, j0 // 2:(j0 + g) // 2], cent[:, b])
+                for b, j0 in enumerate(range(0, K, g)))
+    assert np.allclose(O.codebook_matmul(A, packed, cent, g), parts, rtol=1e-12, atol=1e-15)
+    # the same table in every group, or one group spanning the row, is the embedding-wise setting
+    rep = np.repeat(cent[:, :1], 3, axis=1)
+    assert np.array_equal(O.decode_weights(packed, rep, g), O.decode_weights(packed, cent[:, 0]))
+    assert np.array_equal(O.decode_weights(packed, cent[:, :1], K), O.decode_weights(packed, cent[:, 0]))
+    # changing one group's table changes exactly that group's columns
+    other = cent.copy()
+    other[:, 1] = synth.draw_centroids(rng, N)
+    diff = O.decode_weights(packed, other, g) != W
+    assert not diff[:, :g].any() and not diff[:, 2 * g:].any() and diff[:, g:2 * g].any()
+    # lookup formulation with one product table per (row, group)
+    codes = rng.integers(-7, 8, size=(M, K))
+    assert np.allclose(O.product_lut_matmul(codes, packed, cent, act_bits=4, group_k=g),
+                       O.codebook_matmul(codes, packed, cent, g), rtol=1e-12, atol=1e-15)
+
+
+def test_blockwise_layer_matches_dense():
+    """The block-wise layer equals the dense SwiGLU FFN on brute-force decoded matrices."""
+    cfg = synth.small_variant(synth.CONFIGS["tiny"], H=64, I=96, T=5, E=2, top_k=1, group_k=32,
+                              outlier_channels=(3,), n_outliers=1)
+    L = synth.make_layer(cfg)
+    assert L.experts[0]["gate"][1].shape == (96, 2, 16) and L.experts[0]["down"][1].shape == (64, 3, 16)
+    res = O.moe_forward(L.X, L.R, L.Wr, L.bias, L.experts, cfg.E, cfg.top_k, cfg.act_bits, group_k=32)
+    a = res["scale"][:, None] * res["q"]
+    def dense(mat, K):
+        idx = O.unpack_indices(mat[0])
+        C = O.bf16_bits_to_f64(mat[1])
+        return np.array([[C[n, j // 32, idx[n, j]] for j in range(K)] for n in range(idx.shape[0])])
+    for t in range(cfg.T):
+        e = L.experts[int(res["ids"][t, 0])]
+        y = O.unquantized_ffn(a[t:t + 1], dense(e["gate"], 64), dense(e["up"], 64), dense(e["down"], 96))
+        assert np.allclose(res["Y"][t], y[0], rtol=1e-10, atol=1e-12)
+
+
 def test_codebook_matmul_special_cases():
     rng = _rng(10)
     N, K, M = 10, 64, 4
