@@ -76,7 +76,7 @@ def cpu_baseline(L, budget_s):
     t1 = time.perf_counter()
     for e in active:
         toks = perm[offsets[e]:offsets[e + 1]] // cfg.top_k if e < cfg.E else np.arange(cfg.T)
-        O.expert_ffn(a[toks], L.experts[e], getattr(cfg, "h_bits", 0))
+        O.expert_ffn(a[toks], L.experts[e], getattr(cfg, "h_bits", 0), getattr(cfg, "group_k", 0))
         done += 1
         rows_done += len(toks)
         t_exp = time.perf_counter() - t1

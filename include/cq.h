@@ -68,12 +68,18 @@ enum { CQ_OUT_F32 = 0, CQ_OUT_F16 = 1 };
  *             rb and K step s is at ((rb*(K/64) + s) * 1024) and holds, for l = 0..63, the 16
  *             canonical bytes of row rb*32 + l%32, byte columns s*32 + (l/32)*16 .. +15, at l*16.
  *   K must be a multiple of 64 and N a multiple of 64.
+ *   group_k   0 (or >= K): one table per row over all of K ("Embedding-wise", experimental setup).
+ *             g > 0: "Block-wise" tables, one per group of g consecutive weights of a row; cent is then
+ *             [G, N, ceil(K/g), 16] and weight k of a row is decoded through table k / g (the last group
+ *             is shorter when g does not divide K).  g must be a multiple of 512 and N of 256
+ *             (other values: CQ_ERR_UNSUPPORTED).
  */
 typedef struct {
   const uint8_t* idx;
   const uint16_t* cent;
   const void* prepacked;
   int G, N, K;
+  int group_k;
 } cq_codebook_weights;
 
 /* One MoE expert layer.  Groups 0..E-1 are routed experts, E..E+S-1 always-on shared experts. */

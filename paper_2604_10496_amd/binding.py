@@ -31,7 +31,7 @@ EXPORTS = [
 
 class CodebookWeights(ctypes.Structure):
     _fields_ = [("idx", ctypes.c_void_p), ("cent", ctypes.c_void_p), ("prepacked", ctypes.c_void_p),
-                ("G", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int)]
+                ("G", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int), ("group_k", ctypes.c_int)]
 
 
 class Layer(ctypes.Structure):
@@ -152,9 +152,11 @@ def _ws(nbytes: int):
 # weights
 # ------------------------------------------------------------------------------------------------
 class DeviceCodebook:
-    """Device-resident [G, N, K/2] indices + [G, N, 16] bf16 tables, optionally prepacked."""
+    """Device-resident [G, N, K/2] indices + [G, N, 16] bf16 tables, optionally prepacked.
 
-    def __init__(self, idx, cent, prepack: bool = True, keep_canonical: bool = True):
+    group_k = g > 0: block-wise tables, cent is [G, N, ceil(K/g), 16]."""
+
+    def __init__(self, idx, cent, prepack: bool = True, keep_canonical: bool = True, group_k: int = 0):
         torch = _torch()
         import numpy as np
         if isinstance(idx, np.ndarray):
@@ -163,7 +165,11 @@ class DeviceCodebook:
             cent = torch.from_numpy(np.ascontiguousarray(cent).view(np.int16))
         assert idx.dtype == torch.uint8 and idx.dim() == 3 and cent.dtype == torch.int16
         self.G, self.N, self.K = int(idx.shape[0]), int(idx.shape[1]), int(idx.shape[2]) * 2
-        assert tuple(cent.shape) == (self.G, self.N, 16)
+        self.group_k = int(group_k)
+        if self.group_k > 0:
+            assert tuple(cent.shape) == (self.G, self.N, -(-self.K // self.group_k), 16)
+        else:
+            assert tuple(cent.shape) == (self.G, self.N, 16)
         self.cent = cent.to("cuda").contiguous()
         self.idx = idx.to("cuda").contiguous()
         self.prepacked = None
@@ -174,7 +180,7 @@ class DeviceCodebook:
 
     def struct(self, use_prepacked: bool = True) -> CodebookWeights:
         pre = self.prepacked if use_prepacked else None
-        return CodebookWeights(_ptr(self.idx), _ptr(self.cent), _ptr(pre), self.G, self.N, self.K)
+        return CodebookWeights(_ptr(self.idx), _ptr(self.cent), _ptr(pre), self.G, self.N, self.K, self.group_k)
 
 
 def cq_prepack(W: DeviceCodebook):
@@ -405,8 +411,9 @@ def device_layer_from_inputs(inputs, use_prepacked: bool = True) -> DeviceLayer:
     """Upload a synth.LayerInputs (layout work only: stacking experts, interleaving gate/up rows)."""
     from . import synth
     st = synth.stack_experts(inputs)
-    gu = DeviceCodebook(st["gate_up_idx"], st["gate_up_cent"], prepack=use_prepacked)
-    dn = DeviceCodebook(st["down_idx"], st["down_cent"], prepack=use_prepacked)
+    g = getattr(inputs.cfg, "group_k", 0)
+    gu = DeviceCodebook(st["gate_up_idx"], st["gate_up_cent"], prepack=use_prepacked, group_k=g)
+    dn = DeviceCodebook(st["down_idx"], st["down_cent"], prepack=use_prepacked, group_k=g)
     return DeviceLayer(inputs.cfg, inputs.R, inputs.Wr, inputs.bias, gu, dn, use_prepacked)
 
 

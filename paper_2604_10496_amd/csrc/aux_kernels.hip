@@ -55,8 +55,8 @@ __global__ __launch_bounds__(256) void prepack_kernel(const uint4* __restrict__ 
 }
 
 __global__ __launch_bounds__(256) void decode_dense_kernel(const uint8_t* __restrict__ idx, int prepacked,
-                                                           const uint16_t* __restrict__ cent, int N, int K,
-                                                           uint16_t* __restrict__ out) {
+                                                           const uint16_t* __restrict__ cent, int nblk, int group_k,
+                                                           int N, int K, uint16_t* __restrict__ out) {
   const size_t total = (size_t)N * (K / 2);
   const int steps = K / 64;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void decode_dense_kernel(const uint8_t* __rest
       src = (((n >> 5) * steps + s) * 64 + g * 32 + (n & 31)) * 16 + within;
     }
     const uint32_t b = idx[src];
-    const uint16_t* c = cent + n * CQ_N_CENTROIDS;
+    const uint16_t* c = cent + (n * nblk + (size_t)((2 * bc) / group_k)) * CQ_N_CENTROIDS;  // group_k is even
     out[n * K + 2 * bc] = c[b & 15u];
     out[n * K + 2 * bc + 1] = c[b >> 4];
   }
@@ -161,12 +161,14 @@ extern "C" cq_status cq_prepack(const cq_codebook_weights* W, void* dst, size_t 
 extern "C" cq_status cq_decode_dense(const cq_codebook_weights* W, int g, uint16_t* Wc_bf16, cq_stream stream) {
   if (!W || (!W->idx && !W->prepacked) || !W->cent || !Wc_bf16) return CQ_ERR_NULL;
   if (W->G <= 0 || W->N <= 0 || W->K <= 0 || W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;
-  if (g < 0 || g >= W->G) return CQ_ERR_SHAPE;
+  if (g < 0 || g >= W->G || W->group_k < 0 || W->group_k % 2 != 0) return CQ_ERR_SHAPE;
+  const int nblk = cq_tables_per_row(W);
   const size_t gbytes = (size_t)W->N * (W->K / 2);
   const uint8_t* src = (W->prepacked ? (const uint8_t*)W->prepacked : W->idx) + (size_t)g * gbytes;
   const unsigned grid = (unsigned)((gbytes + 255) / 256 < 65536 ? (gbytes + 255) / 256 : 65536);
   hipLaunchKernelGGL(decode_dense_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, src,
-                     W->prepacked ? 1 : 0, W->cent + (size_t)g * W->N * CQ_N_CENTROIDS, W->N, W->K, Wc_bf16);
+                     W->prepacked ? 1 : 0, W->cent + (size_t)g * W->N * nblk * CQ_N_CENTROIDS, nblk,
+                     nblk > 1 ? W->group_k : W->K, W->N, W->K, Wc_bf16);
   return cq_check_launch();
 }
 

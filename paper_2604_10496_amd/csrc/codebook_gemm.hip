@@ -768,9 +768,13 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     a.upw = (int)upw;
   }
   // Groups of up to 32 rows go to the streaming kernel above; larger ones to the large-tile kernel (when
-  // the row count allows its 256-row tiles), which runs off a device-built tile list.
-  const bool large = cq_gemm_large_supported(W) && M_total > kSmallMaxRows;
-  a.max_rows = large ? kSmallMaxRows : 0x7fffffff;
+  // the row count allows its 256-row tiles), which runs off a device-built tile list.  Block-wise tables
+  // exist in the large-tile kernel only: every group goes there.
+  const bool blockwise = cq_tables_per_row(W) > 1;
+  const bool large = cq_gemm_uses_large_tiles(W, M_total);
+  if (blockwise && !large) return CQ_ERR_UNSUPPORTED;
+  const int small_max = blockwise ? 0 : kSmallMaxRows;
+  a.max_rows = large ? small_max : 0x7fffffff;
   a.small_hdr = nullptr;
   a.small_ids = nullptr;
   void* large_ws = (char*)workspace + cq_gemm_partials_bytes(W, M_total, epilogue);
@@ -778,11 +782,14 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   if (large) {
     // the host does not know which groups are small: a device-built list spreads exactly those over
     // the grid (a grid over all groups would leave most workgroups without work)
-    st = cq_gemm_build_lists(W, group_offsets, M_total, kSmallMaxRows,
+    st = cq_gemm_build_lists(W, group_offsets, M_total, small_max,
                              W->G > kListedWorkgroups ? W->G : kListedWorkgroups, large_ws, &a.small_hdr,
                              &a.small_ids, s);
     if (st != CQ_OK) return st;
   }
+  if (blockwise)
+    return cq_gemm_large_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, small_max, epilogue, out,
+                                out_kind, large_ws, s);
   switch (a_kind) {
     case CQ_A_INT8_CODES: st = dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s); break;
     case CQ_A_F16: st = dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s); break;
@@ -811,10 +818,14 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
 }
 
 
+bool cq_gemm_uses_large_tiles(const cq_codebook_weights* W, int M_total) {
+  return cq_gemm_large_supported(W) && (M_total > kSmallMaxRows || cq_tables_per_row(W) > 1);
+}
+
 extern "C" size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, int M_total) {
   if (!W || W->G <= 0 || W->N <= 0 || W->K <= 0 || M_total <= 0) return 0;
   size_t n = cq_gemm_partials_bytes(W, M_total, CQ_EPI_NONE);
-  if (M_total > kSmallMaxRows && cq_gemm_large_supported(W))
+  if (cq_gemm_uses_large_tiles(W, M_total))
     n += cq_gemm_large_workspace_bytes(W->G, M_total, W->K, true);  // worst case over the operand kinds
   return n;
 }
@@ -827,7 +838,8 @@ extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, cons
   if (!W || !A || !group_offsets || (!out && M_total > 0)) return CQ_ERR_NULL;
   if ((!W->idx && !W->prepacked) || !W->cent) return CQ_ERR_NULL;
   if (W->G <= 0 || W->N <= 0 || W->K <= 0 || M_total < 0) return CQ_ERR_SHAPE;
-  if (W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;
+  if (W->N % 64 != 0 || W->K % 64 != 0 || W->group_k < 0) return CQ_ERR_SHAPE;
+  if (cq_tables_per_row(W) > 1 && !cq_gemm_large_supported(W)) return CQ_ERR_UNSUPPORTED;
   if (a_kind != CQ_A_INT8_CODES && a_kind != CQ_A_F16 && a_kind != CQ_A_F32 && a_kind != CQ_A_BF16)
     return CQ_ERR_UNSUPPORTED;
   if (epilogue != CQ_EPI_NONE && epilogue != CQ_EPI_SWIGLU) return CQ_ERR_UNSUPPORTED;

@@ -9,7 +9,9 @@
 //     nibbles become byte selectors, v_perm_b32 picks the low and the high bytes of the centroids out
 //     of register-resident byte tables (two 8-entry halves; a third perm, steered by bit 3 of the
 //     index, picks between them), two more perm levels interleave the bytes into bf16/f16 pairs.
-//     About 1.7 ALU operations per MFMA, all full rate, hidden behind the matrix pipe;
+//     About 1.7 ALU operations per MFMA, all full rate, hidden behind the matrix pipe.
+//     With block-wise tables (one per group of g weights along K, g a multiple of 512) the two tables are
+//     replaced every g/64 steps; the raw tables of the next group are requested one group ahead;
 //   * LDS holds only the activation tiles.  They arrive by direct global->LDS loads (no staging
 //     registers, no ds_write), four tiles deep, and each wavefront reads a tile once per K step.
 // The activation operand is 16-bit (bf16 integer codes or f16 rows); other kinds are converted by a
@@ -30,6 +32,7 @@ constexpr int kLargeRows = 256;  // weight rows per workgroup
 constexpr int kStepK = 64;       // K per pipeline step
 constexpr int kStepBytes = kStepK * 2;  // one token's share of a step in LDS and in global memory
 constexpr int kLdsTileBytes = 4 * 256 * kStepBytes;  // activation tile rings: 4 x 256, 8 x 128 or 8 x 64 tokens
+constexpr int kNextTableBytes = 2048;  // block-wise tables: raw next tables of a wavefront's 64 rows (x 4 wavefronts x 2)
 
 struct LargeArgs {
   const uint8_t* idx;
@@ -47,6 +50,8 @@ struct LargeArgs {
   const int32_t* tiles64;  // 64-token tiles, same layout
   const int32_t* n_tiles;  // the builder's counts: [0] entries in tiles, [1] in tiles128, [5] in tiles64
   int row_tiles;          // N / 256
+  int nblk;               // centroid tables per weight row (1: one table over all of K)
+  int gsteps;             // K steps per table (block-wise tables: group size / 64, a multiple of 8)
 };
 
 __device__ __forceinline__ uint32_t f32_to_f16_sat(float x) {
@@ -79,7 +84,8 @@ constexpr int epilogue_row_stride(int epi, int outk) {
 // One tile: 256 weight rows (row tile rt) x up to 32*C tokens (rows mrow0 .. mrow0+mcnt-1 of group grp).
 // F16: the activations are f16 (else bf16); C = CT/32 token blocks (8, 4 or 2); D = depth of the load
 // pipeline in K steps (a power of two; narrow tiles spend less matrix time per step and need more).
-template <bool F16, int EPI, int OUTK, int C, int D>
+// BLK: block-wise centroid tables (p.nblk per row, each serving p.gsteps K steps).
+template <bool F16, int EPI, int OUTK, int C, int D, bool BLK>
 __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, const int mrow0, const int mcnt,
                                            const int rt) {
   constexpr int CT = 32 * C;
@@ -104,9 +110,27 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   }
   const int nS = K / kStepK;
 
-  const uint16_t* cbase = p.cent + ((size_t)grp * N + n0) * CQ_N_CENTROIDS;
-  const RowTable t0 = make_row_table<F16>(cbase + (size_t)r32 * CQ_N_CENTROIDS);
-  const RowTable t1 = make_row_table<F16>(cbase + (size_t)(32 + r32) * CQ_N_CENTROIDS);
+  const int nblk = BLK ? p.nblk : 1;
+  const uint16_t* cgrp = p.cent + (size_t)grp * N * nblk * CQ_N_CENTROIDS;   // this group's tables (uniform)
+  const uint32_t crow_off = (uint32_t)(n0 + r32) * nblk * (CQ_N_CENTROIDS * 2);  // row r32's tables, in bytes
+  const uint32_t crow_skip = 32u * nblk * (CQ_N_CENTROIDS * 2);                // from row r32 to row 32 + r32
+  RowTable t0 = make_row_table<F16>(reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(cgrp) + crow_off));
+  RowTable t1 = make_row_table<F16>(
+      reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(cgrp) + crow_off + crow_skip));
+  // Block-wise tables: the raw centroids of the next group of weights wait in LDS above the activation
+  // tiles, 2 KiB per wavefront and parity of the group (two direct-to-LDS loads: lane (r32, g2) moves half
+  // g2 of the 32-byte table of row r32, then of row 32 + r32), and become register tables when that group
+  // starts.  Nothing but one byte offset per lane stays in registers meanwhile.
+  int blk_next = 1;            // group whose tables were requested last (clamped to the last one)
+  int switch_at = p.gsteps;    // first K step of that group
+  const uint32_t tbl_lds = __builtin_amdgcn_readfirstlane(kLdsTileBytes + wave * kNextTableBytes);
+  auto fetch_tables = [&](int b) {
+    const uint8_t* src = reinterpret_cast<const uint8_t*>(cgrp) + (size_t)min(b, nblk - 1) * (CQ_N_CENTROIDS * 2);
+    const uint32_t at = tbl_lds + (b & 1) * (4 * kNextTableBytes);
+    const uint32_t lane_off = crow_off + g2 * 16;
+    load_global_to_lds_s<0>(at, src, lane_off);
+    load_global_to_lds_s<0>(at + 1024, src, lane_off + crow_skip);
+  };
 
   // ---- activation tiles ----
   // LDS tile: token-major, 128 bytes (8 chunks of 8 k) per token; chunk c of token t sits at position
@@ -164,9 +188,16 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   constexpr int kPerStep = C + 2;  // C tile loads + 2 weight loads
   constexpr int kInFlight = (D - 3) * kPerStep;
   static_assert(D >= 4 && (D & (D - 1)) == 0 && kInFlight < 64, "ring depth / vmcnt range");
+  static_assert(2 * kPerStep > 2 && kInFlight + kPerStep + 2 < 64,
+                "the waits of D - 1 steps retire the table loads before they are used");
   cq_v4u wq[D][2];
 #pragma unroll
   for (int i = 0; i < D - 1; ++i) {
+    // (block-wise tables: the first request for tables sits where the loop's requests will sit, in front
+    // of the last step requested ahead -- the wait counts below are the same in every pass)
+    if constexpr (BLK) {
+      if (i == D - 2) fetch_tables(1);
+    }
     fetch_weights(wq[i], min(i, nS - 1));
     fetch_tile(min(i, nS - 1), i, 0, C);
   }
@@ -196,6 +227,32 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int cur = jj & 1, nxt = cur ^ 1;
+        if constexpr (BLK) {
+          if (par == D - 1 && jj == 3) {
+            // A group of weights ends with this step (groups are whole multiples of D steps, so only here;
+            // the branch sits at a sub-step boundary, where the instruction scheduler is fenced anyway).
+            // Its successor's tables were requested at least D steps ago and have arrived: the waits since
+            // left fewer loads outstanding than were issued after that request.  The wait below never
+            // stalls (no more than that many loads are ever outstanding); it orders the LDS reads behind
+            // the arrival.
+            if (s0 + D == switch_at) {
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kInFlight + kPerStep + 2) : "memory");
+              const uint32_t at = tbl_lds + (blk_next & 1) * (4 * kNextTableBytes) + r32 * 16;
+              const cq_v4u a0 = lds_read_u128(at), a1 = lds_read_u128(at + 512);
+              const cq_v4u b0 = lds_read_u128(at + 1024), b1 = lds_read_u128(at + 1536);
+              uint32_t r0[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+              uint32_t r1[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+              t0 = make_row_table<F16>(r0);
+              t1 = make_row_table<F16>(r1);
+              ++blk_next;
+              switch_at += p.gsteps;
+            }
+            // The tables of the group after the current one are requested in EVERY pass (again, if they
+            // were requested before: 2 KiB per wavefront from L2, the same bytes to the same place), so
+            // that the number of loads in flight, and with it every wait count, is a compile-time constant.
+            fetch_tables(blk_next);
+          }
+        }
         // the C tile loads are spread over the step: no LDS write bursts
         if constexpr (C >= 4) fetch_tile(s3, (par + D - 1) & (D - 1), jj * (C / 4), C / 4);
         else if (jj < C) fetch_tile(s3, (par + D - 1) & (D - 1), jj, 1);
@@ -218,12 +275,18 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      vm_wait<kInFlight>(wq[(par + 2) & (D - 1)][0], wq[(par + 2) & (D - 1)][1]);
+      // (block-wise tables: the two table requests of a pass's last step are younger than what the waits
+      // of that step and of the next D - 4 steps are for, and may stay in flight as well)
+      // (par is a constant once the loop is unrolled: no branch is left here)
+      if (BLK && (par == D - 1 || par <= D - 5))
+        vm_wait<kInFlight + 2>(wq[(par + 2) & (D - 1)][0], wq[(par + 2) & (D - 1)][1]);
+      else
+        vm_wait<kInFlight>(wq[(par + 2) & (D - 1)][0], wq[(par + 2) & (D - 1)][1]);
       __syncthreads();
     }
     s0 += D;
   } while (s0 < nS);
-  // nothing of this workgroup may still be on its way into LDS when the workgroup ends
+  // nothing of this workgroup may still be on its way into LDS when the loop is left
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- epilogue: per-token scale, optional SiLU(gate)*up, store ----
@@ -308,7 +371,7 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
 // round-robin over the 8 XCDs): XCD x takes a contiguous share of the 256-token work and then a
 // contiguous share of the 128-token and of the 64-token work (neighbours share activations in its L2;
 // equal mix on every XCD).  The grid is sized for the worst case; the lists are usually much shorter.
-template <bool F16, int EPI, int OUTK>
+template <bool F16, int EPI, int OUTK, bool BLK>
 __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   const int n256 = p.n_tiles[0] * p.row_tiles, n128 = p.n_tiles[1] * p.row_tiles, n64 = p.n_tiles[5] * p.row_tiles;
   const int per256 = (n256 + 7) >> 3, per128 = (n128 + 7) >> 3, per64 = (n64 + 7) >> 3;
@@ -319,7 +382,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n256) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles + tile * 4;
-    large_tile<F16, EPI, OUTK, 8, 4>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 8, 4, BLK>(p, t[0], t[1], t[2], rt);
     return;
   }
   slot -= per256;
@@ -328,7 +391,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n128) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles128 + tile * 4;
-    large_tile<F16, EPI, OUTK, 4, 8>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 4, 8, BLK>(p, t[0], t[1], t[2], rt);
     return;
   }
   slot -= per128;
@@ -337,7 +400,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n64) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles64 + tile * 4;
-    large_tile<F16, EPI, OUTK, 2, 8>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 2, 8, BLK>(p, t[0], t[1], t[2], rt);
   }
 }
 
@@ -455,11 +518,11 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
   }
 }
 
-template <bool F16, int EPI, int OUTK>
+template <bool F16, int EPI, int OUTK, bool BLK>
 cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, const int32_t* counts, int max256,
                       int max128, hipStream_t s) {
-  auto kern = gemm_large_kernel<F16, EPI, OUTK>;
-  constexpr int lds_loop = kLdsTileBytes, lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
+  auto kern = gemm_large_kernel<F16, EPI, OUTK, BLK>;
+  constexpr int lds_loop = kLdsTileBytes + (BLK ? 8 * kNextTableBytes : 0), lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
   static bool configured = false;
   if (!configured) {
@@ -484,14 +547,22 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
   return cq_check_launch();
 }
 
+template <bool F16, bool BLK>
+cq_status dispatch_large_blk(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
+                             const int32_t* counts, int max256, int max128, hipStream_t s) {
+  if (epilogue == CQ_EPI_SWIGLU)
+    return out_kind == CQ_OUT_F16
+               ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16, BLK>(a, t256, t128, counts, max256, max128, s)
+               : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32, BLK>(a, t256, t128, counts, max256, max128, s);
+  return out_kind == CQ_OUT_F16 ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16, BLK>(a, t256, t128, counts, max256, max128, s)
+                                : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32, BLK>(a, t256, t128, counts, max256, max128, s);
+}
+
 template <bool F16>
 cq_status dispatch_large(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
                          const int32_t* counts, int max256, int max128, hipStream_t s) {
-  if (epilogue == CQ_EPI_SWIGLU)
-    return out_kind == CQ_OUT_F16 ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16>(a, t256, t128, counts, max256, max128, s)
-                                  : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32>(a, t256, t128, counts, max256, max128, s);
-  return out_kind == CQ_OUT_F16 ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16>(a, t256, t128, counts, max256, max128, s)
-                                : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32>(a, t256, t128, counts, max256, max128, s);
+  return a.nblk > 1 ? dispatch_large_blk<F16, true>(a, epilogue, out_kind, t256, t128, counts, max256, max128, s)
+                    : dispatch_large_blk<F16, false>(a, epilogue, out_kind, t256, t128, counts, max256, max128, s);
 }
 
 size_t tile_list_bytes(int G, int M_total) {
@@ -517,7 +588,11 @@ size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conver
 }
 
 bool cq_gemm_large_supported(const cq_codebook_weights* W) {
-  return W->N % kLargeRows == 0 && W->K % (2 * kStepK) == 0;
+  if (W->N % kLargeRows != 0 || W->K % (2 * kStepK) != 0) return false;
+  // block-wise tables change between two passes of the unrolled pipeline (8 steps of 64)
+  // (and the kernel addresses a group's tables with 32-bit byte offsets)
+  const int nblk = cq_tables_per_row(W);
+  return nblk == 1 || (W->group_k % (8 * kStepK) == 0 && (long)W->N * nblk * (CQ_N_CENTROIDS * 2) < (1L << 31));
 }
 
 // Builds the work lists of both kernels in `workspace` (first step of a mixed launch).  Returns the list
@@ -566,6 +641,8 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
   a.tiles64 = nullptr;
   a.n_tiles = nullptr;
   a.row_tiles = W->N / kLargeRows;
+  a.nblk = cq_tables_per_row(W);
+  a.gsteps = a.nblk > 1 ? W->group_k / kStepK : W->K / kStepK;
   if (a_kind == CQ_A_INT8_CODES || a_kind == CQ_A_F32) {
     // 16-bit copy of the rows in sorted order (the gather is applied here)
     uint16_t* A16 = (uint16_t*)((char*)workspace + tile_list_bytes(W->G, M_total));

@@ -21,6 +21,11 @@ static inline cq_status cq_check_launch() {
 
 static inline size_t cq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// centroid tables per weight row: one, or with block-wise tables one per group of group_k weights along K
+static inline int cq_tables_per_row(const cq_codebook_weights* W) {
+  return (W->group_k > 0 && W->group_k < W->K) ? (W->K + W->group_k - 1) / W->group_k : 1;
+}
+
 // ---- internal launchers (arguments already validated) -------------------------------------
 // C[T,N] (or partials [ksplit][T][N]) = A[T,K] * B, with B given row-major [K,N] (b_transposed = 0)
 // or as its transpose [N,K] (b_transposed = 1); fp32 MFMA, fp32 accumulation.
@@ -82,6 +87,9 @@ cq_status cq_combine_launch(const float* O, int slices, size_t slice_stride, con
 
 // large-tile (prefill) path of the codebook product
 bool cq_gemm_large_supported(const cq_codebook_weights* W);
+// whether a product over M_total rows launches it (more rows than the streaming kernel takes per group, or
+// block-wise tables, which only the large-tile kernel decodes)
+bool cq_gemm_uses_large_tiles(const cq_codebook_weights* W, int M_total);
 // with_conversion: include room for a 16-bit copy of the activation rows (needed for CQ_A_INT8_CODES
 // and CQ_A_F32 operands; bf16 / f16 operands are read in place)
 size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion);

@@ -18,6 +18,10 @@ cq_status validate_layer(const cq_layer* L, int T) {
   const int G = L->E + L->S;
   if (L->gate_up.G != G || L->gate_up.N != 2 * L->I || L->gate_up.K != L->H) return CQ_ERR_SHAPE;
   if (L->down.G != G || L->down.N != L->H || L->down.K != L->I) return CQ_ERR_SHAPE;
+  if (L->gate_up.group_k < 0 || L->down.group_k < 0) return CQ_ERR_SHAPE;
+  if ((cq_tables_per_row(&L->gate_up) > 1 && !cq_gemm_large_supported(&L->gate_up)) ||
+      (cq_tables_per_row(&L->down) > 1 && !cq_gemm_large_supported(&L->down)))
+    return CQ_ERR_UNSUPPORTED;
   return CQ_OK;
 }
 
@@ -27,7 +31,7 @@ bool use_split_rotation(const cq_layer* L, int T) { return L->R_split && cq_rota
 // Batches large enough for the large-tile product get the codes a second time as bf16, so that staging
 // them into LDS is a plain copy.
 bool use_bf16_codes(const cq_layer* L, int T) {
-  return (long)T * (L->top_k + L->S) > 32 && cq_gemm_large_supported(&L->gate_up);
+  return cq_gemm_uses_large_tiles(&L->gate_up, (int)((long)T * (L->top_k + L->S)));
 }
 
 void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
@@ -51,7 +55,7 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   o->src_token = take(M * 4);
   o->Hbuf = take(M * L->I * (L->h_bits ? 4 : 2));  // f16, or fp32 when it is rotated and quantized next
   o->Obuf = take(M * L->H * 4);
-  const bool hq16 = L->h_bits && M > 32 && cq_gemm_large_supported(&L->down);
+  const bool hq16 = L->h_bits && cq_gemm_uses_large_tiles(&L->down, (int)M);
   o->HQ = take(L->h_bits ? M * L->I : 0);
   o->HQ16 = take(hq16 ? M * L->I * 2 : 0);
   o->hscale = take(L->h_bits ? M * 4 : 0);
@@ -69,7 +73,7 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   }
   {
     size_t g2 = cq_gemm_partials_bytes(&L->down, (int)M, CQ_EPI_NONE);
-    if (M > 32 && cq_gemm_large_supported(&L->down))  // (16-bit operands in either variant: f16 h or bf16 codes)
+    if (cq_gemm_uses_large_tiles(&L->down, (int)M))  // (16-bit operands in either variant: f16 h or bf16 codes)
       g2 += cq_gemm_large_workspace_bytes(L->down.G, (int)M, L->down.K, false);
     if (g2 > scratch) scratch = g2;
   }
@@ -178,7 +182,7 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
     // down projection reads integer codes and per-row scales like the gate/up projection does
     int8_t* HQ = (int8_t*)(ws + lay.HQ);
     float* hscale = (float*)(ws + lay.hscale);
-    const bool hq16 = M > 32 && cq_gemm_large_supported(&L->down);
+    const bool hq16 = cq_gemm_uses_large_tiles(&L->down, (int)M);
     uint16_t* HQ16 = hq16 ? (uint16_t*)(ws + lay.HQ16) : nullptr;
     st = cq_hadamard_quant_launch((const float*)Hbuf, M, L->I, L->h_bits, HQ, HQ16, hscale, nullptr, hs);
     if (st != CQ_OK) return st;

@@ -42,7 +42,7 @@ def make_inputs(cfg, with_experts=True):
 def oracle_forward(inputs, **kw):
     c = inputs.cfg
     return O.moe_forward(inputs.X, inputs.R, inputs.Wr, inputs.bias, inputs.experts, c.E, c.top_k, c.act_bits,
-                         h_bits=getattr(c, "h_bits", 0), **kw)
+                         h_bits=getattr(c, "h_bits", 0), group_k=getattr(c, "group_k", 0), **kw)
 
 
 def check_codes(q_gpu, q_ref, XR_ref, scale_ref, tie_window=1e-3):
