@@ -142,8 +142,11 @@ def main():
     counts = np.diff(offs)
     active = int((counts > 0).sum())
     rows = int(offs[-1])
-    gu_bytes = active * (2 * cfg.I * cfg.H // 2 + 2 * cfg.I * 32)      # packed indices + centroid tables
-    dn_bytes = active * (cfg.H * cfg.I // 2 + cfg.H * 32)
+    # packed indices + centroid tables (one 32-byte table per row, or per group of group_k weights of a row)
+    g = getattr(cfg, "group_k", 0)
+    gu_tables, dn_tables = synth.n_blocks(cfg.H, g) or 1, synth.n_blocks(cfg.I, g) or 1
+    gu_bytes = active * (2 * cfg.I * cfg.H // 2 + 2 * cfg.I * 32 * gu_tables)
+    dn_bytes = active * (cfg.H * cfg.I // 2 + cfg.H * 32 * dn_tables)
     gu_flops = rows * 2.0 * (2 * cfg.I) * cfg.H
     dn_flops = rows * 2.0 * cfg.H * cfg.I
     flop_per_byte = (gu_flops + dn_flops) / (gu_bytes + dn_bytes)
@@ -195,7 +198,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name} (E={cfg.E} top-{cfg.top_k} S={cfg.S} H={cfg.H} I={cfg.I} T={cfg.T} "
-                               f"A{cfg.act_bits}W4, 16 bf16 centroids per weight row"
+                               f"A{cfg.act_bits}W4, 16 bf16 centroids per "
+                               + (f"group of {g} weights of a row (block-wise)" if g else "weight row")
                                + (", Hadamard rotation" if getattr(cfg, "r_hadamard", False) else "")
                                + (f", online Hadamard + A{cfg.h_bits} in front of the down projection)"
                                   if getattr(cfg, "h_bits", 0) else ")"),

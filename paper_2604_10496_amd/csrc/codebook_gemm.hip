@@ -725,6 +725,21 @@ void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue,
   const int nS = W->K / 64;
   *ksplit = 1;
   *ksteps = nS;
+  const int nblk = cq_tables_per_row(W);
+  if (nblk > 1) {
+    // Block-wise tables run on the large-tile kernel, one workgroup per 256 rows and group of tokens.  With
+    // at most 64 rows in all (one 64-token tile per group) and a short N there are too few of those to fill
+    // the chip, so K is cut into ranges of whole table groups, up to about two workgroups per compute unit.
+    if (epilogue != CQ_EPI_NONE || M_total > 64 || !cq_gemm_large_supported(W)) return;
+    const long wgs = (long)(W->G < M_total ? W->G : M_total) * (W->N / 256);
+    long want = wgs > 0 ? 512 / wgs : 1;
+    if (want > nblk) want = nblk;
+    if (want <= 1) return;
+    const int per = (nblk + (int)want - 1) / (int)want;   // table groups per range
+    *ksteps = per * (W->group_k / 64);
+    *ksplit = (nblk + per - 1) / per;
+    return;
+  }
   if (epilogue != CQ_EPI_NONE || M_total > 256 || nS <= 64) return;
   const int want = (nS + 63) / 64;
   const int per = ((nS + want - 1) / want + kWaves - 1) / kWaves * kWaves;  // whole rounds of the wavefronts
@@ -787,9 +802,24 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
                              &a.small_ids, s);
     if (st != CQ_OK) return st;
   }
-  if (blockwise)
-    return cq_gemm_large_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, small_max, epilogue, out,
-                                out_kind, large_ws, s);
+  if (blockwise) {
+    // (with a K split the kernel stores fp32 partial sums, per split, where the streaming kernel would)
+    st = cq_gemm_large_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, small_max, epilogue,
+                              a.ksplit > 1 ? (void*)a.partials : out, a.ksplit > 1 ? CQ_OUT_F32 : out_kind, large_ws, s);
+    if (st != CQ_OK || a.ksplit == 1) return st;
+    if (ksplit_left) {
+      *ksplit_left = a.ksplit;  // the caller adds the partial sums itself
+      return st;
+    }
+    const dim3 grid((W->N / 4 + 255) / 256, W->G);
+    if (out_kind == CQ_OUT_F16)
+      hipLaunchKernelGGL(sum_partials_kernel<CQ_OUT_F16>, grid, dim3(256), 0, s, a.partials, a.part_stride, a.ksplit,
+                         group_offsets, 0x7fffffff, W->N, out);
+    else
+      hipLaunchKernelGGL(sum_partials_kernel<CQ_OUT_F32>, grid, dim3(256), 0, s, a.partials, a.part_stride, a.ksplit,
+                         group_offsets, 0x7fffffff, W->N, out);
+    return cq_check_launch();
+  }
   switch (a_kind) {
     case CQ_A_INT8_CODES: st = dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s); break;
     case CQ_A_F16: st = dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s); break;

@@ -52,6 +52,11 @@ struct LargeArgs {
   int row_tiles;          // N / 256
   int nblk;               // centroid tables per weight row (1: one table over all of K)
   int gsteps;             // K steps per table (block-wise tables: group size / 64, a multiple of 8)
+  // K split (block-wise tables, plain products of few rows): workgroups with blockIdx.y = z take the K steps
+  // [z * ksteps, (z+1) * ksteps), a whole number of table groups, and store fp32 partial sums at
+  // out + z * part_stride elements; ksteps covers all of K when there is no split
+  int ksteps;
+  size_t part_stride;
 };
 
 __device__ __forceinline__ uint32_t f32_to_f16_sat(float x) {
@@ -108,11 +113,18 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
     wp1 = wbase + (size_t)(32 + r32) * rowbytes + g2 * 16;
     sstride = 32;
   }
-  const int nS = K / kStepK;
+  // this workgroup's K range: steps [sb, sb + nS) (all of K unless the launch splits K)
+  const int sb = BLK ? (int)blockIdx.y * p.ksteps : 0;
+  const int nS = BLK ? min(p.ksteps, K / kStepK - sb) : K / kStepK;
+  if constexpr (BLK) {
+    wp0 += (size_t)sb * sstride;
+    wp1 += (size_t)sb * sstride;
+  }
 
   const int nblk = BLK ? p.nblk : 1;
   const uint16_t* cgrp = p.cent + (size_t)grp * N * nblk * CQ_N_CENTROIDS;   // this group's tables (uniform)
-  const uint32_t crow_off = (uint32_t)(n0 + r32) * nblk * (CQ_N_CENTROIDS * 2);  // row r32's tables, in bytes
+  const int blk0 = BLK ? sb / p.gsteps : 0;                                     // first table group of the K range
+  const uint32_t crow_off = ((uint32_t)(n0 + r32) * nblk + blk0) * (CQ_N_CENTROIDS * 2);  // row r32's first table, bytes
   const uint32_t crow_skip = 32u * nblk * (CQ_N_CENTROIDS * 2);                // from row r32 to row 32 + r32
   RowTable t0 = make_row_table<F16>(reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(cgrp) + crow_off));
   RowTable t1 = make_row_table<F16>(
@@ -121,11 +133,12 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   // tiles, 2 KiB per wavefront and parity of the group (two direct-to-LDS loads: lane (r32, g2) moves half
   // g2 of the 32-byte table of row r32, then of row 32 + r32), and become register tables when that group
   // starts.  Nothing but one byte offset per lane stays in registers meanwhile.
-  int blk_next = 1;            // group whose tables were requested last (clamped to the last one)
+  int blk_next = 1;            // group (counted from the range's first) whose tables were requested last
   int switch_at = p.gsteps;    // first K step of that group
-  const uint32_t tbl_lds = __builtin_amdgcn_readfirstlane(kLdsTileBytes + wave * kNextTableBytes);
+  const uint32_t tbl_lds = __builtin_amdgcn_readfirstlane(D * kBufBytes + wave * kNextTableBytes);  // above the ring
   auto fetch_tables = [&](int b) {
-    const uint8_t* src = reinterpret_cast<const uint8_t*>(cgrp) + (size_t)min(b, nblk - 1) * (CQ_N_CENTROIDS * 2);
+    // (clamped to the row's last table)
+    const uint8_t* src = reinterpret_cast<const uint8_t*>(cgrp) + (size_t)min(b, nblk - 1 - blk0) * (CQ_N_CENTROIDS * 2);
     const uint32_t at = tbl_lds + (b & 1) * (4 * kNextTableBytes);
     const uint32_t lane_off = crow_off + g2 * 16;
     load_global_to_lds_s<0>(at, src, lane_off);
@@ -149,7 +162,7 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
     const int m = mrow0 + min(tok, mcnt - 1);
     const size_t row = (size_t)(p.a_gather ? p.a_gather[m] : m);
     const int chunk = (lane & 7) ^ ((tok >> 1) & 7);
-    ap[i] = reinterpret_cast<const uint8_t*>(p.A) + (row * (size_t)K + chunk * 8) * 2;
+    ap[i] = reinterpret_cast<const uint8_t*>(p.A) + (row * (size_t)K + (size_t)sb * kStepK + chunk * 8) * 2;
   }
   const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(wave * (CT / 4) * kStepBytes);
   // this wavefront's loads i0 .. i0+n-1 of the activations of step s into tile `buf`
@@ -357,6 +370,7 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
       if (tok < mcnt) {
         const uint32_t at = (uint32_t)tl * kRowStride + (uint32_t)pc * kPiece;
         char* dst = reinterpret_cast<char*>(p.out) + ((size_t)(mrow0 + tok) * p.out_ld + out_col0) * kEsize + (size_t)pc * kPiece;
+        if constexpr (BLK) dst += (size_t)blockIdx.y * p.part_stride * kEsize;
         if constexpr (kPiece == 16)
           *reinterpret_cast<cq_v4u*>(dst) = *reinterpret_cast<const lds_v4u*>((uintptr_t)at);
         else
@@ -402,6 +416,22 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     const int32_t* t = p.tiles64 + tile * 4;
     large_tile<F16, EPI, OUTK, 2, 8, BLK>(p, t[0], t[1], t[2], rt);
   }
+}
+
+// The 64-token tiles alone, for launches in which no group has more than 64 rows (block-wise tables at decode
+// sizes): a quarter of the accumulators and half the LDS, so two workgroups share a compute unit and each
+// SIMD has a second wavefront to hide the decode's vector-ALU work behind.
+template <bool F16, int EPI, int OUTK, bool BLK>
+__global__ __launch_bounds__(256, 2) void gemm_large64_kernel(const LargeArgs p) {
+  const int n64 = p.n_tiles[5] * p.row_tiles;
+  const int per64 = (n64 + 7) >> 3;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  if (slot >= per64) return;
+  const int work = xcd * per64 + slot;
+  if (work >= n64) return;
+  const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
+  const int32_t* t = p.tiles64 + tile * 4;
+  large_tile<F16, EPI, OUTK, 2, 8, BLK>(p, t[0], t[1], t[2], rt);
 }
 
 // Pre-pass for activation kinds the main kernel does not read: sorted row m of the result is row
@@ -518,26 +548,48 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
   }
 }
 
+template <typename Kernel>
+cq_status configure_lds(Kernel kern, int lds, bool* configured) {
+  if (*configured) return CQ_OK;
+  hipFuncAttributes fa;
+  if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
+  if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+      hipSuccess)
+    return CQ_ERR_HIP;
+  *configured = true;
+  return CQ_OK;
+}
+
+// only64: the caller knows that no group has more than 64 rows
 template <bool F16, int EPI, int OUTK, bool BLK>
 cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, const int32_t* counts, int max256,
-                      int max128, hipStream_t s) {
-  auto kern = gemm_large_kernel<F16, EPI, OUTK, BLK>;
-  constexpr int lds_loop = kLdsTileBytes + (BLK ? 8 * kNextTableBytes : 0), lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
-  constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
-  static bool configured = false;
-  if (!configured) {
-    hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
-    if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
-        hipSuccess)
-      return CQ_ERR_HIP;
-    configured = true;
-  }
+                      int max128, bool only64, hipStream_t s) {
   a.tiles = t256;
   a.tiles128 = t128;
   a.tiles64 = t128 + (size_t)max128 * 4;
   a.n_tiles = counts;
+  constexpr int lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
+  if constexpr (BLK) if (only64) {
+    auto kern = gemm_large64_kernel<F16, EPI, OUTK, BLK>;
+    constexpr int lds_loop = 8 * 64 * kStepBytes + (BLK ? 8 * kNextTableBytes : 0);
+    constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
+    static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
+    static bool configured = false;
+    const cq_status st = configure_lds(kern, lds, &configured);
+    if (st != CQ_OK) return st;
+    const long grid = (((long)max128 * a.row_tiles + 7) / 8) * 8;
+    if (grid <= 0) return CQ_OK;
+    const int total = a.K / kStepK;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)((total + a.ksteps - 1) / a.ksteps)), dim3(256), lds, s, a);
+    return cq_check_launch();
+  }
+  auto kern = gemm_large_kernel<F16, EPI, OUTK, BLK>;
+  constexpr int lds_loop = kLdsTileBytes + (BLK ? 8 * kNextTableBytes : 0);
+  constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
+  static bool configured = false;
+  const cq_status st = configure_lds(kern, lds, &configured);
+  if (st != CQ_OK) return st;
   // worst case of the kernel's per-XCD shares (a group ends in at most one 128- or 64-token tile, but the
   // two lists round up separately): ceil(n256/8) + ceil(n128/8) + ceil(n64/8) slots on each of 8 XCDs
   const long w256 = (long)max256 * a.row_tiles, w128 = (long)max128 * a.row_tiles;
@@ -549,20 +601,24 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
 
 template <bool F16, bool BLK>
 cq_status dispatch_large_blk(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
-                             const int32_t* counts, int max256, int max128, hipStream_t s) {
+                             const int32_t* counts, int max256, int max128, bool only64, hipStream_t s) {
   if (epilogue == CQ_EPI_SWIGLU)
     return out_kind == CQ_OUT_F16
-               ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16, BLK>(a, t256, t128, counts, max256, max128, s)
-               : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32, BLK>(a, t256, t128, counts, max256, max128, s);
-  return out_kind == CQ_OUT_F16 ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16, BLK>(a, t256, t128, counts, max256, max128, s)
-                                : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32, BLK>(a, t256, t128, counts, max256, max128, s);
+               ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16, BLK>(a, t256, t128, counts, max256, max128, only64, s)
+               : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32, BLK>(a, t256, t128, counts, max256, max128, only64, s);
+  return out_kind == CQ_OUT_F16
+             ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16, BLK>(a, t256, t128, counts, max256, max128, only64, s)
+             : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32, BLK>(a, t256, t128, counts, max256, max128, only64, s);
 }
 
+// The two-workgroup kernel for 64-token tiles exists for block-wise tables only (the streaming kernel takes
+// the small groups otherwise).
 template <bool F16>
 cq_status dispatch_large(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
-                         const int32_t* counts, int max256, int max128, hipStream_t s) {
-  return a.nblk > 1 ? dispatch_large_blk<F16, true>(a, epilogue, out_kind, t256, t128, counts, max256, max128, s)
-                    : dispatch_large_blk<F16, false>(a, epilogue, out_kind, t256, t128, counts, max256, max128, s);
+                         const int32_t* counts, int max256, int max128, bool only64, hipStream_t s) {
+  return a.nblk > 1
+             ? dispatch_large_blk<F16, true>(a, epilogue, out_kind, t256, t128, counts, max256, max128, only64, s)
+             : dispatch_large_blk<F16, false>(a, epilogue, out_kind, t256, t128, counts, max256, max128, false, s);
 }
 
 size_t tile_list_bytes(int G, int M_total) {
@@ -643,6 +699,11 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
   a.row_tiles = W->N / kLargeRows;
   a.nblk = cq_tables_per_row(W);
   a.gsteps = a.nblk > 1 ? W->group_k / kStepK : W->K / kStepK;
+  {
+    int ksplit;
+    cq_gemm_split_plan(W, M_total, epilogue, &ksplit, &a.ksteps);  // a split is planned for 64-token launches only
+    a.part_stride = ksplit > 1 ? (size_t)M_total * W->N : 0;
+  }
   if (a_kind == CQ_A_INT8_CODES || a_kind == CQ_A_F32) {
     // 16-bit copy of the rows in sorted order (the gather is applied here)
     uint16_t* A16 = (uint16_t*)((char*)workspace + tile_list_bytes(W->G, M_total));
@@ -658,6 +719,7 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
     a.a_gather = nullptr;
   }
   const bool f16 = a_kind == CQ_A_F16 || a_kind == CQ_A_F32;
-  return f16 ? dispatch_large<true>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, s)
-             : dispatch_large<false>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, s);
+  const bool only64 = M_total <= 64;  // then every group has at most 64 rows: one 64-token tile each
+  return f16 ? dispatch_large<true>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, only64, s)
+             : dispatch_large<false>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, only64, s);
 }

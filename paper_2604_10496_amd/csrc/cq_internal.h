@@ -81,6 +81,8 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
                                   const int32_t* group_offsets, int M_total, int epilogue,
                                   void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left);
 size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue);
+// K split of a product: ksplit ranges of ksteps K steps (of 64) each; 1 and K/64 when K is not split
+void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue, int* ksplit, int* ksteps);
 // weighted combine over `slices` partial copies of O that are `slice_stride` floats apart
 cq_status cq_combine_launch(const float* O, int slices, size_t slice_stride, const float* topk_w,
                             const int32_t* inv_perm, int T, int H, int top_k, int n_shared, float* Y, hipStream_t s);

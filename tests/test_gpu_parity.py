@@ -360,7 +360,9 @@ def test_gemm_swiglu_epilogue(B, out_kind, I, counts):
 # block-wise centroid tables (one per group of g weights along K): every group of rows takes the large-tile
 # kernel, whatever its size; tables change inside the K loop (also with a shorter last group)
 BLOCKWISE_CASES = [(256, 1024, 512, [3, 40]), (256, 1408, 1024, [1, 0, 33, 300]), (512, 4096, 1024, [5, 129, 257]),
-                   (256, 14336, 1024, [7, 70]), (256, 1536, 512, [64, 65, 128, 256])]
+                   (256, 14336, 1024, [7, 70]), (256, 1536, 512, [64, 65, 128, 256]),
+                   # at most 64 rows in all: K is cut into ranges of whole groups, partial sums added afterwards
+                   (256, 14336, 1024, [7, 30]), (512, 4096, 1024, [64]), (256, 1408, 1024, [0, 5])]
 
 
 def _integer_block_tables(rng, G, N, nblk):
@@ -422,9 +424,10 @@ def test_gemm_blockwise_float_rows_against_oracle(B, a_kind, N, K, g, counts):
         assert Hp.row_rel_l2(out[rows], ref).max() < 2e-5
 
 
-def test_gemm_blockwise_swiglu_epilogue(B):
+@pytest.mark.parametrize("counts", [[9, 140], [9, 40]])   # the second: no group above 64 rows (two-workgroup kernel)
+def test_gemm_blockwise_swiglu_epilogue(B, counts):
     rng = np.random.default_rng(61)
-    I, K, g, counts = 128, 1024, 512, [9, 140]
+    I, K, g = 128, 1024, 512
     G, M = len(counts), sum(counts)
     draw = lambda: (rng.integers(0, 256, size=(I, K // 2), dtype=np.uint8), synth.draw_centroids(rng, I, n_blocks=2))
     gate, up = [draw() for _ in range(G)], [draw() for _ in range(G)]
