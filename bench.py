@@ -154,9 +154,11 @@ def main():
     dn_s = stage["down"] * 1e-3
     if flop_per_byte < MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9):
         ach = gu_bytes / gu_s / 1e9
-        roofline = {"bound": "hbm", "kernel": "gemm_small_kernel (gate/up codebook product + SwiGLU)",
+        # (block-wise tables are decoded by the large-tile kernel's 64-token variant, whatever the batch)
+        kern = "gemm_large64_kernel" if g and rows <= 64 else "gemm_large_kernel" if g else "gemm_small_kernel"
+        roofline = {"bound": "hbm", "kernel": f"{kern} (gate/up codebook product + SwiGLU)",
                     "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
-                    "traffic": measured_traffic(cfg.name, "gemm_small_kernel"),
+                    "traffic": measured_traffic(cfg.name, kern),
                     "algorithmic_bytes_per_launch": gu_bytes, "avg_launch_ms": stage["gate_up"]}
     else:
         ach = gu_flops / gu_s / 1e12

@@ -130,35 +130,48 @@ def permute_by_expert(ids: np.ndarray, n_experts: int) -> Tuple[np.ndarray, np.n
 # ------------------------------------------------------------------------------------------
 # a6 / a7: codebook weights
 # ------------------------------------------------------------------------------------------
-def centroid_per_weight(cent: np.ndarray, K: int, group_k: int = 0) -> np.ndarray:
-    """The table that serves every weight: [N, K, 16] view of the centroid array.
+def _column_groups(K: int, group_k: int):
+    """(table number, first column, end column) of every clustering group along d_in.
 
-    Embedding-wise (group_k = 0; cent [N, 16]): one table per output row over all of d_in.
-    Block-wise (group_k = g > 0; cent [N, ceil(K/g), 16]): weights are clustered in groups of g
+    Embedding-wise (group_k = 0; centroids [N, 16]): one table per output row over all of d_in.
+    Block-wise (group_k = g > 0; centroids [N, ceil(K/g), 16]): weights are clustered in groups of g
     consecutive values along d_in (experimental setup, g = 1024), so column j of row n uses table
     j // g of that row; the last group of a row is shorter when g does not divide K.
     """
+    g = group_k if group_k > 0 else K
+    return [(b, j0, min(K, j0 + g)) for b, j0 in enumerate(range(0, K, g))]
+
+
+def _tables(cent: np.ndarray, K: int, group_k: int) -> np.ndarray:
+    """The centroid array as [N, groups, 16] (a view; checks the shape against the grouping)."""
     cent = np.asarray(cent)
     if group_k <= 0:
         assert cent.ndim == 2 and cent.shape[1] == N_CENTROIDS
-        return np.broadcast_to(cent[:, None, :], (cent.shape[0], K, N_CENTROIDS))
-    nblk = -(-K // group_k)
-    assert cent.ndim == 3 and cent.shape[1] == nblk and cent.shape[2] == N_CENTROIDS
-    return cent[:, np.arange(K) // group_k, :]
+        return cent[:, None, :]
+    assert cent.ndim == 3 and cent.shape[1] == -(-K // group_k) and cent.shape[2] == N_CENTROIDS
+    return cent
 
 
 def decode_weights(idx_packed: np.ndarray, cent_bits: np.ndarray, group_k: int = 0) -> np.ndarray:
     """W_c [N, K] float64: every weight is the centroid its 4-bit index points at (Eq. W_c)."""
     idx = unpack_indices(idx_packed).astype(np.int64)
-    C = bf16_bits_to_f64(centroid_per_weight(cent_bits, idx.shape[1], group_k))
-    return np.take_along_axis(C, idx[:, :, None], axis=2)[:, :, 0]
+    K = idx.shape[1]
+    C = bf16_bits_to_f64(_tables(cent_bits, K, group_k))
+    W = np.empty(idx.shape, dtype=np.float64)
+    for b, j0, j1 in _column_groups(K, group_k):
+        W[:, j0:j1] = np.take_along_axis(C[:, b], idx[:, j0:j1], axis=1)
+    return W
 
 
 def decode_weights_bf16_bits(idx_packed: np.ndarray, cent_bits: np.ndarray, group_k: int = 0) -> np.ndarray:
     """Same decode, returning the bf16 bit patterns (what a bit-exact decode check compares)."""
     idx = unpack_indices(idx_packed).astype(np.int64)
-    C = centroid_per_weight(np.asarray(cent_bits, dtype=np.uint16), idx.shape[1], group_k)
-    return np.take_along_axis(C, idx[:, :, None], axis=2)[:, :, 0]
+    K = idx.shape[1]
+    C = _tables(np.asarray(cent_bits, dtype=np.uint16), K, group_k)
+    W = np.empty(idx.shape, dtype=np.uint16)
+    for b, j0, j1 in _column_groups(K, group_k):
+        W[:, j0:j1] = np.take_along_axis(C[:, b], idx[:, j0:j1], axis=1)
+    return W
 
 
 def decode_weights_onehot(idx_packed: np.ndarray, cent_bits: np.ndarray, group_k: int = 0) -> np.ndarray:
@@ -169,13 +182,11 @@ def decode_weights_onehot(idx_packed: np.ndarray, cent_bits: np.ndarray, group_k
     n, j = np.meshgrid(np.arange(N), np.arange(K), indexing="ij")
     A[n, j, idx] = 1.0
     assert np.all(A.sum(axis=2) == 1.0)
-    if group_k <= 0:
-        return np.einsum("nk,njk->nj", bf16_bits_to_f64(cent_bits), A)
     # one contraction per clustering group of columns, each with its own centroid matrix
+    C = bf16_bits_to_f64(_tables(cent_bits, K, group_k))
     W = np.empty((N, K), dtype=np.float64)
-    for b, j0 in enumerate(range(0, K, group_k)):
-        j1 = min(K, j0 + group_k)
-        W[:, j0:j1] = np.einsum("nk,njk->nj", bf16_bits_to_f64(np.asarray(cent_bits)[:, b]), A[:, j0:j1])
+    for b, j0, j1 in _column_groups(K, group_k):
+        W[:, j0:j1] = np.einsum("nk,njk->nj", C[:, b], A[:, j0:j1])
     return W
 
 
