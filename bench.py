@@ -49,6 +49,8 @@ def parse_args():
     ap.add_argument("--workload", default="mixtral_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle's expert sample")
+    ap.add_argument("--compare-lut", action="store_true",
+                    help="A4 workloads: also time the gate/up product in the lookup formulation (product tables)")
     return ap.parse_args()
 
 
@@ -217,6 +219,25 @@ def main():
                  "measured_mfma_loop_TFLOPs": mfma_tflops},
         "device": info, "setup_s": t_gen,
     }
+    if args.compare_lut and cfg.act_bits == 4 and not getattr(cfg, "h_bits", 0):
+        # the gate/up product of this step's sorted rows, once on the matrix cores and once by table lookup
+        def timed(fn, n):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(n):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / n
+        argsg = (mid["scale"], mid["src_token"], mid["offsets"], rows, B.CQ_EPI_SWIGLU, B.CQ_OUT_F32)
+        n_rep = 20 if rows <= 256 else 2
+        mm = timed(lambda: B.cq_codebook_grouped_gemm(layer.gate_up, mid["Q"], B.CQ_A_INT8_CODES, *argsg), n_rep)
+        lut_out = B.cq_codebook_grouped_gemm_lut(layer.gate_up, mid["Q"], *argsg)
+        lut = timed(lambda: B.cq_codebook_grouped_gemm_lut(layer.gate_up, mid["Q"], *argsg, out=lut_out), n_rep)
+        out["lut_comparison"] = {"stage": "gate/up product + SwiGLU on int8-held 4-bit codes", "rows": rows,
+                                 "matrix_core_ms": mm, "lookup_ms": lut, "lookup_over_matrix_core": lut / mm}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L, args.cpu_seconds)
     print(json.dumps(out))

@@ -177,6 +177,22 @@ cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W,
                                    void* workspace, size_t workspace_bytes, cq_stream stream);
 
 /*
+ * The same product in the lookup formulation of the kernel section (Fig. 4b and the text beside it): per
+ * group of weights that shares a table, the 16 sub-tables (one per centroid) of 16 products centroid x 4-bit
+ * activation value are precomputed in LDS; every (weight index, activation code) pair then selects a
+ * product, which is accumulated in fp32 -- no multiplication in the inner loop.  A software rendering for
+ * comparison with the matrix-core kernels above (the paper's version needs modified tensor cores); same
+ * results up to fp32 summation order.
+ *   codes [rows, K] int8 holding 4-bit codes in [-8, 7] (values outside wrap modulo 16: the caller's duty);
+ *   W->idx (canonical bytes) is read, W->prepacked is ignored; group_k: 0 or a multiple of 32.
+ *   Other arguments as for cq_codebook_grouped_gemm; no workspace.
+ */
+cq_status cq_codebook_grouped_gemm_lut(const cq_codebook_weights* W, const int8_t* codes,
+                                       const float* row_scale, const int32_t* row_gather,
+                                       const int32_t* group_offsets, int M_total,
+                                       int epilogue, void* out, int out_kind, cq_stream stream);
+
+/*
  * Online-Hadamard variant (evaluation section, the "had" setting): rows h [M, I] f32 -> h' = h H_I / sqrt(I)
  * and its per-row symmetric integer quantization (same rule as cq_rotate_quant).  H_I = H_m (x) H_{2^k}
  * (Kronecker product, index i = a*2^k + b) with the Sylvester matrix H_{2^k}[b,b'] = (-1)^popcount(b & b')

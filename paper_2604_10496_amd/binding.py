@@ -26,6 +26,7 @@ EXPORTS = [
     "cq_moe_forward", "cq_moe_forward_timed", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
     "cq_stream_read", "cq_mfma_loop", "cq_rotation_split_bytes", "cq_rotation_split",
     "cq_rotate_quant_split_workspace_bytes", "cq_rotate_quant_split", "cq_hadamard_quant",
+    "cq_codebook_grouped_gemm_lut",
 ]
 
 
@@ -104,6 +105,8 @@ def load_library() -> ctypes.CDLL:
     lib.cq_prepack_bytes.argtypes = [ctypes.POINTER(CodebookWeights)]
     lib.cq_prepack.restype = ci
     lib.cq_prepack.argtypes = [ctypes.POINTER(CodebookWeights), vp, sz, vp]
+    lib.cq_codebook_grouped_gemm_lut.restype = ci
+    lib.cq_codebook_grouped_gemm_lut.argtypes = [ctypes.POINTER(CodebookWeights), vp, vp, vp, vp, ci, ci, vp, ci, vp]
     lib.cq_decode_dense.restype = ci
     lib.cq_decode_dense.argtypes = [ctypes.POINTER(CodebookWeights), ci, vp, vp]
     lib.cq_device_info.restype = ci
@@ -203,6 +206,21 @@ def cq_rotation_split(R):
         raise CqError(2)
     out = torch.empty(n, dtype=torch.uint8, device="cuda")
     _check(lib.cq_rotation_split(_ptr(R), H, _ptr(out), n, _stream()))
+    return out
+
+
+def cq_codebook_grouped_gemm_lut(W: DeviceCodebook, codes, row_scale, row_gather, group_offsets, M_total: int,
+                                 epilogue: int, out_kind: int, out=None):
+    """The lookup formulation of the product (4-bit codes in an int8 container); see include/cq.h."""
+    torch = _torch()
+    lib = load_library()
+    n_out = W.N // 2 if epilogue == CQ_EPI_SWIGLU else W.N
+    if out is None:
+        out = torch.empty((M_total, n_out), dtype=torch.float16 if out_kind == CQ_OUT_F16 else torch.float32,
+                          device="cuda")
+    s = W.struct(use_prepacked=False)
+    _check(lib.cq_codebook_grouped_gemm_lut(ctypes.byref(s), _ptr(codes), _ptr(row_scale), _ptr(row_gather),
+                                            _ptr(group_offsets), M_total, epilogue, _ptr(out), out_kind, _stream()))
     return out
 
 

@@ -86,6 +86,9 @@ CONFIGS: Dict[str, LayerConfig] = {
                     outlier_channels=(), n_outliers=8, outlier_scale=100.0, group_k=1024),
         LayerConfig("mixtral_prefill_blockwise", 2, E=8, top_k=2, S=0, H=4096, I=14336, T=4096, act_bits=4,
                     outlier_channels=(), n_outliers=8, outlier_scale=100.0, group_k=1024),
+        # the decode workload with 4-bit activations (what the lookup formulation of the product needs)
+        LayerConfig("mixtral_decode_a4", 1, E=8, top_k=2, S=0, H=4096, I=14336, T=16, act_bits=4,
+                    outlier_channels=(), n_outliers=8, outlier_scale=100.0),
     ]
 }
 

@@ -59,6 +59,18 @@ def test_argument_validation_happens_before_any_device_call():
     assert g(B.CodebookWeights(256, 256, None, 2, 100, 128)) == 2
     assert g(B.CodebookWeights(256, 256, None, 2, 128, 96)) == 2
     assert g(W, a_kind=7) == 3 and g(W, epi=5) == 3 and g(W, outk=9) == 3
+    # the lookup formulation of the product
+    gl = lambda W, epi=0, outk=0, codes=one: lib.cq_codebook_grouped_gemm_lut(ctypes.byref(W), codes, None, None,
+                                                                             one, 4, epi, one, outk, None)
+    assert gl(W, codes=None) == 1
+    assert gl(B.CodebookWeights(None, 256, 256, 2, 128, 128)) == 1          # canonical bytes are required
+    assert gl(B.CodebookWeights(256, 256, None, 2, 100, 128)) == 2
+    assert gl(B.CodebookWeights(256, 256, None, 2, 128, 128, 48)) == 2      # groups of 48 weights
+    assert gl(W, epi=5) == 3 and gl(W, outk=9) == 3
+    # block-wise tables in the matrix-core product: groups must be multiples of 512 weights, rows of 256
+    assert g(B.CodebookWeights(256, 256, None, 2, 256, 1024, 256)) == 3
+    assert g(B.CodebookWeights(256, 256, None, 2, 128, 1024, 512)) == 3
+    assert g(B.CodebookWeights(256, 256, None, 2, 128, 1024, -4)) == 2
     # moe_forward: shape mismatch between layer and weights, bad bits
     gu = B.CodebookWeights(256, 256, None, 4, 256, 128)
     dn = B.CodebookWeights(256, 256, None, 4, 128, 128)

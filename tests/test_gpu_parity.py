@@ -459,6 +459,73 @@ def test_gemm_blockwise_unsupported_shapes_are_refused(B):
                                        B.CQ_EPI_NONE, B.CQ_OUT_F32, use_prepacked=False)
 
 
+# the lookup formulation (product tables in LDS, accumulate without multiplying)
+def test_gemm_lut_tiny_against_python_loops(B):
+    """Against the oracle's own lookup formulation (pure-Python loops): tiny sizes."""
+    rng = np.random.default_rng(71)
+    N, K, M = 64, 64, 3
+    idx = rng.integers(0, 256, size=(1, N, K // 2), dtype=np.uint8)
+    cent = synth.draw_centroids(rng, N)[None]
+    codes = rng.integers(-8, 8, size=(M, K)).astype(np.int8)          # the whole 4-bit range, -8 included
+    W = B.DeviceCodebook(idx, cent, prepack=False)
+    out = B.cq_codebook_grouped_gemm_lut(W, _dev(codes), None, None, _dev(_group_offsets([M])), M, B.CQ_EPI_NONE,
+                                         B.CQ_OUT_F32).cpu().numpy()
+    ref = O.product_lut_matmul(codes.astype(np.int64), idx[0], cent[0], act_bits=4)
+    assert Hp.row_rel_l2(out, ref).max() < 2e-6
+
+
+@pytest.mark.parametrize("N,K,g,counts", [(128, 256, 0, [3, 0, 9, 20]), (192, 1408, 0, [1, 17]),
+                                          (64, 1024, 256, [5, 12]), (128, 1408, 1024, [11])])
+def test_gemm_lut_integer_centroids_exact(B, N, K, g, counts):
+    rng = np.random.default_rng(72 + K)
+    G, M = len(counts), int(sum(counts))
+    if g:
+        cent = _integer_block_tables(rng, G, N, -(-K // g))
+    else:
+        cent = np.broadcast_to(synth.f32_to_bf16_bits(np.arange(16, dtype=np.float32) - 8.0), (G, N, 16)).copy()
+    idx = rng.integers(0, 256, size=(G, N, K // 2), dtype=np.uint8)
+    codes = rng.integers(-8, 8, size=(M, K)).astype(np.int8)
+    off = _group_offsets(counts)
+    W = B.DeviceCodebook(idx, cent, prepack=False, group_k=g)
+    out = B.cq_codebook_grouped_gemm_lut(W, _dev(codes), None, None, _dev(off), M, B.CQ_EPI_NONE,
+                                         B.CQ_OUT_F32).cpu().numpy()
+    for grp in range(G):
+        rows = slice(off[grp], off[grp + 1])
+        ref = O.codebook_matmul(codes[rows].astype(np.float64), idx[grp], cent[grp], g)
+        assert np.array_equal(out[rows].astype(np.float64), ref), f"group {grp}"
+
+
+@pytest.mark.parametrize("out_kind", ["f16", "f32"])
+def test_gemm_lut_swiglu_gather_scale_and_matrix_core_kernel(B, out_kind):
+    """SiLU-gated epilogue with gathered rows and scales, against the oracle and against the matrix-core product."""
+    rng = np.random.default_rng(73)
+    I, K, counts, R = 96, 512, [10, 0, 23], 12
+    G, M = len(counts), sum(counts)
+    draw = lambda: (rng.integers(0, 256, size=(I, K // 2), dtype=np.uint8), synth.draw_centroids(rng, I))
+    gate, up = [draw() for _ in range(G)], [draw() for _ in range(G)]
+    fused = [synth.interleave_gate_up(gate[i], up[i]) for i in range(G)]
+    W = B.DeviceCodebook(np.stack([f[0] for f in fused]), np.stack([f[1] for f in fused]))
+    codes = rng.integers(-7, 8, size=(R, K)).astype(np.int8)
+    scale = rng.uniform(0.01, 0.2, size=R).astype(np.float32)
+    gather = rng.integers(0, R, size=M).astype(np.int32)
+    off = _group_offsets(counts)
+    ok = B.CQ_OUT_F16 if out_kind == "f16" else B.CQ_OUT_F32
+    out = B.cq_codebook_grouped_gemm_lut(W, _dev(codes), _dev(scale), _dev(gather), _dev(off), M, B.CQ_EPI_SWIGLU,
+                                         ok).cpu().numpy().astype(np.float64)
+    mm = B.cq_codebook_grouped_gemm(W, _dev(codes), B.CQ_A_INT8_CODES, _dev(scale), _dev(gather), _dev(off), M,
+                                    B.CQ_EPI_SWIGLU, ok).cpu().numpy().astype(np.float64)
+    tol = 1e-3 if out_kind == "f16" else 2e-5
+    for grp in range(G):
+        rows = slice(off[grp], off[grp + 1])
+        if rows.start == rows.stop:
+            continue
+        src = gather[rows]
+        a = scale[src, None].astype(np.float64) * codes[src].astype(np.float64)
+        ref = O.silu(O.codebook_matmul(a, *gate[grp])) * O.codebook_matmul(a, *up[grp])
+        assert Hp.row_rel_l2(out[rows], ref).max() < tol
+        assert Hp.row_rel_l2(out[rows], mm[rows]).max() < 2 * tol
+
+
 # ---------------------------------------------------------------------------------------------
 # the whole layer
 # ---------------------------------------------------------------------------------------------
