@@ -17,7 +17,8 @@ What follows which passage of the paper
   route_topk        Top-K experts and weights Pi       ACCF section (MoE weighted sum), appendix (Top-K)
   permute_by_expert X_t = tokens assigned to expert    AOS section (definition of X_t)
   decode_*          W_c[i,j] = sum_k C[i,k] A[i,j,k]   ACCF section (Eq. W_c); embedding-wise or block-wise
-                                                       tables (experimental setup, g = 1024)
+                                                       tables (experimental setup, g = 1024); budgets of 4 or 8
+                                                       centroids (ablation on centroid budgets, W2 / W3)
   expert_ffn        (phi(X W_gate) . X W_up) W_down    AOS section (rotation-invariance equation)
   moe_forward       sum_i Pi_i X_R W_c (+ shared)      ACCF section (Eq. L, MoE case), appendix (shared expert)
   hadamard_*        online Hadamard transform          evaluation section (the "had" variant)
@@ -34,6 +35,7 @@ Readings taken where the paper is silent (each is also listed in the design note
     of order m in {12, 28, 44} when I is not a power of two, and quantized per row exactly like X_R;
   * block-wise clustering groups g consecutive weights of a row along d_in; when g does not divide d_in
     the last group of the row is shorter;
+  * 2- and 3-bit indices (budgets of 4 and 8 centroids) are packed as a little-endian bit stream per row;
   * phi is SiLU; the output stays in the rotated basis (no R^T is applied);
   * shared experts see every token with weight 1 and are added after the routed sum.
 
@@ -66,6 +68,33 @@ def unpack_indices(idx_packed: np.ndarray) -> np.ndarray:
     out[:, 0::2] = p & 0x0F
     out[:, 1::2] = p >> 4
     return out
+
+
+def unpack_indices_bits(idx_packed: np.ndarray, bits: int, K: int) -> np.ndarray:
+    """[N, K*bits/8] bytes -> [N, K] indices in [0, 2^bits) for the smaller centroid budgets (W2: 4
+    centroids, W3: 8; ablation on centroid budgets).  The indices of a row form one little-endian bit
+    stream: weight j occupies bits [j*bits, (j+1)*bits) of the row, bit i of the stream being bit i%8 of
+    byte i//8.  With bits = 4 this is the nibble order of unpack_indices."""
+    p = np.asarray(idx_packed, dtype=np.uint8)
+    assert p.shape[1] * 8 == K * bits
+    stream = np.unpackbits(p, axis=1, bitorder="little")            # [N, K*bits], stream bit i at column i
+    fields = stream.reshape(p.shape[0], K, bits).astype(np.uint8)   # field j = bits j*bits .. j*bits+bits-1
+    weights = (np.uint8(1) << np.arange(bits, dtype=np.uint8))
+    return (fields * weights[None, None, :]).sum(axis=2).astype(np.uint8)
+
+
+def decode_weights_budget(idx_packed: np.ndarray, cent_bits: np.ndarray, bits: int, K: int,
+                          group_k: int = 0) -> np.ndarray:
+    """W_c [N, K] float64 for a budget of 2^bits centroids per table (Eq. W_c with fewer columns in C):
+    cent_bits is [N, 2^bits] or, block-wise, [N, ceil(K/g), 2^bits]."""
+    idx = unpack_indices_bits(idx_packed, bits, K).astype(np.int64)
+    cent = np.asarray(cent_bits)
+    C = bf16_bits_to_f64(cent if group_k > 0 else cent[:, None, :])
+    assert C.shape[2] == 2 ** bits and C.shape[1] == (-(-K // group_k) if group_k > 0 else 1)
+    W = np.empty(idx.shape, dtype=np.float64)
+    for b, j0, j1 in _column_groups(K, group_k):
+        W[:, j0:j1] = np.take_along_axis(C[:, b], idx[:, j0:j1], axis=1)
+    return W
 
 
 # ------------------------------------------------------------------------------------------

@@ -229,6 +229,20 @@ def redraw_rows(inputs: LayerInputs, rows: np.ndarray, attempt: int) -> None:
     inputs.redrawn_rows += int(rows.size)
 
 
+def pack_indices_bits(idx: np.ndarray, bits: int) -> np.ndarray:
+    """[N, K] indices in [0, 2^bits) -> [N, K*bits/8] bytes: weight j at bits [j*bits, (j+1)*bits) of the row's
+    little-endian bit stream (pure layout; with bits = 4, weight 2j is the low nibble of byte j)."""
+    idx = np.asarray(idx, dtype=np.uint64)
+    N, K = idx.shape
+    assert (K * bits) % 8 == 0 and int(idx.max(initial=0)) < (1 << bits)
+    out = np.zeros((N, K * bits // 8), dtype=np.uint8)
+    for j in range(K):
+        for i in range(bits):
+            pos = j * bits + i
+            out[:, pos >> 3] |= (((idx[:, j] >> np.uint64(i)) & np.uint64(1)) << np.uint64(pos & 7)).astype(np.uint8)
+    return out
+
+
 def interleave_gate_up(gate: Tuple[np.ndarray, np.ndarray],
                        up: Tuple[np.ndarray, np.ndarray]) -> Tuple[np.ndarray, np.ndarray]:
     """Fused [2I, ...] matrix whose row 2i is gate row i and row 2i+1 is up row i (pure layout)."""

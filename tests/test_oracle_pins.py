@@ -290,6 +290,43 @@ def test_blockwise_layer_matches_dense():
         assert np.allclose(res["Y"][t], y[0], rtol=1e-10, atol=1e-12)
 
 
+def test_smaller_centroid_budgets():
+    """W2 / W3: 4 or 8 centroids, indices as a little-endian bit stream per row."""
+    # hand-made bytes.  2 bits: 0b11_10_01_00 = 0xE4 holds weights 0,1,2,3 = 0,1,2,3.
+    assert O.unpack_indices_bits(np.array([[0xE4, 0x1B]], dtype=np.uint8), 2, 8).tolist() == [[0, 1, 2, 3, 3, 2, 1, 0]]
+    # 3 bits: weights 0..7 = 0..7 -> stream 000 100 010 110 001 101 011 111 (LSB first) = bytes 0x88 0xC6 0xFA
+    assert O.unpack_indices_bits(np.array([[0x88, 0xC6, 0xFA]], dtype=np.uint8), 3, 8).tolist() == \
+        [[0, 1, 2, 3, 4, 5, 6, 7]]
+    rng = _rng(23)
+    N, K = 5, 64
+    for bits in (2, 3, 4):
+        idx = rng.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+        packed = synth.pack_indices_bits(idx, bits)
+        assert packed.shape == (N, K * bits // 8)
+        assert np.array_equal(O.unpack_indices_bits(packed, bits, K), idx)
+        # brute force over the bit stream
+        for n in (0, N - 1):
+            big = int.from_bytes(packed[n].tobytes(), "little")
+            assert [(big >> (j * bits)) & ((1 << bits) - 1) for j in range(K)] == idx[n].tolist()
+    # 4 bits: the same bytes as the nibble packing used everywhere else
+    idx4 = rng.integers(0, 16, size=(N, K), dtype=np.uint8)
+    assert np.array_equal(synth.pack_indices_bits(idx4, 4), _pack(idx4))
+    assert np.array_equal(O.unpack_indices_bits(_pack(idx4), 4, K), O.unpack_indices(_pack(idx4)))
+    # decode: brute force, embedding-wise and block-wise
+    for bits, g in ((2, 0), (3, 0), (3, 32), (2, 48)):
+        nblk = -(-K // g) if g else 0
+        idx = rng.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+        cent = synth.draw_centroids(rng, N, n_blocks=nblk)[..., :1 << bits]
+        C = O.bf16_bits_to_f64(cent)
+        brute = np.array([[(C[n, j // g, idx[n, j]] if g else C[n, idx[n, j]]) for j in range(K)] for n in range(N)])
+        assert np.array_equal(O.decode_weights_budget(synth.pack_indices_bits(idx, bits), cent, bits, K, g), brute)
+    # a 4-bit table whose upper entries are never addressed decodes to the same matrix
+    idx = rng.integers(0, 4, size=(N, K), dtype=np.uint8)
+    cent16 = synth.draw_centroids(rng, N)
+    assert np.array_equal(O.decode_weights_budget(synth.pack_indices_bits(idx, 2), cent16[:, :4], 2, K),
+                          O.decode_weights(_pack(idx), cent16))
+
+
 def test_codebook_matmul_special_cases():
     rng = _rng(10)
     N, K, M = 10, 64, 4
