@@ -177,6 +177,20 @@ cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W,
                                    void* workspace, size_t workspace_bytes, cq_stream stream);
 
 /*
+ * Smaller centroid budgets (ablation on centroid budgets: W2 = 4 centroids, W3 = 8): conversion of such
+ * weights into the 16-entry format above, once, at load time.
+ *   idx_bits  [G, N, K*bits/8] bytes: the indices of a row as one little-endian bit stream, weight j at bits
+ *             [j*bits, (j+1)*bits) (bit i of the stream = bit i%8 of byte i/8);  bits in {2, 3}
+ *   cent_bits [G, N, tables_per_row, 2^bits] bf16 (tables_per_row = 1, or ceil(K/group_k) for block-wise tables)
+ *   idx4_out  [G, N, K/2] canonical 4-bit bytes;  cent16_out [G, N, tables_per_row, 16]: entries >= 2^bits,
+ *             which no index addresses, repeat the table's last entry.
+ * The products then run on the 4-bit kernels: the results are those of the smaller budget exactly, the bytes
+ * streamed per weight are those of W4 (kernels that read the 2-/3-bit stream directly are not built).
+ */
+cq_status cq_expand_centroid_budget(const uint8_t* idx_bits, const uint16_t* cent_bits, int bits, int G, int N, int K,
+                                    int tables_per_row, uint8_t* idx4_out, uint16_t* cent16_out, cq_stream stream);
+
+/*
  * The same product in the lookup formulation of the kernel section (Fig. 4b and the text beside it): per
  * group of weights that shares a table, the 16 sub-tables (one per centroid) of 16 products centroid x 4-bit
  * activation value are precomputed in LDS; every (weight index, activation code) pair then selects a

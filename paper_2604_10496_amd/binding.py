@@ -26,7 +26,7 @@ EXPORTS = [
     "cq_moe_forward", "cq_moe_forward_timed", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
     "cq_stream_read", "cq_mfma_loop", "cq_rotation_split_bytes", "cq_rotation_split",
     "cq_rotate_quant_split_workspace_bytes", "cq_rotate_quant_split", "cq_hadamard_quant",
-    "cq_codebook_grouped_gemm_lut",
+    "cq_codebook_grouped_gemm_lut", "cq_expand_centroid_budget",
 ]
 
 
@@ -107,6 +107,8 @@ def load_library() -> ctypes.CDLL:
     lib.cq_prepack.argtypes = [ctypes.POINTER(CodebookWeights), vp, sz, vp]
     lib.cq_codebook_grouped_gemm_lut.restype = ci
     lib.cq_codebook_grouped_gemm_lut.argtypes = [ctypes.POINTER(CodebookWeights), vp, vp, vp, vp, ci, ci, vp, ci, vp]
+    lib.cq_expand_centroid_budget.restype = ci
+    lib.cq_expand_centroid_budget.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp]
     lib.cq_decode_dense.restype = ci
     lib.cq_decode_dense.argtypes = [ctypes.POINTER(CodebookWeights), ci, vp, vp]
     lib.cq_device_info.restype = ci
@@ -222,6 +224,28 @@ def cq_codebook_grouped_gemm_lut(W: DeviceCodebook, codes, row_scale, row_gather
     _check(lib.cq_codebook_grouped_gemm_lut(ctypes.byref(s), _ptr(codes), _ptr(row_scale), _ptr(row_gather),
                                             _ptr(group_offsets), M_total, epilogue, _ptr(out), out_kind, _stream()))
     return out
+
+
+def cq_expand_centroid_budget(idx_bits, cent_bits, bits: int, K: int, group_k: int = 0, prepack: bool = True):
+    """W2 / W3 weights ([G, N, K*bits/8] bit-stream bytes, [G, N, (tables,) 2^bits] bf16 tables, numpy or torch)
+    -> a DeviceCodebook in the 16-entry format the kernels read."""
+    torch = _torch()
+    import numpy as np
+    lib = load_library()
+    if isinstance(idx_bits, np.ndarray):
+        idx_bits = torch.from_numpy(np.ascontiguousarray(idx_bits))
+    if isinstance(cent_bits, np.ndarray):
+        cent_bits = torch.from_numpy(np.ascontiguousarray(cent_bits).view(np.int16))
+    idx_bits, cent_bits = idx_bits.to("cuda").contiguous(), cent_bits.to("cuda").contiguous()
+    G, N = int(idx_bits.shape[0]), int(idx_bits.shape[1])
+    tables = -(-K // group_k) if group_k > 0 else 1
+    assert idx_bits.shape[2] * 8 == K * bits and cent_bits.numel() == G * N * tables * (1 << bits)
+    idx4 = torch.empty((G, N, K // 2), dtype=torch.uint8, device="cuda")
+    shape = (G, N, tables, 16) if group_k > 0 else (G, N, 16)
+    cent16 = torch.empty(shape, dtype=torch.int16, device="cuda")
+    _check(lib.cq_expand_centroid_budget(_ptr(idx_bits), _ptr(cent_bits), bits, G, N, K, tables, _ptr(idx4),
+                                         _ptr(cent16), _stream()))
+    return DeviceCodebook(idx4, cent16, prepack=prepack, group_k=group_k)
 
 
 def cq_decode_dense(W: DeviceCodebook, g: int, use_prepacked: bool = True):

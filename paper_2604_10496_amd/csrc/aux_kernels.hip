@@ -74,6 +74,41 @@ __global__ __launch_bounds__(256) void decode_dense_kernel(const uint8_t* __rest
   }
 }
 
+// Budgets of 4 or 8 centroids: indices packed as a little-endian bit stream per row (weight j at bits
+// [j*bits, (j+1)*bits)) -> the canonical 4-bit bytes; one thread per output byte (two weights).
+__global__ __launch_bounds__(256) void expand_indices_kernel(const uint8_t* __restrict__ src, int bits, size_t n_rows,
+                                                             int K, uint8_t* __restrict__ dst) {
+  const size_t half = (size_t)K / 2, total = n_rows * half;
+  const size_t src_row = (size_t)K * bits / 8;
+  const uint32_t mask = (1u << bits) - 1u;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t n = i / half;
+    const uint32_t j = (uint32_t)(i - n * half);
+    const uint8_t* row = src + n * src_row;
+    uint32_t v[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t bit = (2 * j + h) * bits, byte = bit >> 3;
+      uint32_t w = row[byte];
+      if (byte + 1 < src_row) w |= (uint32_t)row[byte + 1] << 8;  // a field may straddle two bytes
+      v[h] = (w >> (bit & 7)) & mask;
+    }
+    dst[i] = (uint8_t)(v[0] | (v[1] << 4));
+  }
+}
+
+// tables of 2^bits entries -> 16 entries (the entries that no index can address repeat the last real one)
+__global__ __launch_bounds__(256) void expand_tables_kernel(const uint16_t* __restrict__ src, int bits, size_t n_tables,
+                                                            uint16_t* __restrict__ dst) {
+  const int n = 1 << bits;
+  const size_t total = n_tables * CQ_N_CENTROIDS;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t t = i / CQ_N_CENTROIDS;
+    const int c = (int)(i - t * CQ_N_CENTROIDS);
+    dst[i] = src[t * n + (c < n ? c : n - 1)];
+  }
+}
+
 // 16 independent accumulators per wavefront: the matrix pipe never waits for a result
 __global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, float* __restrict__ sink) {
   cq_v16f acc[16];
@@ -155,6 +190,22 @@ extern "C" cq_status cq_prepack(const cq_codebook_weights* W, void* dst, size_t 
   const unsigned grid = (unsigned)((n16 + 255) / 256 < 65536 ? (n16 + 255) / 256 : 65536);
   hipLaunchKernelGGL(prepack_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)W->idx,
                      (uint4*)dst, rows, W->K);
+  return cq_check_launch();
+}
+
+extern "C" cq_status cq_expand_centroid_budget(const uint8_t* idx_bits, const uint16_t* cent_bits, int bits, int G,
+                                               int N, int K, int tables_per_row, uint8_t* idx4_out,
+                                               uint16_t* cent16_out, cq_stream stream) {
+  if (!idx_bits || !cent_bits || !idx4_out || !cent16_out) return CQ_ERR_NULL;
+  if (G <= 0 || N <= 0 || K <= 0 || tables_per_row <= 0 || K % 64 != 0) return CQ_ERR_SHAPE;
+  if (bits != 2 && bits != 3) return CQ_ERR_UNSUPPORTED;
+  const size_t rows = (size_t)G * N, bytes = rows * (K / 2), entries = rows * tables_per_row * CQ_N_CENTROIDS;
+  const unsigned g1 = (unsigned)((bytes + 255) / 256 < 65536 ? (bytes + 255) / 256 : 65536);
+  const unsigned g2 = (unsigned)((entries + 255) / 256 < 65536 ? (entries + 255) / 256 : 65536);
+  hipLaunchKernelGGL(expand_indices_kernel, dim3(g1), dim3(256), 0, (hipStream_t)stream, idx_bits, bits, rows, K,
+                     idx4_out);
+  hipLaunchKernelGGL(expand_tables_kernel, dim3(g2), dim3(256), 0, (hipStream_t)stream, cent_bits, bits,
+                     rows * tables_per_row, cent16_out);
   return cq_check_launch();
 }
 

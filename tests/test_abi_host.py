@@ -71,6 +71,9 @@ def test_argument_validation_happens_before_any_device_call():
     assert g(B.CodebookWeights(256, 256, None, 2, 256, 1024, 256)) == 3
     assert g(B.CodebookWeights(256, 256, None, 2, 128, 1024, 512)) == 3
     assert g(B.CodebookWeights(256, 256, None, 2, 128, 1024, -4)) == 2
+    # smaller centroid budgets
+    ex = lambda bits=2, K=128, src=one: lib.cq_expand_centroid_budget(src, one, bits, 2, 64, K, 1, one, one, None)
+    assert ex(src=None) == 1 and ex(K=100) == 2 and ex(bits=4) == 3 and ex(bits=1) == 3
     # moe_forward: shape mismatch between layer and weights, bad bits
     gu = B.CodebookWeights(256, 256, None, 4, 256, 128)
     dn = B.CodebookWeights(256, 256, None, 4, 128, 128)

@@ -459,6 +459,35 @@ def test_gemm_blockwise_unsupported_shapes_are_refused(B):
                                        B.CQ_EPI_NONE, B.CQ_OUT_F32, use_prepacked=False)
 
 
+# budgets of 4 and 8 centroids: converted once into the 16-entry format, then the same kernels
+@pytest.mark.parametrize("bits,N,K,g,counts", [(2, 128, 256, 0, [3, 20]), (3, 192, 1408, 0, [7, 70]),
+                                               (3, 256, 1024, 512, [5, 140]), (2, 256, 4096, 0, [300, 9])])
+def test_smaller_centroid_budgets(B, bits, N, K, g, counts):
+    rng = np.random.default_rng(80 + bits + K)
+    G, M, nblk = len(counts), int(sum(counts)), (-(-K // g) if g else 0)
+    idx = rng.integers(0, 1 << bits, size=(G, N, K), dtype=np.uint8)
+    packed = np.stack([synth.pack_indices_bits(idx[i], bits) for i in range(G)])
+    cent = np.stack([synth.draw_centroids(rng, N, n_blocks=nblk) for _ in range(G)])[..., :1 << bits]
+    W = B.cq_expand_centroid_budget(packed, np.ascontiguousarray(cent), bits, K, group_k=g)
+    # the conversion itself, bit-exact: indices, and tables padded with their last entry
+    assert np.array_equal(W.idx.cpu().numpy(), (idx[..., 0::2] | (idx[..., 1::2] << 4)).astype(np.uint8))
+    c16 = W.cent.cpu().numpy().view(np.uint16)
+    assert np.array_equal(c16[..., :1 << bits], cent) and np.all(c16[..., (1 << bits):] == cent[..., -1:])
+    for grp in range(G):
+        ref = O.decode_weights_budget(packed[grp], cent[grp], bits, K, g)
+        got = synth.bf16_bits_to_f32(B.cq_decode_dense(W, grp).cpu().numpy().view(np.uint16))
+        assert np.array_equal(got.astype(np.float64), ref)
+    # and a product on them
+    A = (rng.standard_normal((M, K)) * 3).astype(np.float16)
+    off = _group_offsets(counts)
+    out = B.cq_codebook_grouped_gemm(W, _dev(A), B.CQ_A_F16, None, None, _dev(off), M, B.CQ_EPI_NONE,
+                                     B.CQ_OUT_F32).cpu().numpy()
+    for grp in range(G):
+        rows = slice(off[grp], off[grp + 1])
+        ref = A[rows].astype(np.float64) @ O.decode_weights_budget(packed[grp], cent[grp], bits, K, g).T
+        assert Hp.row_rel_l2(out[rows], ref).max() < 2e-5
+
+
 # the lookup formulation (product tables in LDS, accumulate without multiplying)
 def test_gemm_lut_tiny_against_python_loops(B):
     """Against the oracle's own lookup formulation (pure-Python loops): tiny sizes."""
