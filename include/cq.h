@@ -66,7 +66,9 @@ enum { CQ_OUT_F32 = 0, CQ_OUT_F16 = 1 };
  *   prepacked optional kernel-native copy of idx written by cq_prepack() (same byte count):
  *             rows are taken 32 at a time and K 64 weights at a time; the 1 KiB tile of row block
  *             rb and K step s is at ((rb*(K/64) + s) * 1024) and holds, for l = 0..63, the 16
- *             canonical bytes of row rb*32 + l%32, byte columns s*32 + (l/32)*16 .. +15, at l*16.
+ *             canonical bytes of row rb*32 + l%32, byte columns s*32 + (l/32)*16 .. +15, at l*16, with
+ *             the nibbles of every 4 bytes (8 weights w0..w7) regrouped: byte i of the four holds w_i in
+ *             bits 0-3 and w_{i+4} in bits 4-7.
  *   K must be a multiple of 64 and N a multiple of 64.
  *   group_k   0 (or >= K): one table per row over all of K ("Embedding-wise", experimental setup).
  *             g > 0: "Block-wise" tables, one per group of g consecutive weights of a row; cent is then

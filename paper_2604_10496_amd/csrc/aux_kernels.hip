@@ -38,7 +38,17 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 }
 
 // canonical [rows, K/2] -> tiles of 32 rows x 64 weights (1 KiB): lane l of a tile owns the 16 bytes
-// of row l%32, byte columns s*32 + (l/32)*16.
+// of row l%32, byte columns s*32 + (l/32)*16.  Inside every dword (8 weights w0..w7) the nibbles are
+// regrouped: byte i holds w_i (low nibble) and w_{i+4} (high nibble), so that the register decoder's two
+// nibble planes are the first and the second four weights (no reordering after the lookup).
+__device__ __forceinline__ uint32_t regroup_nibbles(uint32_t d) {
+  const uint32_t lo = d & 0x0f0f0f0fu;         // w0 w2 w4 w6
+  const uint32_t hi = (d >> 4) & 0x0f0f0f0fu;  // w1 w3 w5 w7
+  const uint32_t x = __builtin_amdgcn_perm(hi, lo, 0x05010400u);  // w0 w1 w2 w3
+  const uint32_t y = __builtin_amdgcn_perm(hi, lo, 0x07030602u);  // w4 w5 w6 w7
+  return x | (y << 4);
+}
+
 __global__ __launch_bounds__(256) void prepack_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
                                                       size_t n_rows, int K) {
   const size_t n16 = n_rows * (size_t)(K / 32);  // 16-byte pieces in total
@@ -50,7 +60,8 @@ __global__ __launch_bounds__(256) void prepack_kernel(const uint4* __restrict__ 
     const int s = (int)(tile - rb * steps);
     const size_t row = rb * 32 + (l & 31);
     const size_t piece = (size_t)s * 2 + (l >> 5);  // 16-byte piece inside the row
-    dst[i] = src[row * (size_t)(K / 32) + piece];
+    const uint4 v = src[row * (size_t)(K / 32) + piece];
+    dst[i] = make_uint4(regroup_nibbles(v.x), regroup_nibbles(v.y), regroup_nibbles(v.z), regroup_nibbles(v.w));
   }
 }
 
@@ -61,16 +72,23 @@ __global__ __launch_bounds__(256) void decode_dense_kernel(const uint8_t* __rest
   const int steps = K / 64;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
     const size_t n = i / (K / 2);
-    const int bc = (int)(i - n * (K / 2));  // canonical byte column
-    size_t src = i;
-    if (prepacked) {
-      const int s = bc >> 5, g = (bc >> 4) & 1, within = bc & 15;
-      src = (((n >> 5) * steps + s) * 64 + g * 32 + (n & 31)) * 16 + within;
-    }
-    const uint32_t b = idx[src];
+    const int bc = (int)(i - n * (K / 2));  // canonical byte column: weights 2 bc and 2 bc + 1
     const uint16_t* c = cent + (n * nblk + (size_t)((2 * bc) / group_k)) * CQ_N_CENTROIDS;  // group_k is even
-    out[n * K + 2 * bc] = c[b & 15u];
-    out[n * K + 2 * bc + 1] = c[b >> 4];
+    uint32_t i0, i1;
+    if (prepacked) {
+      // 16-byte piece of (row block, step, lane); inside a dword weight w of 8 sits in byte w % 4, nibble w / 4
+      const int s = bc >> 5, g = (bc >> 4) & 1, within = bc & 15;
+      const size_t piece = (((n >> 5) * steps + s) * 64 + g * 32 + (n & 31)) * 16 + (within & ~3);
+      const int w0 = 2 * (within & 3), w1 = w0 + 1;
+      i0 = (idx[piece + (w0 & 3)] >> (4 * (w0 >> 2))) & 15u;
+      i1 = (idx[piece + (w1 & 3)] >> (4 * (w1 >> 2))) & 15u;
+    } else {
+      const uint32_t b = idx[i];
+      i0 = b & 15u;
+      i1 = b >> 4;
+    }
+    out[n * K + 2 * bc] = c[i0];
+    out[n * K + 2 * bc + 1] = c[i1];
   }
 }
 

@@ -183,6 +183,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     // last chunk; rows of padding tokens read row 0 and store zeros): one memory latency per pass
     // instead of one per chunk.
     auto stage = [&](int sl) {
+      const bool grouped = p.prepacked != 0;
       const int k0 = sl * KSfull;
       const int nC = min(KSfull, Kl - k0) >> 3;
       const size_t ebase = srow + (size_t)sb * 64 + k0;
@@ -208,25 +209,38 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
           if (ci >= nC) break;
           uint4 v = make_uint4(0u, 0u, 0u, 0u);
           if (svalid) {
+            // The prepacked bytes pair weight i with weight i+4 of every 8, and so does a looked-up pair: the
+            // 8 activations of a chunk are then paired the same way (k0 k4 | k1 k5 | k2 k6 | k3 k7) instead
+            // of (k0 k1 | k2 k3 | k4 k5 | k6 k7).
             if constexpr (AK == CQ_A_INT8_CODES) {
               const uint32_t rw[2] = {raw[i].x, raw[i].y};
-              uint32_t o[4];
+              uint32_t c8[8];
 #pragma unroll
               for (int h = 0; h < 2; ++h) {
-                const int b0 = (int)(int8_t)(rw[h] & 0xff), b1 = (int)(int8_t)((rw[h] >> 8) & 0xff);
-                const int b2 = (int)(int8_t)((rw[h] >> 16) & 0xff), b3 = (int)(int8_t)(rw[h] >> 24);
-                o[2 * h] = code_to_bf16_bits(b0) | (code_to_bf16_bits(b1) << 16);
-                o[2 * h + 1] = code_to_bf16_bits(b2) | (code_to_bf16_bits(b3) << 16);
+                c8[4 * h] = code_to_bf16_bits((int)(int8_t)(rw[h] & 0xff));
+                c8[4 * h + 1] = code_to_bf16_bits((int)(int8_t)((rw[h] >> 8) & 0xff));
+                c8[4 * h + 2] = code_to_bf16_bits((int)(int8_t)((rw[h] >> 16) & 0xff));
+                c8[4 * h + 3] = code_to_bf16_bits((int)(int8_t)(rw[h] >> 24));
               }
-              v = make_uint4(o[0], o[1], o[2], o[3]);
+              v = grouped ? make_uint4(c8[0] | (c8[4] << 16), c8[1] | (c8[5] << 16), c8[2] | (c8[6] << 16),
+                                       c8[3] | (c8[7] << 16))
+                          : make_uint4(c8[0] | (c8[1] << 16), c8[2] | (c8[3] << 16), c8[4] | (c8[5] << 16),
+                                       c8[6] | (c8[7] << 16));
             } else if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
               v = raw[i];
+              if (grouped)
+                v = make_uint4(__builtin_amdgcn_perm(v.z, v.x, 0x05040100u), __builtin_amdgcn_perm(v.z, v.x, 0x07060302u),
+                               __builtin_amdgcn_perm(v.w, v.y, 0x05040100u), __builtin_amdgcn_perm(v.w, v.y, 0x07060302u));
             } else {
               const uint4 f0 = raw[i], f1 = raw2[i];
-              v.x = f32_to_f16_bits_sat(__uint_as_float(f0.x)) | (f32_to_f16_bits_sat(__uint_as_float(f0.y)) << 16);
-              v.y = f32_to_f16_bits_sat(__uint_as_float(f0.z)) | (f32_to_f16_bits_sat(__uint_as_float(f0.w)) << 16);
-              v.z = f32_to_f16_bits_sat(__uint_as_float(f1.x)) | (f32_to_f16_bits_sat(__uint_as_float(f1.y)) << 16);
-              v.w = f32_to_f16_bits_sat(__uint_as_float(f1.z)) | (f32_to_f16_bits_sat(__uint_as_float(f1.w)) << 16);
+              const uint32_t c8[8] = {f32_to_f16_bits_sat(__uint_as_float(f0.x)), f32_to_f16_bits_sat(__uint_as_float(f0.y)),
+                                      f32_to_f16_bits_sat(__uint_as_float(f0.z)), f32_to_f16_bits_sat(__uint_as_float(f0.w)),
+                                      f32_to_f16_bits_sat(__uint_as_float(f1.x)), f32_to_f16_bits_sat(__uint_as_float(f1.y)),
+                                      f32_to_f16_bits_sat(__uint_as_float(f1.z)), f32_to_f16_bits_sat(__uint_as_float(f1.w))};
+              v = grouped ? make_uint4(c8[0] | (c8[4] << 16), c8[1] | (c8[5] << 16), c8[2] | (c8[6] << 16),
+                                       c8[3] | (c8[7] << 16))
+                          : make_uint4(c8[0] | (c8[1] << 16), c8[2] | (c8[3] << 16), c8[4] | (c8[5] << 16),
+                                       c8[6] | (c8[7] << 16));
             }
           }
           slab[ci * Mpad + st] = v;

@@ -9,7 +9,7 @@
 //     nibbles become byte selectors, v_perm_b32 picks the low and the high bytes of the centroids out
 //     of register-resident byte tables (two 8-entry halves; a third perm, steered by bit 3 of the
 //     index, picks between them), two more perm levels interleave the bytes into bf16/f16 pairs.
-//     About 1.7 ALU operations per MFMA, all full rate, hidden behind the matrix pipe.
+//     About 1.5 ALU operations per MFMA, all full rate, mostly hidden behind the matrix pipe.
 //     With block-wise tables (one per group of g weights along K, g a multiple of 512) the two tables are
 //     replaced every g/64 steps; the raw tables of the next group are requested one group ahead;
 //   * LDS holds only the activation tiles.  They arrive by direct global->LDS loads (no staging
@@ -89,8 +89,9 @@ constexpr int epilogue_row_stride(int epi, int outk) {
 // One tile: 256 weight rows (row tile rt) x up to 32*C tokens (rows mrow0 .. mrow0+mcnt-1 of group grp).
 // F16: the activations are f16 (else bf16); C = CT/32 token blocks (8, 4 or 2); D = depth of the load
 // pipeline in K steps (a power of two; narrow tiles spend less matrix time per step and need more).
-// BLK: block-wise centroid tables (p.nblk per row, each serving p.gsteps K steps).
-template <bool F16, int EPI, int OUTK, int C, int D, bool BLK>
+// BLK: block-wise centroid tables (p.nblk per row, each serving p.gsteps K steps).  PRE: the indices are the
+// prepacked copy (whose nibble arrangement decodes with four operations fewer per 8 weights).
+template <bool F16, int EPI, int OUTK, int C, int D, bool BLK, bool PRE>
 __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, const int mrow0, const int mcnt,
                                            const int rt) {
   constexpr int CT = 32 * C;
@@ -104,7 +105,7 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   const uint8_t* wbase = p.idx + ((size_t)grp * N + n0) * rowbytes;
   const uint8_t *wp0, *wp1;  // this lane's 16 bytes of step 0, for each of its two rows
   int sstride;
-  if (p.prepacked) {
+  if constexpr (PRE) {
     wp0 = wbase + (size_t)lane * 16;
     wp1 = wbase + 32 * rowbytes + (size_t)lane * 16;
     sstride = 1024;
@@ -225,8 +226,8 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   // its registers take the block's fragment of the next sub-step (a full sub-step of slack).
   cq_v4u af[2][2];
   cq_v4u bfr[C];
-  af[0][0] = decode8(wq[0][0][0], t0);
-  af[0][1] = decode8(wq[0][1][0], t1);
+  af[0][0] = decode8<PRE>(wq[0][0][0], t0);
+  af[0][1] = decode8<PRE>(wq[0][1][0], t1);
 #pragma unroll
   for (int cb = 0; cb < C; ++cb) bfr[cb] = read_b(0, 0, cb);
 
@@ -271,8 +272,8 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
         else if (jj < C) fetch_tile(s3, (par + D - 1) & (D - 1), jj, 1);
         // next sub-step: jj + 1 of this step, or the first one of the next step
         const int nbuf = jj < 3 ? par : (par + 1) & (D - 1), njj = (jj + 1) & 3;
-        af[nxt][0] = decode8(wq[nbuf][0][njj], t0);
-        af[nxt][1] = decode8(wq[nbuf][1][njj], t1);
+        af[nxt][0] = decode8<PRE>(wq[nbuf][0][njj], t0);
+        af[nxt][1] = decode8<PRE>(wq[nbuf][1][njj], t1);
 #pragma unroll
         for (int cb = 0; cb < C; ++cb) {
           const cq_v4u b = bfr[cb];
@@ -385,7 +386,7 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
 // round-robin over the 8 XCDs): XCD x takes a contiguous share of the 256-token work and then a
 // contiguous share of the 128-token and of the 64-token work (neighbours share activations in its L2;
 // equal mix on every XCD).  The grid is sized for the worst case; the lists are usually much shorter.
-template <bool F16, int EPI, int OUTK, bool BLK>
+template <bool F16, int EPI, int OUTK, bool BLK, bool PRE>
 __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   const int n256 = p.n_tiles[0] * p.row_tiles, n128 = p.n_tiles[1] * p.row_tiles, n64 = p.n_tiles[5] * p.row_tiles;
   const int per256 = (n256 + 7) >> 3, per128 = (n128 + 7) >> 3, per64 = (n64 + 7) >> 3;
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n256) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles + tile * 4;
-    large_tile<F16, EPI, OUTK, 8, 4, BLK>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 8, 4, BLK, PRE>(p, t[0], t[1], t[2], rt);
     return;
   }
   slot -= per256;
@@ -405,7 +406,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n128) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles128 + tile * 4;
-    large_tile<F16, EPI, OUTK, 4, 8, BLK>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 4, 8, BLK, PRE>(p, t[0], t[1], t[2], rt);
     return;
   }
   slot -= per128;
@@ -414,14 +415,14 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     if (work >= n64) return;
     const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
     const int32_t* t = p.tiles64 + tile * 4;
-    large_tile<F16, EPI, OUTK, 2, 8, BLK>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 2, 8, BLK, PRE>(p, t[0], t[1], t[2], rt);
   }
 }
 
 // The 64-token tiles alone, for launches in which no group has more than 64 rows (block-wise tables at decode
 // sizes): a quarter of the accumulators and half the LDS, so two workgroups share a compute unit and each
 // SIMD has a second wavefront to hide the decode's vector-ALU work behind.
-template <bool F16, int EPI, int OUTK, bool BLK>
+template <bool F16, int EPI, int OUTK, bool BLK, bool PRE>
 __global__ __launch_bounds__(256, 2) void gemm_large64_kernel(const LargeArgs p) {
   const int n64 = p.n_tiles[5] * p.row_tiles;
   const int per64 = (n64 + 7) >> 3;
@@ -431,7 +432,7 @@ __global__ __launch_bounds__(256, 2) void gemm_large64_kernel(const LargeArgs p)
   if (work >= n64) return;
   const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
   const int32_t* t = p.tiles64 + tile * 4;
-  large_tile<F16, EPI, OUTK, 2, 8, BLK>(p, t[0], t[1], t[2], rt);
+  large_tile<F16, EPI, OUTK, 2, 8, BLK, PRE>(p, t[0], t[1], t[2], rt);
 }
 
 // Pre-pass for activation kinds the main kernel does not read: sorted row m of the result is row
@@ -562,7 +563,7 @@ cq_status configure_lds(Kernel kern, int lds, bool* configured) {
 }
 
 // only64: the caller knows that no group has more than 64 rows
-template <bool F16, int EPI, int OUTK, bool BLK>
+template <bool F16, int EPI, int OUTK, bool BLK, bool PRE>
 cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, const int32_t* counts, int max256,
                       int max128, bool only64, hipStream_t s) {
   a.tiles = t256;
@@ -571,7 +572,7 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
   a.n_tiles = counts;
   constexpr int lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
   if constexpr (BLK) if (only64) {
-    auto kern = gemm_large64_kernel<F16, EPI, OUTK, BLK>;
+    auto kern = gemm_large64_kernel<F16, EPI, OUTK, BLK, PRE>;
     constexpr int lds_loop = 8 * 64 * kStepBytes + (BLK ? 8 * kNextTableBytes : 0);
     constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
     static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
@@ -584,7 +585,7 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
     hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)((total + a.ksteps - 1) / a.ksteps)), dim3(256), lds, s, a);
     return cq_check_launch();
   }
-  auto kern = gemm_large_kernel<F16, EPI, OUTK, BLK>;
+  auto kern = gemm_large_kernel<F16, EPI, OUTK, BLK, PRE>;
   constexpr int lds_loop = kLdsTileBytes + (BLK ? 8 * kNextTableBytes : 0);
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
   static bool configured = false;
@@ -599,16 +600,24 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
   return cq_check_launch();
 }
 
-template <bool F16, bool BLK>
-cq_status dispatch_large_blk(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
+template <bool F16, bool BLK, bool PRE>
+cq_status dispatch_large_pre(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
                              const int32_t* counts, int max256, int max128, bool only64, hipStream_t s) {
   if (epilogue == CQ_EPI_SWIGLU)
     return out_kind == CQ_OUT_F16
-               ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16, BLK>(a, t256, t128, counts, max256, max128, only64, s)
-               : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32, BLK>(a, t256, t128, counts, max256, max128, only64, s);
+               ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16, BLK, PRE>(a, t256, t128, counts, max256, max128, only64, s)
+               : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32, BLK, PRE>(a, t256, t128, counts, max256, max128, only64, s);
   return out_kind == CQ_OUT_F16
-             ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16, BLK>(a, t256, t128, counts, max256, max128, only64, s)
-             : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32, BLK>(a, t256, t128, counts, max256, max128, only64, s);
+             ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16, BLK, PRE>(a, t256, t128, counts, max256, max128, only64, s)
+             : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32, BLK, PRE>(a, t256, t128, counts, max256, max128, only64, s);
+}
+
+template <bool F16, bool BLK>
+cq_status dispatch_large_blk(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
+                             const int32_t* counts, int max256, int max128, bool only64, hipStream_t s) {
+  return a.prepacked
+             ? dispatch_large_pre<F16, BLK, true>(a, epilogue, out_kind, t256, t128, counts, max256, max128, only64, s)
+             : dispatch_large_pre<F16, BLK, false>(a, epilogue, out_kind, t256, t128, counts, max256, max128, only64, s);
 }
 
 // The two-workgroup kernel for 64-token tiles exists for block-wise tables only (the streaming kernel takes

@@ -39,10 +39,15 @@ __device__ __forceinline__ RowTable make_row_table(const uint16_t* crow) {
   return make_row_table<F16>(p);
 }
 
-// 8 packed indices (one dword, weight 2i in the low nibble of byte i) -> 4 dwords of 16-bit pairs
+// 8 packed indices (one dword) -> 4 dwords of 16-bit pairs.  GROUPED = false: canonical bytes (weight 2i in
+// the low nibble of byte i, 2i+1 in the high one).  GROUPED = true: the prepacked arrangement (weight i in the
+// low nibble of byte i, weight i+4 in the high one): the two nibble planes are then the first and the second
+// four weights, and the final re-pairing of even and odd weights falls away.
+template <bool GROUPED>
 __device__ __forceinline__ cq_v4u decode8(uint32_t d, const RowTable& t) {
-  const uint32_t sA = d & 0x07070707u;                 // even weights: selector within a half table
-  const uint32_t sB = (d >> 4) & 0x07070707u;          // odd weights
+  // selectors within a half table: low nibbles (even weights, or weights 0..3), high nibbles (odd, or 4..7)
+  const uint32_t sA = d & 0x07070707u;
+  const uint32_t sB = (d >> 4) & 0x07070707u;
   // bit 3 of an index picks the upper half table: as a byte selector, byte i of the result comes from
   // the lower-half candidate (source bytes 0-3) or the upper-half one (bytes 4-7)
   const uint32_t mA = ((d >> 1) & 0x04040404u) | 0x03020100u;
@@ -53,9 +58,10 @@ __device__ __forceinline__ cq_v4u decode8(uint32_t d, const RowTable& t) {
   const uint32_t hiB0 = __builtin_amdgcn_perm(t.hi[1], t.hi[0], sB), hiB1 = __builtin_amdgcn_perm(t.hi[3], t.hi[2], sB);
   const uint32_t loA = __builtin_amdgcn_perm(loA1, loA0, mA), hiA = __builtin_amdgcn_perm(hiA1, hiA0, mA);
   const uint32_t loB = __builtin_amdgcn_perm(loB1, loB0, mB), hiB = __builtin_amdgcn_perm(hiB1, hiB0, mB);
-  // 16-bit values: xa01 = {even0, even1}, xa23 = {even2, even3}; same for the odd weights
+  // 16-bit values: xa01 = {low-nibble weights 0, 1}, xa23 = {2, 3}; same for the high-nibble weights
   const uint32_t xa01 = __builtin_amdgcn_perm(hiA, loA, 0x05010400u), xa23 = __builtin_amdgcn_perm(hiA, loA, 0x07030602u);
   const uint32_t xb01 = __builtin_amdgcn_perm(hiB, loB, 0x05010400u), xb23 = __builtin_amdgcn_perm(hiB, loB, 0x07030602u);
+  if constexpr (GROUPED) return cq_v4u{xa01, xa23, xb01, xb23};
   cq_v4u o;
   o[0] = __builtin_amdgcn_perm(xb01, xa01, 0x05040100u);  // weights 0,1
   o[1] = __builtin_amdgcn_perm(xb01, xa01, 0x07060302u);  // weights 2,3

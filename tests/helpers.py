@@ -63,3 +63,22 @@ def row_rel_l2(a, ref):
     num = np.linalg.norm(a - ref, axis=1)
     den = np.linalg.norm(ref, axis=1)
     return num / np.where(den == 0, 1.0, den)
+
+
+def prepack_model(idx):
+    """The layout stated in cq.h, written out in numpy for one [N, K/2] matrix of canonical bytes."""
+    N, Kh = idx.shape
+    K = 2 * Kh
+    packed = np.empty(N * Kh, dtype=np.uint8)
+    for rb in range(N // 32):
+        for s in range(K // 64):
+            base = (rb * (K // 64) + s) * 1024
+            for l in range(64):
+                row, col = rb * 32 + l % 32, s * 32 + (l // 32) * 16
+                piece = idx[row, col:col + 16].astype(np.uint32)
+                w = np.empty(32, dtype=np.uint32)            # the 32 weights of the piece
+                w[0::2], w[1::2] = piece & 15, piece >> 4
+                w = w.reshape(4, 8)                           # four dwords of 8 weights
+                regrouped = (w[:, 0:4] | (w[:, 4:8] << 4)).reshape(16)
+                packed[base + l * 16: base + l * 16 + 16] = regrouped
+    return packed

@@ -7,6 +7,8 @@ import re
 import numpy as np
 import pytest
 
+from tests import helpers as Hp
+
 from paper_2604_10496_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -119,14 +121,20 @@ def test_workspace_sizes_are_pure_and_monotone():
 
 
 def test_prepack_layout_documented_in_header_matches_numpy_model():
-    """The tile order stated in cq.h, modelled in numpy, is a permutation of the canonical bytes."""
+    """The tile order and nibble grouping stated in cq.h keep every weight exactly once."""
+    rng = np.random.default_rng(5)
     N, K = 64, 128
-    canon = np.arange(N * K // 2, dtype=np.int64).reshape(N, K // 2)
-    packed = np.empty(N * K // 2, dtype=np.int64)
-    for rb in range(N // 32):
-        for s in range(K // 64):
-            base = (rb * (K // 64) + s) * 1024
-            for l in range(64):
-                row, col = rb * 32 + l % 32, s * 32 + (l // 32) * 16
-                packed[base + l * 16: base + l * 16 + 16] = canon[row, col:col + 16]
-    assert sorted(packed.tolist()) == list(range(N * K // 2))
+    idx = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    packed = Hp.prepack_model(idx)
+    # read every weight back through the documented position
+    for n in (0, 17, 40, 63):
+        for k in (0, 1, 5, 12, 63, 64, 77, 127):
+            rb, s, l = n // 32, k // 64, (n % 32) + 32 * ((k % 64) // 32)
+            within = k % 32                                   # weight inside the lane's 16-byte piece
+            dword, w = within // 8, within % 8
+            byte = packed[(rb * (K // 64) + s) * 1024 + l * 16 + dword * 4 + w % 4]
+            got = (int(byte) >> (4 * (w // 4))) & 15
+            want = (int(idx[n, k // 2]) >> (4 * (k % 2))) & 15
+            assert got == want
+    assert sorted(np.concatenate([packed & 15, packed >> 4]).tolist()) == \
+        sorted(np.concatenate([idx.reshape(-1) & 15, idx.reshape(-1) >> 4]).tolist())

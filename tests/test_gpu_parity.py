@@ -64,6 +64,15 @@ def test_decode_dense_bit_exact(B, G, N, K):
             assert np.array_equal(got, ref), f"decode mismatch g={g} prepacked={pre}"
 
 
+def test_prepacked_copy_matches_documented_layout(B):
+    rng = np.random.default_rng(99)
+    idx = rng.integers(0, 256, size=(2, 64, 192), dtype=np.uint8)
+    W = B.DeviceCodebook(idx, np.stack([synth.draw_centroids(rng, 64) for _ in range(2)]), prepack=True)
+    got = W.prepacked.cpu().numpy().reshape(2, -1)
+    for g in range(2):
+        assert np.array_equal(got[g], Hp.prepack_model(idx[g]))
+
+
 @pytest.mark.parametrize("N,K,g", [(64, 1024, 512), (128, 1408, 1024), (64, 256, 64)])
 def test_decode_dense_blockwise_bit_exact(B, N, K, g):
     rng = np.random.default_rng(300 + K + g)
