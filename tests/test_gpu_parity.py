@@ -610,14 +610,14 @@ def _had_reference_output(L, ref, mid, toks):
         for j in range(cfg.top_k):
             e = int(ref["ids"][t, j])
             if e not in dense:
-                dense[e] = O.decode_weights(*L.experts[e]["down"])
+                dense[e] = O.decode_weights(*L.experts[e]["down"], cfg.group_k)
             m = int(inv[t, j])
             assert offsets[e] <= m < offsets[e + 1]
             Y[n] += ref["w"][t, j] * (hs[m] * (dense[e] @ hq[m]))
         for s_ in range(cfg.S):
             e = cfg.E + s_
             if e not in dense:
-                dense[e] = O.decode_weights(*L.experts[e]["down"])
+                dense[e] = O.decode_weights(*L.experts[e]["down"], cfg.group_k)
             m = cfg.T * cfg.top_k + s_ * cfg.T + t
             Y[n] += hs[m] * (dense[e] @ hq[m])
     return Y
@@ -746,6 +746,9 @@ def test_hadamard_quant(B, M, I, bits):
     ("mixtral_prefill", dict(H=1024, I=1408, T=400, group_k=1024)),         # short last group (1408 = 1024 + 384)
     ("dsv2lite", dict(H=512, I=1024, T=64, E=16, group_k=512)),             # shared experts
     ("mixtral_decode", dict(H=1024, I=512, T=16, group_k=2048)),            # group >= K: one table per row
+    # with the online-Hadamard variant: the down product reads integer codes through block-wise tables
+    ("mixtral_decode", dict(H=1024, I=1536, T=16, group_k=512, h_bits=8)),
+    ("mixtral_prefill", dict(H=512, I=1024, T=300, group_k=512, h_bits=4, r_hadamard=True, outlier_channels=(3, 41))),
 ])
 def test_layer_blockwise(B, name, over):
     cfg = synth.small_variant(synth.CONFIGS[name], **over)
