@@ -366,6 +366,23 @@ def test_gemm_swiglu_epilogue(B, out_kind, I, counts):
         assert Hp.row_rel_l2(out[rows], ref).max() < tol
 
 
+@pytest.mark.parametrize("T", [7, 300])
+def test_gemm_single_group_attention_projection_shape(B, T):
+    """One group (G = 1) holding all tokens: the shape of a clustered Q/K/V projection (rotated, quantized input,
+    fused [3H, H] weight), which is the same product as an expert's with one expert and no routing."""
+    rng = np.random.default_rng(91 + T)
+    H = 512
+    idx, cent = _rand_weights(rng, 1, 3 * H, H)
+    X = (rng.standard_normal((T, H)) * 2).astype(np.float32)
+    q, scale = O.quantize(X, 4)
+    W = B.DeviceCodebook(idx, cent)
+    off = np.array([0, T], dtype=np.int32)
+    out = B.cq_codebook_grouped_gemm(W, _dev(q.astype(np.int8)), B.CQ_A_INT8_CODES, _dev(scale.astype(np.float32)), None,
+                                     _dev(off), T, B.CQ_EPI_NONE, B.CQ_OUT_F32).cpu().numpy()
+    ref = O.codebook_matmul(scale.astype(np.float32).astype(np.float64)[:, None] * q, idx[0], cent[0])
+    assert Hp.row_rel_l2(out, ref).max() < 2e-5
+
+
 # block-wise centroid tables (one per group of g weights along K): every group of rows takes the large-tile
 # kernel, whatever its size; tables change inside the K loop (also with a shorter last group)
 BLOCKWISE_CASES = [(256, 1024, 512, [3, 40]), (256, 1408, 1024, [1, 0, 33, 300]), (512, 4096, 1024, [5, 129, 257]),
