@@ -156,8 +156,8 @@ def main():
     dn_s = stage["down"] * 1e-3
     if flop_per_byte < MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9):
         ach = gu_bytes / gu_s / 1e9
-        # (block-wise tables are decoded by the large-tile kernel's 64-token variant, whatever the batch)
-        kern = "gemm_large64_kernel" if g and rows <= 64 else "gemm_large_kernel" if g else "gemm_small_kernel"
+        # (block-wise tables are decoded by the large-tile kernel, at decode sizes by its narrow-tile variant)
+        kern = "gemm_narrow_kernel" if g and rows <= 64 else "gemm_large_kernel" if g else "gemm_small_kernel"
         roofline = {"bound": "hbm", "kernel": f"{kern} (gate/up codebook product + SwiGLU)",
                     "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
                     "traffic": measured_traffic(cfg.name, kern),

@@ -323,10 +323,10 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t v2u;
   typedef __attribute__((address_space(3))) v2u lds_v2u;
 #pragma unroll
-  for (int pass = 0; pass < C / 2; ++pass) {
+  for (int pass = 0; pass < (C + 1) / 2; ++pass) {
     __syncthreads();  // the tile buffers (first pass) or the previous pass's rows are no longer read
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+    for (int half = 0; half < (C >= 2 ? 2 : 1); ++half) {
       const int cb = pass * 2 + half;
       const int tl = half * 32 + r32;  // token within the pass
       float sc = 1.f;
@@ -419,11 +419,11 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   }
 }
 
-// The 64-token tiles alone, for launches in which no group has more than 64 rows (block-wise tables at decode
-// sizes): a quarter of the accumulators and half the LDS, so two workgroups share a compute unit and each
-// SIMD has a second wavefront to hide the decode's vector-ALU work behind.
-template <bool F16, int EPI, int OUTK, bool BLK, bool PRE>
-__global__ __launch_bounds__(256, 2) void gemm_large64_kernel(const LargeArgs p) {
+// Narrow tiles alone, for launches in which no group has more than 64 (C = 2) or 32 (C = 1) rows (block-wise
+// tables at decode sizes): few accumulators and at most half the LDS, so two workgroups share a compute
+// unit.  The list of 64-token tiles holds one entry per non-empty group in such a launch.
+template <bool F16, int EPI, int OUTK, bool BLK, bool PRE, int C>
+__global__ __launch_bounds__(256, 2) void gemm_narrow_kernel(const LargeArgs p) {
   const int n64 = p.n_tiles[5] * p.row_tiles;
   const int per64 = (n64 + 7) >> 3;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256, 2) void gemm_large64_kernel(const LargeArgs p)
   if (work >= n64) return;
   const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
   const int32_t* t = p.tiles64 + tile * 4;
-  large_tile<F16, EPI, OUTK, 2, 8, BLK, PRE>(p, t[0], t[1], t[2], rt);
+  large_tile<F16, EPI, OUTK, C, 8, BLK, PRE>(p, t[0], t[1], t[2], rt);
 }
 
 // Pre-pass for activation kinds the main kernel does not read: sorted row m of the result is row
@@ -562,28 +562,35 @@ cq_status configure_lds(Kernel kern, int lds, bool* configured) {
   return CQ_OK;
 }
 
-// only64: the caller knows that no group has more than 64 rows
+template <bool F16, int EPI, int OUTK, bool BLK, bool PRE, int C>
+cq_status launch_narrow(const LargeArgs& a, int max128, hipStream_t s) {
+  auto kern = gemm_narrow_kernel<F16, EPI, OUTK, BLK, PRE, C>;
+  constexpr int lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
+  constexpr int lds_loop = 8 * 32 * C * kStepBytes + (BLK ? 8 * kNextTableBytes : 0);
+  constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
+  static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
+  static bool configured = false;
+  const cq_status st = configure_lds(kern, lds, &configured);
+  if (st != CQ_OK) return st;
+  const long grid = (((long)max128 * a.row_tiles + 7) / 8) * 8;
+  if (grid <= 0) return CQ_OK;
+  const int total = a.K / kStepK;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)((total + a.ksteps - 1) / a.ksteps)), dim3(256), lds, s, a);
+  return cq_check_launch();
+}
+
+// narrow: 64 or 32 when the caller knows that no group has more rows than that, else 0
 template <bool F16, int EPI, int OUTK, bool BLK, bool PRE>
 cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, const int32_t* counts, int max256,
-                      int max128, bool only64, hipStream_t s) {
+                      int max128, int narrow, hipStream_t s) {
   a.tiles = t256;
   a.tiles128 = t128;
   a.tiles64 = t128 + (size_t)max128 * 4;
   a.n_tiles = counts;
   constexpr int lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
-  if constexpr (BLK) if (only64) {
-    auto kern = gemm_large64_kernel<F16, EPI, OUTK, BLK, PRE>;
-    constexpr int lds_loop = 8 * 64 * kStepBytes + (BLK ? 8 * kNextTableBytes : 0);
-    constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
-    static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
-    static bool configured = false;
-    const cq_status st = configure_lds(kern, lds, &configured);
-    if (st != CQ_OK) return st;
-    const long grid = (((long)max128 * a.row_tiles + 7) / 8) * 8;
-    if (grid <= 0) return CQ_OK;
-    const int total = a.K / kStepK;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)((total + a.ksteps - 1) / a.ksteps)), dim3(256), lds, s, a);
-    return cq_check_launch();
+  if constexpr (BLK) {
+    if (narrow == 32) return launch_narrow<F16, EPI, OUTK, BLK, PRE, 1>(a, max128, s);
+    if (narrow == 64) return launch_narrow<F16, EPI, OUTK, BLK, PRE, 2>(a, max128, s);
   }
   auto kern = gemm_large_kernel<F16, EPI, OUTK, BLK, PRE>;
   constexpr int lds_loop = kLdsTileBytes + (BLK ? 8 * kNextTableBytes : 0);
@@ -602,32 +609,32 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
 
 template <bool F16, bool BLK, bool PRE>
 cq_status dispatch_large_pre(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
-                             const int32_t* counts, int max256, int max128, bool only64, hipStream_t s) {
+                             const int32_t* counts, int max256, int max128, int narrow, hipStream_t s) {
   if (epilogue == CQ_EPI_SWIGLU)
     return out_kind == CQ_OUT_F16
-               ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16, BLK, PRE>(a, t256, t128, counts, max256, max128, only64, s)
-               : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32, BLK, PRE>(a, t256, t128, counts, max256, max128, only64, s);
+               ? launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F16, BLK, PRE>(a, t256, t128, counts, max256, max128, narrow, s)
+               : launch_both<F16, CQ_EPI_SWIGLU, CQ_OUT_F32, BLK, PRE>(a, t256, t128, counts, max256, max128, narrow, s);
   return out_kind == CQ_OUT_F16
-             ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16, BLK, PRE>(a, t256, t128, counts, max256, max128, only64, s)
-             : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32, BLK, PRE>(a, t256, t128, counts, max256, max128, only64, s);
+             ? launch_both<F16, CQ_EPI_NONE, CQ_OUT_F16, BLK, PRE>(a, t256, t128, counts, max256, max128, narrow, s)
+             : launch_both<F16, CQ_EPI_NONE, CQ_OUT_F32, BLK, PRE>(a, t256, t128, counts, max256, max128, narrow, s);
 }
 
 template <bool F16, bool BLK>
 cq_status dispatch_large_blk(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
-                             const int32_t* counts, int max256, int max128, bool only64, hipStream_t s) {
+                             const int32_t* counts, int max256, int max128, int narrow, hipStream_t s) {
   return a.prepacked
-             ? dispatch_large_pre<F16, BLK, true>(a, epilogue, out_kind, t256, t128, counts, max256, max128, only64, s)
-             : dispatch_large_pre<F16, BLK, false>(a, epilogue, out_kind, t256, t128, counts, max256, max128, only64, s);
+             ? dispatch_large_pre<F16, BLK, true>(a, epilogue, out_kind, t256, t128, counts, max256, max128, narrow, s)
+             : dispatch_large_pre<F16, BLK, false>(a, epilogue, out_kind, t256, t128, counts, max256, max128, narrow, s);
 }
 
 // The two-workgroup kernel for 64-token tiles exists for block-wise tables only (the streaming kernel takes
 // the small groups otherwise).
 template <bool F16>
 cq_status dispatch_large(const LargeArgs& a, int epilogue, int out_kind, const int32_t* t256, const int32_t* t128,
-                         const int32_t* counts, int max256, int max128, bool only64, hipStream_t s) {
+                         const int32_t* counts, int max256, int max128, int narrow, hipStream_t s) {
   return a.nblk > 1
-             ? dispatch_large_blk<F16, true>(a, epilogue, out_kind, t256, t128, counts, max256, max128, only64, s)
-             : dispatch_large_blk<F16, false>(a, epilogue, out_kind, t256, t128, counts, max256, max128, false, s);
+             ? dispatch_large_blk<F16, true>(a, epilogue, out_kind, t256, t128, counts, max256, max128, narrow, s)
+             : dispatch_large_blk<F16, false>(a, epilogue, out_kind, t256, t128, counts, max256, max128, 0, s);
 }
 
 size_t tile_list_bytes(int G, int M_total) {
@@ -728,7 +735,8 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
     a.a_gather = nullptr;
   }
   const bool f16 = a_kind == CQ_A_F16 || a_kind == CQ_A_F32;
-  const bool only64 = M_total <= 64;  // then every group has at most 64 rows: one 64-token tile each
-  return f16 ? dispatch_large<true>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, only64, s)
-             : dispatch_large<false>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, only64, s);
+  // with so few rows in all, every group has at most that many: one narrow tile each
+  const int narrow = M_total <= 32 ? 32 : M_total <= 64 ? 64 : 0;
+  return f16 ? dispatch_large<true>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, narrow, s)
+             : dispatch_large<false>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, narrow, s);
 }

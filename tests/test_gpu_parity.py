@@ -450,7 +450,7 @@ def test_gemm_blockwise_float_rows_against_oracle(B, a_kind, N, K, g, counts):
         assert Hp.row_rel_l2(out[rows], ref).max() < 2e-5
 
 
-@pytest.mark.parametrize("counts", [[9, 140], [9, 40]])   # the second: no group above 64 rows (two-workgroup kernel)
+@pytest.mark.parametrize("counts", [[9, 140], [9, 40], [9, 20]])   # no group above 64 / 32 rows: the narrow-tile kernels
 def test_gemm_blockwise_swiglu_epilogue(B, counts):
     rng = np.random.default_rng(61)
     I, K, g = 128, 1024, 512
