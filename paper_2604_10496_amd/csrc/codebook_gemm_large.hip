@@ -226,8 +226,10 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
   // its registers take the block's fragment of the next sub-step (a full sub-step of slack).
   cq_v4u af[2][2];
   cq_v4u bfr[C];
-  af[0][0] = decode8<PRE>(wq[0][0][0], t0);
-  af[0][1] = decode8<PRE>(wq[0][1][0], t1);
+  uint32_t ident = 0x03020100u;   // kept in a vector register (see decode8)
+  asm volatile("" : "+v"(ident));
+  af[0][0] = decode8<PRE>(wq[0][0][0], t0, ident);
+  af[0][1] = decode8<PRE>(wq[0][1][0], t1, ident);
 #pragma unroll
   for (int cb = 0; cb < C; ++cb) bfr[cb] = read_b(0, 0, cb);
 
@@ -272,8 +274,8 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
         else if (jj < C) fetch_tile(s3, (par + D - 1) & (D - 1), jj, 1);
         // next sub-step: jj + 1 of this step, or the first one of the next step
         const int nbuf = jj < 3 ? par : (par + 1) & (D - 1), njj = (jj + 1) & 3;
-        af[nxt][0] = decode8<PRE>(wq[nbuf][0][njj], t0);
-        af[nxt][1] = decode8<PRE>(wq[nbuf][1][njj], t1);
+        af[nxt][0] = decode8<PRE>(wq[nbuf][0][njj], t0, ident);
+        af[nxt][1] = decode8<PRE>(wq[nbuf][1][njj], t1, ident);
 #pragma unroll
         for (int cb = 0; cb < C; ++cb) {
           const cq_v4u b = bfr[cb];

@@ -43,15 +43,17 @@ __device__ __forceinline__ RowTable make_row_table(const uint16_t* crow) {
 // the low nibble of byte i, 2i+1 in the high one).  GROUPED = true: the prepacked arrangement (weight i in the
 // low nibble of byte i, weight i+4 in the high one): the two nibble planes are then the first and the second
 // four weights, and the final re-pairing of even and odd weights falls away.
+// ident: the byte selector 0x03020100 held in a vector register (the merge selector is then one
+// v_and_or_b32; two constants in scalar registers would not fit one instruction).
 template <bool GROUPED>
-__device__ __forceinline__ cq_v4u decode8(uint32_t d, const RowTable& t) {
+__device__ __forceinline__ cq_v4u decode8(uint32_t d, const RowTable& t, uint32_t ident) {
   // selectors within a half table: low nibbles (even weights, or weights 0..3), high nibbles (odd, or 4..7)
   const uint32_t sA = d & 0x07070707u;
   const uint32_t sB = (d >> 4) & 0x07070707u;
   // bit 3 of an index picks the upper half table: as a byte selector, byte i of the result comes from
   // the lower-half candidate (source bytes 0-3) or the upper-half one (bytes 4-7)
-  const uint32_t mA = ((d >> 1) & 0x04040404u) | 0x03020100u;
-  const uint32_t mB = ((d >> 5) & 0x04040404u) | 0x03020100u;
+  const uint32_t mA = ((d >> 1) & 0x04040404u) | ident;
+  const uint32_t mB = ((d >> 5) & 0x04040404u) | ident;
   const uint32_t loA0 = __builtin_amdgcn_perm(t.lo[1], t.lo[0], sA), loA1 = __builtin_amdgcn_perm(t.lo[3], t.lo[2], sA);
   const uint32_t hiA0 = __builtin_amdgcn_perm(t.hi[1], t.hi[0], sA), hiA1 = __builtin_amdgcn_perm(t.hi[3], t.hi[2], sA);
   const uint32_t loB0 = __builtin_amdgcn_perm(t.lo[1], t.lo[0], sB), loB1 = __builtin_amdgcn_perm(t.lo[3], t.lo[2], sB);
