@@ -163,7 +163,8 @@ cq_status cq_route_permute(const float* XR, const float* Wr, const float* bias, 
  *     out[m, n] = (row_scale ? row_scale[src(m)] : 1) * acc[m, n]          (CQ_EPI_NONE, N outputs)
  *     out[m, i] = SiLU(sc*acc[m,2i]) * (sc*acc[m,2i+1])                    (CQ_EPI_SWIGLU, N/2 outputs)
  *   Weights are never materialised: packed indices stream from HBM, are turned into centroid
- *   values through a table staged in LDS, and feed the matrix cores directly.  Integer codes and
+ *   values through a table staged in LDS (groups of up to 32 rows) or held in registers (larger
+ *   groups, and all groups when the tables are block-wise), and feed the matrix cores directly.  Integer codes and
  *   bf16 centroids are exact operands (bf16 MFMA, fp32 accumulation); CQ_A_F16 / CQ_A_F32 rows
  *   use f16 MFMA with centroids converted bf16 -> f16.
  *   A: [rows, K] of a_kind.  out: [M_total, N or N/2] of out_kind (CQ_OUT_F16 saturates).

@@ -1,6 +1,6 @@
 // a6 / a7 for groups with many tokens (prefill regime, bound by the matrix cores).
 //
-// Workgroup tile: 256 weight rows x CT tokens (CT = 256 or 128), four wavefronts, each owning 64 rows
+// Workgroup tile: 256 weight rows x CT tokens (CT = 256, 128, 64 or 32), four wavefronts, each owning 64 rows
 // and ALL the tile's tokens (accumulators 2 x CT/32 MFMA blocks of 32x32).  Consequences:
 //   * every wavefront decodes only its own rows, straight into MFMA A-operand registers: the decoded
 //     weights never touch LDS, and no weight is decoded twice;
@@ -8,8 +8,8 @@
 //     centroid tables it needs are loop invariant and live in registers.  Decoding is pure vector ALU:
 //     nibbles become byte selectors, v_perm_b32 picks the low and the high bytes of the centroids out
 //     of register-resident byte tables (two 8-entry halves; a third perm, steered by bit 3 of the
-//     index, picks between them), two more perm levels interleave the bytes into bf16/f16 pairs.
-//     About 1.5 ALU operations per MFMA, all full rate, mostly hidden behind the matrix pipe.
+//     index, picks between them), one or two more perm levels interleave the bytes into bf16/f16 pairs.
+//     About 1.4 ALU operations per MFMA, all full rate, mostly hidden behind the matrix pipe.
 //     With block-wise tables (one per group of g weights along K, g a multiple of 512) the two tables are
 //     replaced every g/64 steps; the raw tables of the next group are requested one group ahead;
 //   * LDS holds only the activation tiles.  They arrive by direct global->LDS loads (no staging
