@@ -88,6 +88,11 @@ def test_argument_validation_happens_before_any_device_call():
     assert lib.cq_moe_forward(ctypes.byref(Lbad2), one, 16, one, one, 1 << 30, None) == 2
     Lbad3 = B.Layer(128, 64, 4, 2, 0, 8, 256, 256, None, gu, dn)
     assert lib.cq_moe_forward(ctypes.byref(Lbad3), one, 16, one, one, 1 << 30, None) == 2
+    # block-wise tables the kernels cannot take: refused for the layer as well
+    gu_b = B.CodebookWeights(256, 256, None, 4, 256, 128, 64)
+    Lblk = B.Layer(128, 128, 4, 2, 0, 8, 256, 256, None, gu_b, dn)
+    assert lib.cq_moe_workspace_bytes(ctypes.byref(Lblk), 16) == 0
+    assert lib.cq_moe_forward(ctypes.byref(Lblk), one, 16, one, one, 1 << 30, None) == 3
     # prepack / decode
     assert lib.cq_prepack(ctypes.byref(W), one, 8, None) == 4
     assert lib.cq_decode_dense(ctypes.byref(W), 5, one, None) == 2
