@@ -33,8 +33,18 @@ def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def _compile(src: str) -> str:
+def _stale(src: str, obj: str) -> bool:
+    if not os.path.exists(obj):
+        return True
+    deps = [os.path.join(CSRC, src), os.path.join(INCLUDE, "cq.h")]
+    deps += [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
+
+
+def _compile(src: str, force: bool = True) -> str:
     obj = os.path.join(BUILD_DIR, src[:-4] + ".o")
+    if not force and not _stale(src, obj):
+        return obj
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
@@ -46,10 +56,11 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(verbose: bool = True) -> str:
+def build_library(verbose: bool = True, force: bool = True) -> str:
+    """force=False recompiles only sources older than their object (development); the default compiles all."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=4) as pool:
-        objs = list(pool.map(_compile, sources()))
+        objs = list(pool.map(lambda s: _compile(s, force), sources()))
     # no rpath to a particular ROCm: when torch is imported first its HIP runtime (same soname) is
     # already mapped and is the one this library binds to, so streams and pointers are shared.
     cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB_PATH]
@@ -61,15 +72,5 @@ def build_library(verbose: bool = True) -> str:
     return LIB_PATH
 
 
-def build_oracle_c() -> None:
-    """Compile whatever C the oracle holds (it holds none: the oracle is numpy)."""
-    odir = os.path.join(ROOT, "oracle")
-    for f in sorted(os.listdir(odir)):
-        if f.endswith(".c"):
-            out = os.path.join(odir, f[:-2] + ".so")
-            subprocess.run(["gcc", "-O2", "-shared", "-fPIC", os.path.join(odir, f), "-o", out, "-lm"], check=True)
-
-
 if __name__ == "__main__":
-    build_library()
-    build_oracle_c()
+    build_library(force="--changed" not in sys.argv)

@@ -30,6 +30,9 @@
 
 namespace {
 
+#ifndef CQ_STREAM_NT
+#define CQ_STREAM_NT 1
+#endif
 #ifndef CQ_SMALL_MAX_ROWS
 #define CQ_SMALL_MAX_ROWS 32
 #endif
@@ -87,6 +90,17 @@ __device__ __forceinline__ uint32_t code_to_bf16_bits(int c) { return __float_as
 // a table lookup can use the byte offset built by v_perm_b32 as the LDS address itself.
 __device__ __forceinline__ uint32_t lds_read_u32(uint32_t byte_offset) {
   return *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>((uintptr_t)byte_offset);
+}
+
+// 16 bytes of the packed-index stream: read once, never reused, so the load carries the non-temporal hint
+// (the bytes do not displace the activations, tables and partial sums that do get reused from the caches)
+__device__ __forceinline__ uint4 load_stream(const uint8_t* p) {
+#if CQ_STREAM_NT
+  const cq_v4u v = __builtin_nontemporal_load(reinterpret_cast<const cq_v4u*>(p));
+  return make_uint4(v[0], v[1], v[2], v[3]);
+#else
+  return *reinterpret_cast<const uint4*>(p);
+#endif
 }
 
 template <bool F16>
@@ -308,8 +322,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         for (int j = 0; j < kRing; ++j) {
           const int gs = wave + NW * j;
           const size_t off = (size_t)(gs < nS ? gs : 0) * sstride;
-          ring[j][0] = *reinterpret_cast<const uint4*>(wb + lane_off0 + off);
-          ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off1 + off);
+          ring[j][0] = load_stream(wb + lane_off0 + off);
+          ring[j][1] = load_stream(wb + lane_off1 + off);
         }
       }
       // single slab: the activations are staged here, behind the first ring requests, so that their
@@ -370,8 +384,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
               const int gn = wave + NW * (same ? qq : qq - Qpad);
               const uint8_t* base = same ? wb : wb_next;
               const size_t off = (gn < nS && (same || has_next)) ? (size_t)gn * sstride : 0;
-              ring[j][0] = *reinterpret_cast<const uint4*>(base + lane_off0 + off);
-              ring[j][1] = *reinterpret_cast<const uint4*>(base + lane_off1 + off);
+              ring[j][0] = load_stream(base + lane_off0 + off);
+              ring[j][1] = load_stream(base + lane_off1 + off);
             }
             if (gs < nS) {
               // chunk (8 k) index inside the slab of this lane's first fragment
@@ -501,8 +515,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         for (int j = 0; j < kRing; ++j) {
           const int gs = wave + NW * j;
           const size_t off = (size_t)(gs < nS ? gs : 0) * sstride;
-          ring[j][0] = *reinterpret_cast<const uint4*>(wb + lane_off0 + off);
-          ring[j][1] = *reinterpret_cast<const uint4*>(wb + lane_off1 + off);
+          ring[j][0] = load_stream(wb + lane_off0 + off);
+          ring[j][1] = load_stream(wb + lane_off1 + off);
         }
       }
       // single slab: the activations are staged here, behind the first ring requests, so that their
@@ -558,8 +572,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
               const int gn = wave + NW * (same ? qq : qq - Qpad);
               const uint8_t* base = same ? wb : wb_next;
               const size_t off = (gn < nS && (same || has_next)) ? (size_t)gn * sstride : 0;
-              ring[j][0] = *reinterpret_cast<const uint4*>(base + lane_off0 + off);
-              ring[j][1] = *reinterpret_cast<const uint4*>(base + lane_off1 + off);
+              ring[j][0] = load_stream(base + lane_off0 + off);
+              ring[j][1] = load_stream(base + lane_off1 + off);
             }
             if (gs < nS) {
               const int ls = gs - (q / qPerSlab) * (qPerSlab * NW);
