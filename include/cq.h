@@ -248,6 +248,20 @@ cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y,
                          void* workspace, size_t workspace_bytes, cq_stream stream);
 
 /*
+ * cq_moe_forward for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same launches and same results as
+ * cq_moe_forward, bit for bit; the intermediates live in an array of CQ_STATIC_SCRATCH_BYTES bytes that
+ * the library itself holds in the device memory of every GPU it has run on (until the process ends).  The
+ * call allocates and frees nothing and does not synchronise the host.
+ *   A batch whose cq_moe_workspace_bytes(L, T) exceeds CQ_STATIC_SCRATCH_BYTES returns CQ_ERR_WORKSPACE
+ *   and launches nothing (the Mixtral-8x7B shape fits up to T = 128 tokens).
+ *   All calls on one GPU share the array, which keeps the previous call's contents (no kernel of the layer
+ *   needs it cleared): calls that overlap on one GPU -- two streams, two threads -- race; serialise them.
+ */
+#define CQ_STATIC_SCRATCH_BYTES (32u << 20)
+cq_status cq_moe_forward_static(const cq_layer* L, const float* X, int T, float* Y, cq_stream stream);
+
+/*
  * Measurement variant of cq_moe_forward: same launches, with HIP events recorded on `stream` at the
  * stage boundaries.  It waits for the last event (so, unlike cq_moe_forward, it synchronises the
  * host) and writes the elapsed milliseconds of the CQ_N_STAGES stages to stage_ms (host memory):

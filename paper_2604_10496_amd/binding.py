@@ -23,7 +23,7 @@ EXPORTS = [
     "cq_status_string", "cq_rotate_quant_workspace_bytes", "cq_rotate_quant",
     "cq_route_permute_workspace_bytes", "cq_route_permute", "cq_grouped_gemm_workspace_bytes",
     "cq_codebook_grouped_gemm", "cq_combine", "cq_moe_workspace_bytes", "cq_moe_workspace_layout",
-    "cq_moe_forward", "cq_moe_forward_timed", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
+    "cq_moe_forward", "cq_moe_forward_static", "cq_moe_forward_timed", "cq_prepack_bytes", "cq_prepack", "cq_decode_dense", "cq_device_info",
     "cq_stream_read", "cq_mfma_loop", "cq_rotation_split_bytes", "cq_rotation_split",
     "cq_rotate_quant_split_workspace_bytes", "cq_rotate_quant_split", "cq_hadamard_quant",
     "cq_codebook_grouped_gemm_lut", "cq_expand_centroid_budget",
@@ -89,6 +89,8 @@ def load_library() -> ctypes.CDLL:
     lib.cq_moe_workspace_layout.argtypes = [ctypes.POINTER(Layer), ci, ctypes.POINTER(MoeLayout)]
     lib.cq_moe_forward.restype = ci
     lib.cq_moe_forward.argtypes = [ctypes.POINTER(Layer), vp, ci, vp, vp, sz, vp]
+    lib.cq_moe_forward_static.restype = ci
+    lib.cq_moe_forward_static.argtypes = [ctypes.POINTER(Layer), vp, ci, vp, vp]
     lib.cq_moe_forward_timed.restype = ci
     lib.cq_moe_forward_timed.argtypes = [ctypes.POINTER(Layer), vp, ci, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]
     lib.cq_rotation_split_bytes.restype = sz
@@ -397,6 +399,14 @@ def cq_moe_forward(layer: DeviceLayer, X, Y=None):
     ws = layer.workspace(T)
     s = layer.struct()
     _check(lib.cq_moe_forward(ctypes.byref(s), _ptr(X), T, _ptr(Y), _ptr(ws), ws.numel(), _stream()))
+    return Y
+
+
+def cq_moe_forward_static(layer: DeviceLayer, X, Y):
+    """cq_moe_forward on the library's own scratch array: no workspace, nothing allocated (Y is the caller's)."""
+    lib = load_library()
+    s = layer.struct()
+    _check(lib.cq_moe_forward_static(ctypes.byref(s), _ptr(X), X.shape[0], _ptr(Y), _stream()))
     return Y
 
 

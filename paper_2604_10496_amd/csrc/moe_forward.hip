@@ -1,8 +1,30 @@
 // The whole layer a1..a8 on one stream: rotate + quantize, route + permute, gate/up codebook product
 // with the SiLU-gated epilogue, down codebook product, weighted combine.  Host code only enqueues.
+#include <atomic>
+
 #include "cq_internal.h"
 
 namespace {
+
+// Workspace of cq_moe_forward_static: one array per GPU in the library's own device memory, so that the
+// call needs no allocation by anybody.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and launchers get the address that call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[CQ_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// device address of `scratch` on the current device (looked up once per device, then cached)
+cq_status static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CQ_ERR_HIP;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CQ_ERR_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // racing threads store the same address
+  }
+  *out = p;
+  return CQ_OK;
+}
 
 cq_status validate_layer(const cq_layer* L, int T) {
   if (!L) return CQ_ERR_NULL;
@@ -208,6 +230,19 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
 extern "C" cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y, void* workspace,
                                     size_t workspace_bytes, cq_stream stream) {
   return run_layer(L, X, T, Y, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" cq_status cq_moe_forward_static(const cq_layer* L, const float* X, int T, float* Y, cq_stream stream) {
+  cq_status st = validate_layer(L, T);
+  if (st != CQ_OK) return st;
+  if (!X || !Y) return CQ_ERR_NULL;
+  cq_moe_layout lay;
+  make_layout(L, T, &lay);
+  if (lay.total > (size_t)CQ_STATIC_SCRATCH_BYTES) return CQ_ERR_WORKSPACE;  // batch too large for the array
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != CQ_OK) return st;
+  return run_layer(L, X, T, Y, ws, (size_t)CQ_STATIC_SCRATCH_BYTES, stream, nullptr);
 }
 
 extern "C" cq_status cq_moe_forward_timed(const cq_layer* L, const float* X, int T, float* Y, void* workspace,

@@ -82,6 +82,12 @@ def test_argument_validation_happens_before_any_device_call():
     L = B.Layer(128, 128, 4, 2, 0, 8, 256, 256, None, gu, dn)
     assert lib.cq_moe_workspace_bytes(ctypes.byref(L), 16) > 0
     assert lib.cq_moe_forward(ctypes.byref(L), one, 16, one, None, 0, None) == 4
+    # the entry point with the library's own scratch array: same validation, and a batch beyond the array's
+    # size is refused before any device call
+    assert lib.cq_moe_forward_static(ctypes.byref(L), None, 16, one, None) == 1
+    assert lib.cq_moe_forward_static(ctypes.byref(L), one, 0, one, None) == 2
+    assert lib.cq_moe_workspace_bytes(ctypes.byref(L), 1 << 16) > (32 << 20)
+    assert lib.cq_moe_forward_static(ctypes.byref(L), one, 1 << 16, one, None) == 4
     Lbad = B.Layer(128, 128, 4, 2, 0, 6, 256, 256, None, gu, dn)
     assert lib.cq_moe_forward(ctypes.byref(Lbad), one, 16, one, one, 1 << 30, None) == 3
     Lbad2 = B.Layer(128, 128, 4, 5, 0, 8, 256, 256, None, gu, dn)

@@ -1,0 +1,77 @@
+"""cq_moe_forward_static (the entry point that allocates nothing: its workspace is an array inside the
+library's own device memory) against cq_moe_forward on the same inputs, through the C ABI.
+
+The two calls issue the same launches, so their outputs must be equal bit for bit, which is tighter than the
+2e-3 per-row bar the layer is held to against the oracle (checked here as well).  Two calls in a row share the
+array: the second runs a smaller batch over whatever the first one left there."""
+import numpy as np
+import pytest
+
+from paper_2604_10496_amd import synth
+from tests import helpers as Hp
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2604_10496_amd import binding
+    binding.load_library()
+    return binding
+
+
+@pytest.mark.parametrize("name,over,T2", [
+    ("tiny", dict(), 17),
+    # a K-split down projection (I / 64 > 64 steps), the rotation's partial sums, decode-sized front end
+    ("mixtral_decode", dict(H=512, I=4352, T=16), 5),
+    # shared experts, the large-tile product and its tile lists in the scratch area
+    ("dsv2lite", dict(H=256, I=256, T=100, E=16), 33),
+])
+def test_static_scratch_entry_point_matches_workspace_entry_point(B, name, over, T2):
+    import torch
+    cfg = synth.small_variant(synth.CONFIGS[name], **over) if over else synth.CONFIGS[name]
+    L = Hp.make_inputs(cfg)
+    layer = B.device_layer_from_inputs(L)
+    X = torch.from_numpy(L.X).to("cuda")
+    print(f"static scratch: {name} T={cfg.T} then T={T2}", flush=True)
+
+    want = B.cq_moe_forward(layer, X).cpu().numpy()
+    Y = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device="cuda")
+    B.cq_moe_forward_static(layer, X, Y)
+    torch.cuda.synchronize()
+    got = Y.cpu().numpy()
+    assert np.array_equal(got, want)
+    ref = Hp.oracle_forward(L)
+    q_gpu = B.moe_intermediates(layer, cfg.T)["Q"].cpu().numpy()
+    clean = np.array([t for t in range(cfg.T) if np.array_equal(q_gpu[t], ref["q"][t])])   # rows without a tie code
+    assert clean.size >= cfg.T - 2
+    assert Hp.row_rel_l2(got[clean], ref["Y"][clean]).max() <= OUT_TOL
+
+    # second call, smaller batch, same array (it still holds the first call's intermediates)
+    X2 = X[:T2].contiguous()
+    want2 = B.cq_moe_forward(layer, X2).cpu().numpy()
+    Y2 = torch.full((T2, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
+    B.cq_moe_forward_static(layer, X2, Y2)
+    torch.cuda.synchronize()
+    assert np.array_equal(Y2.cpu().numpy(), want2)
+    # and the first batch again: nothing of the smaller run lingers
+    B.cq_moe_forward_static(layer, X, Y)
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), want)
+
+
+def test_static_scratch_refuses_a_batch_that_does_not_fit(B):
+    import torch
+    cfg = synth.small_variant(synth.CONFIGS["mixtral_decode"], H=512, I=1024, T=16)
+    L = synth.make_layer(cfg)
+    layer = B.device_layer_from_inputs(L)
+    T = 1 << 16   # 64 Ki tokens of this shape need far more than the array holds
+    X = torch.zeros((T, cfg.H), dtype=torch.float32, device="cuda")
+    Y = torch.zeros((T, cfg.H), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.CqError) as e:
+        B.cq_moe_forward_static(layer, X, Y)
+    assert e.value.status == 4   # CQ_ERR_WORKSPACE
