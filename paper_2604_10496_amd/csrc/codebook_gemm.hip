@@ -47,6 +47,10 @@ constexpr int kRedBytes = 32768;     // K partials of up to 16 token columns: 8 
 constexpr int kWaves = CQ_GEMM_WAVES;  // wavefronts per workgroup: they split K (step s -> wavefront s % kWaves)
 // K steps a wavefront keeps in flight: 4 (64 KiB per CU) or, when its step count is a multiple of 8,
 // 8 (the per-unit phases in which nothing is consumed then find more data already on its way)
+#ifndef CQ_PIPE_RING
+#define CQ_PIPE_RING 8
+#endif
+constexpr int kPipeRing = CQ_PIPE_RING;  // ring depth (K steps in flight per wavefront) of the pipelined unit loop
 constexpr int kSlabCheck = 16 / kWaves;  // smallest number of wavefront steps in a slab (Mpad = 32)
 
 struct GemmArgs {
@@ -86,6 +90,57 @@ __device__ __forceinline__ uint32_t bf16_bits_to_f16_bits(uint32_t b) {
 // integer code -> bf16 bits: a float holding a small integer has zero low mantissa bits.
 __device__ __forceinline__ uint32_t code_to_bf16_bits(int c) { return __float_as_uint((float)c) >> 16; }
 
+// Eight consecutive activations of one row, as loaded (raw) and as four dwords of 16-bit MFMA operand pairs:
+// bf16 for integer codes and bf16 rows, f16 for f16 / f32 rows.  grouped: paired like the prepacked index
+// bytes pair the weights, (k0 k4 | k1 k5 | k2 k6 | k3 k7), instead of (k0 k1 | k2 k3 | k4 k5 | k6 k7).
+struct ActRaw { uint4 a, b; };
+
+template <int AK>
+__device__ __forceinline__ ActRaw act_load8(const void* A, size_t e0) {
+  ActRaw r;
+  r.b = make_uint4(0u, 0u, 0u, 0u);
+  if constexpr (AK == CQ_A_INT8_CODES) {
+    const uint2 v = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(A) + e0);
+    r.a = make_uint4(v.x, v.y, 0u, 0u);
+  } else if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
+    r.a = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(A) + e0);
+  } else {
+    r.a = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(A) + e0);
+    r.b = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(A) + e0 + 4);
+  }
+  return r;
+}
+
+template <int AK>
+__device__ __forceinline__ uint4 act_pack8(const ActRaw& r, bool grouped) {
+  if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
+    const uint4 v = r.a;
+    if (!grouped) return v;
+    return make_uint4(__builtin_amdgcn_perm(v.z, v.x, 0x05040100u), __builtin_amdgcn_perm(v.z, v.x, 0x07060302u),
+                      __builtin_amdgcn_perm(v.w, v.y, 0x05040100u), __builtin_amdgcn_perm(v.w, v.y, 0x07060302u));
+  } else {
+    uint32_t c8[8];
+    if constexpr (AK == CQ_A_INT8_CODES) {
+      const uint32_t rw[2] = {r.a.x, r.a.y};
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        c8[4 * h] = code_to_bf16_bits((int)(int8_t)(rw[h] & 0xff));
+        c8[4 * h + 1] = code_to_bf16_bits((int)(int8_t)((rw[h] >> 8) & 0xff));
+        c8[4 * h + 2] = code_to_bf16_bits((int)(int8_t)((rw[h] >> 16) & 0xff));
+        c8[4 * h + 3] = code_to_bf16_bits((int)(int8_t)(rw[h] >> 24));
+      }
+    } else {
+      const uint32_t f[8] = {r.a.x, r.a.y, r.a.z, r.a.w, r.b.x, r.b.y, r.b.z, r.b.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) c8[i] = f32_to_f16_bits_sat(__uint_as_float(f[i]));
+    }
+    return grouped ? make_uint4(c8[0] | (c8[4] << 16), c8[1] | (c8[5] << 16), c8[2] | (c8[6] << 16),
+                                c8[3] | (c8[7] << 16))
+                   : make_uint4(c8[0] | (c8[1] << 16), c8[2] | (c8[3] << 16), c8[4] | (c8[5] << 16),
+                                c8[6] | (c8[7] << 16));
+  }
+}
+
 // The pair table sits at LDS address 0 (the kernel has no static LDS, which the launcher verifies), so
 // a table lookup can use the byte offset built by v_perm_b32 as the LDS address itself.
 __device__ __forceinline__ uint32_t lds_read_u32(uint32_t byte_offset) {
@@ -116,7 +171,9 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
 }
 
 
-template <int AK, int EPI, int OUTK, int kRing>
+// QS > 0: a workgroup whose token block has at most 8 rows and whose wavefronts have exactly QS K steps per unit
+// runs the pipelined unit loop (run_units_pipe below); 0: that path is left out of the instantiation.
+template <int AK, int EPI, int OUTK, int kRing, int QS>
 __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmArgs p) {
   constexpr bool F16 = (AK == CQ_A_F16 || AK == CQ_A_F32);
   constexpr int NW = kWaves;
@@ -128,7 +185,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   uint4* slab = reinterpret_cast<uint4*>(lds + kTableBytes);
   float* redc = reinterpret_cast<float*>(lds + kTableBytes + kSlabBytes);  // kRedBytes: partials of <= 16 tokens
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: what depends on it stays scalar
   const int N = p.N, K = p.K;
   const int nUnits = N >> 6;
   int grp, u0, upw;
@@ -175,6 +233,244 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   const uint32_t lanebase1 = (uint32_t)((32 + r32) * 4);
   const int n_tb = (Me + 31) >> 5;
 
+  // ---- up to 8 tokens, K range of QS steps per wavefront: the unit loop as a pipeline ----
+  // With few tokens the activations of a wavefront's own K steps fit in registers (QS x 2 fragments: its K
+  // steps are the same in every unit), so no slab is needed and LDS holds TWO pair tables and two buffers of
+  // K partials.  While unit u is looked up in one table, the table of unit u+1 is written into the other,
+  // a few entries per K step, and the partial sums of unit u-1 are added up, scaled, passed through the
+  // epilogue and stored: one workgroup barrier per unit, and nothing but that barrier between two units' K
+  // loops.  Hazards: table (u+1)%2 was last read in unit u-1, partial buffer u%2 last read (for unit u-2)
+  // in unit u-1 -- both before the barrier that ends unit u-1.
+  // Ring slot q % RD serves K step q and is refilled with step q + RD (of this unit, or of the next one) as
+  // soon as step q's lookups are issued.
+  auto run_units_pipe = [&]() {
+    constexpr int Q = QS > 0 ? QS : 1;
+    constexpr int RD = kPipeRing < Q ? kPipeRing : Q;
+    constexpr int TB0 = Q / 2;            // the next unit's table is written during steps TB0 .. Q-1
+    const int i16 = lane & 15, g4 = lane >> 4;
+    const bool tok = (i16 & 7) < Me;      // this lane holds activations of a real token
+    const bool grouped = p.prepacked != 0;
+    float sc16 = 1.f;
+    size_t arow = 0;
+    if (tok) {
+      const int m = m0 + (i16 & 7);
+      const size_t src = p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
+      arow = src * K;
+      if (p.row_scale) sc16 = p.row_scale[src];
+    }
+    constexpr uint32_t kRed = 2 * kTableBytes;   // partial buffers: [2][wave][16 registers][32 columns] floats
+    const uint32_t slot = (uint32_t)(g4 * 8 + (i16 & 7));
+    // ring loads: uniform base (unit, K step, row block) + 32-bit lane offset
+    const uint32_t loff = p.prepacked ? (uint32_t)lane * 16u : (uint32_t)r32 * (uint32_t)rowbytes + (uint32_t)g2 * 16u;
+    const size_t rb1 = 32 * rowbytes;            // the unit's second block of 32 rows
+    const uint8_t* const kbase = gbase + (size_t)sb * sstride;
+
+    // centroid rows of a unit (raw bf16 pairs; ch: the two entries this wavefront uses as high halves)
+    uint32_t cp[8], chp;
+    auto cent_req = [&](int u) {
+      const uint16_t* crow = p.cent + ((size_t)grp * N + (size_t)u * 64 + lane) * CQ_N_CENTROIDS;
+      const uint4 a = reinterpret_cast<const uint4*>(crow)[0];
+      const uint4 b = reinterpret_cast<const uint4*>(crow)[1];
+      cp[0] = a.x; cp[1] = a.y; cp[2] = a.z; cp[3] = a.w; cp[4] = b.x; cp[5] = b.y; cp[6] = b.z; cp[7] = b.w;
+      chp = *reinterpret_cast<const uint32_t*>(crow + 2 * wave);
+    };
+    auto cent_f16 = [&]() {
+      if constexpr (F16) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          cp[i] = bf16_bits_to_f16_bits(cp[i] & 0xffffu) | (bf16_bits_to_f16_bits(cp[i] >> 16) << 16);
+        chp = bf16_bits_to_f16_bits(chp & 0xffffu) | (bf16_bits_to_f16_bits(chp >> 16) << 16);
+      }
+    };
+    // entries [e0, e1) of this wavefront's 32 (entry e: high half = its centroid 2*wave + e/16, low half = e%16)
+    auto table_part = [&](const uint32_t tbase, const int e0, const int e1) {
+#pragma unroll
+      for (int e = e0; e < e1; ++e) {
+        const int i = e >> 4, l = e & 15;
+        const uint32_t sel = ((l & 1) ? 0x0302u : 0x0100u) | ((i ? 0x0706u : 0x0504u) << 16);
+        const uint32_t v = __builtin_amdgcn_perm(chp, cp[l >> 1], sel);
+        *reinterpret_cast<__attribute__((address_space(3))) uint32_t*>((uintptr_t)(tbase + (uint32_t)(e * 256))) = v;
+      }
+    };
+    typedef __attribute__((ext_vector_type(2))) unsigned pair_u32;
+
+    // -- prologue: centroid rows, activations of this wavefront's K steps, the ring, the first table
+    cent_req(u0);
+    // B fragments of step q: both K halves in ONE register set -- lanes of columns 0..7 hold the first half's
+    // fragment of their token, lanes of columns 8..15 the second half's fragment of token column - 8 (the
+    // matrix cores' output columns 8..15 are never stored, so what their B columns hold does not matter);
+    // a rotation by 8 inside each row of 16 lanes brings the second half into place.
+    cq_v4u breg[Q];
+    uint4 ring[RD][2];
+    {
+      ActRaw raw[Q];
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        const int gs = wave + NW * q;
+        const int chunk = (gs < nS ? gs : 0) * 8 + (g4 & 1) + 4 * (g4 >> 1) + 2 * (i16 >> 3);
+        raw[q] = act_load8<AK>(p.A, arow + (size_t)sb * 64 + (size_t)chunk * 8);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const uint8_t* wb = kbase + (size_t)u0 * 64 * rowbytes;
+#pragma unroll
+        for (int j = 0; j < RD; ++j) {
+          const int gs = wave + NW * j;
+          const uint8_t* sp = wb + (size_t)(gs < nS ? gs : 0) * sstride;
+          ring[j][0] = load_stream(sp + loff);
+          ring[j][1] = load_stream(sp + rb1 + loff);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        const uint4 v = tok ? act_pack8<AK>(raw[q], grouped) : make_uint4(0u, 0u, 0u, 0u);
+        breg[q] = cq_v4u{v.x, v.y, v.z, v.w};
+      }
+    }
+    cent_f16();
+    table_part((uint32_t)(wave * 8192 + lane * 4), 0, 32);
+    __syncthreads();
+
+    // finish of a unit: this wavefront adds up accumulator registers 2*wave and 2*wave+1 (a gate/up pair of
+    // rows) of all wavefronts' partials in buffer pb, in wavefront order
+    auto finish = [&](const int uu, const uint32_t pb) {
+      if (i16 < 8) {
+        const uint32_t rb0 = kRed + pb * 16384u + (uint32_t)(2 * wave) * 128u + slot * 4u;
+        float val[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          float sum = __uint_as_float(lds_read_u32(rb0 + (uint32_t)(i * 128)));
+#pragma unroll
+          for (int w = 1; w < NW; ++w) sum += __uint_as_float(lds_read_u32(rb0 + (uint32_t)(w * 2048 + i * 128)));
+          val[i] = sum;
+        }
+        if (tok) {
+          const int m = m0 + i16;
+          const int r = 2 * wave;
+          const int row = uu * 64 + (r >> 3) * 32 + ((r >> 2) & 1) * 16 + g4 * 4 + (r & 3);
+          const float x0 = sc16 * val[0], x1 = sc16 * val[1];
+          if (p.ksplit > 1) {  // partial sum of this K range (CQ_EPI_NONE only)
+            float* dst = p.partials + (size_t)blockIdx.z * p.part_stride + (size_t)m * N + row;
+            *reinterpret_cast<float2*>(dst) = make_float2(x0, x1);
+          } else if constexpr (EPI == CQ_EPI_SWIGLU) {
+            const float h0 = x0 / (1.f + __expf(-x0)) * x1;
+            const size_t o = (size_t)m * p.out_ld + (row >> 1);
+            if constexpr (OUTK == CQ_OUT_F16)
+              reinterpret_cast<uint16_t*>(p.out)[o] = (uint16_t)f32_to_f16_bits_sat(h0);
+            else
+              reinterpret_cast<float*>(p.out)[o] = h0;
+          } else {
+            const size_t o = (size_t)m * p.out_ld + row;
+            if constexpr (OUTK == CQ_OUT_F16)
+              *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(p.out) + o) =
+                  f32_to_f16_bits_sat(x0) | (f32_to_f16_bits_sat(x1) << 16);
+            else
+              *reinterpret_cast<float2*>(reinterpret_cast<float*>(p.out) + o) = make_float2(x0, x1);
+          }
+        }
+      }
+    };
+
+    uint32_t par = 0;   // table and partial buffer of the current unit
+    for (int u = u0; u < u1; ++u) {
+      const uint8_t* wb = kbase + (size_t)u * 64 * rowbytes;
+      const bool has_next = u + 1 < u1;
+      const uint8_t* wb_next = has_next ? wb + 64 * rowbytes : wb;
+      // the next unit's centroid rows, requested ahead of this unit's ring refills and used from step TB0 on
+      cent_req(has_next ? u + 1 : u);
+      __builtin_amdgcn_sched_barrier(0);
+      const uint32_t lbase[2] = {lanebase0 | (par << 16), lanebase1 | (par << 16)};
+      const uint32_t tnext = ((par ^ 1u) << 16) + (uint32_t)(wave * 8192 + lane * 4);
+
+      cq_v4f acc[2][2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) acc[rb][h] = cq_v4f{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        const int gs = wave + NW * q;
+        constexpr int dummy = 0; (void)dummy;
+        const int sl = q % RD;
+        if (gs < nS) {
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            cq_v4u bv = breg[q];
+            if (c == 1) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i)   // row_ror:8 -- lane l of a row of 16 takes lane (l + 8) % 16
+                bv[i] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bv[i], 0x128, 0xf, 0xf, false);
+            }
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+              const uint4 w = ring[sl][rb];
+              const uint32_t wd[4] = {w.x, w.y, w.z, w.w};
+              cq_v4u a0, a1;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                // pair index byte -> table entry, row slot -> bank, byte 2 of the lane base -> table
+                const uint32_t ox = __builtin_amdgcn_perm(wd[2 * c], lbase[rb], 0x0c020400u + (i << 8));
+                const uint32_t oy = __builtin_amdgcn_perm(wd[2 * c + 1], lbase[rb], 0x0c020400u + (i << 8));
+                const uint32_t x = lds_read_u32(ox);
+                const uint32_t y = lds_read_u32(oy);
+                const pair_u32 sw = __builtin_amdgcn_permlane16_swap(x, y, false, false);
+                a0[i] = sw[0];
+                a1[i] = sw[1];
+              }
+              if constexpr (F16) {
+                acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                    __builtin_bit_cast(cq_v8f16, a0), __builtin_bit_cast(cq_v8f16, bv), acc[rb][0], 0, 0, 0);
+                acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                    __builtin_bit_cast(cq_v8f16, a1), __builtin_bit_cast(cq_v8f16, bv), acc[rb][1], 0, 0, 0);
+              } else {
+                acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    __builtin_bit_cast(cq_v8bf16, a0), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][0], 0, 0, 0);
+                acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    __builtin_bit_cast(cq_v8bf16, a1), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][1], 0, 0, 0);
+              }
+            }
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);  // the refill must stay behind the last use of the slot
+        {
+          const int qn = q + RD;             // the step that reuses this slot
+          const bool same = qn < Q;
+          const int gn = wave + NW * (same ? qn : qn - Q);
+          const uint8_t* sp = (same ? wb : wb_next) + ((gn < nS && (same || has_next)) ? (size_t)gn * sstride : 0);
+          ring[sl][0] = load_stream(sp + loff);
+          ring[sl][1] = load_stream(sp + rb1 + loff);
+        }
+        // the previous unit's results (once), and this step's share of the next unit's table
+        if (q == 0 && u > u0) finish(u - 1, par ^ 1u);
+        if (q == TB0) cent_f16();
+        if (q >= TB0) table_part(tnext, ((q - TB0) * 32) / (Q - TB0), ((q - TB0 + 1) * 32) / (Q - TB0));
+      }
+      // this unit's K partials: register r = rb*8 + h*4 + v of wavefront w at [par][w][r][column]
+      if (i16 < 8) {
+        const uint32_t wbase = kRed + par * 16384u + (uint32_t)wave * 2048u + slot * 4u;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              *reinterpret_cast<__attribute__((address_space(3))) float*>(
+                  (uintptr_t)(wbase + (uint32_t)((rb * 8 + h * 4 + v) * 128))) = acc[rb][h][v];
+      }
+      __syncthreads();
+      par ^= 1u;
+    }
+    finish(u1 - 1, par ^ 1u);
+  };
+  if constexpr (QS > 0) {
+    if (Me <= 8 && Qmax == QS) {
+      run_units_pipe();
+      return;
+    }
+  }
+
   for (int tb = 0; tb < n_tb; ++tb) {
     const int Mb = min(32, Me - 32 * tb);
     const int Mpad = Mb <= 8 ? 8 : Mb <= 16 ? 16 : 32;     // divides the workgroup: a thread stages one token
@@ -203,61 +499,14 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
       const size_t ebase = srow + (size_t)sb * 64 + k0;
       constexpr int kBatch = 4;
       for (int c = sc0; c < nC; c += kBatch * cstep) {
-        uint4 raw[kBatch], raw2[kBatch];
+        ActRaw raw[kBatch];
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
-          const size_t e0 = ebase + (size_t)min(c + i * cstep, nC - 1) * 8;
-          if constexpr (AK == CQ_A_INT8_CODES) {
-            const uint2 r = *reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(p.A) + e0);
-            raw[i] = make_uint4(r.x, r.y, 0u, 0u);
-          } else if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
-            raw[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.A) + e0);
-          } else {
-            raw[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.A) + e0);
-            raw2[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.A) + e0 + 4);
-          }
-        }
+        for (int i = 0; i < kBatch; ++i) raw[i] = act_load8<AK>(p.A, ebase + (size_t)min(c + i * cstep, nC - 1) * 8);
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
           const int ci = c + i * cstep;
           if (ci >= nC) break;
-          uint4 v = make_uint4(0u, 0u, 0u, 0u);
-          if (svalid) {
-            // The prepacked bytes pair weight i with weight i+4 of every 8, and so does a looked-up pair: the
-            // 8 activations of a chunk are then paired the same way (k0 k4 | k1 k5 | k2 k6 | k3 k7) instead
-            // of (k0 k1 | k2 k3 | k4 k5 | k6 k7).
-            if constexpr (AK == CQ_A_INT8_CODES) {
-              const uint32_t rw[2] = {raw[i].x, raw[i].y};
-              uint32_t c8[8];
-#pragma unroll
-              for (int h = 0; h < 2; ++h) {
-                c8[4 * h] = code_to_bf16_bits((int)(int8_t)(rw[h] & 0xff));
-                c8[4 * h + 1] = code_to_bf16_bits((int)(int8_t)((rw[h] >> 8) & 0xff));
-                c8[4 * h + 2] = code_to_bf16_bits((int)(int8_t)((rw[h] >> 16) & 0xff));
-                c8[4 * h + 3] = code_to_bf16_bits((int)(int8_t)(rw[h] >> 24));
-              }
-              v = grouped ? make_uint4(c8[0] | (c8[4] << 16), c8[1] | (c8[5] << 16), c8[2] | (c8[6] << 16),
-                                       c8[3] | (c8[7] << 16))
-                          : make_uint4(c8[0] | (c8[1] << 16), c8[2] | (c8[3] << 16), c8[4] | (c8[5] << 16),
-                                       c8[6] | (c8[7] << 16));
-            } else if constexpr (AK == CQ_A_F16 || AK == CQ_A_BF16) {
-              v = raw[i];
-              if (grouped)
-                v = make_uint4(__builtin_amdgcn_perm(v.z, v.x, 0x05040100u), __builtin_amdgcn_perm(v.z, v.x, 0x07060302u),
-                               __builtin_amdgcn_perm(v.w, v.y, 0x05040100u), __builtin_amdgcn_perm(v.w, v.y, 0x07060302u));
-            } else {
-              const uint4 f0 = raw[i], f1 = raw2[i];
-              const uint32_t c8[8] = {f32_to_f16_bits_sat(__uint_as_float(f0.x)), f32_to_f16_bits_sat(__uint_as_float(f0.y)),
-                                      f32_to_f16_bits_sat(__uint_as_float(f0.z)), f32_to_f16_bits_sat(__uint_as_float(f0.w)),
-                                      f32_to_f16_bits_sat(__uint_as_float(f1.x)), f32_to_f16_bits_sat(__uint_as_float(f1.y)),
-                                      f32_to_f16_bits_sat(__uint_as_float(f1.z)), f32_to_f16_bits_sat(__uint_as_float(f1.w))};
-              v = grouped ? make_uint4(c8[0] | (c8[4] << 16), c8[1] | (c8[5] << 16), c8[2] | (c8[6] << 16),
-                                       c8[3] | (c8[7] << 16))
-                          : make_uint4(c8[0] | (c8[1] << 16), c8[2] | (c8[3] << 16), c8[4] | (c8[5] << 16),
-                                       c8[6] | (c8[7] << 16));
-            }
-          }
-          slab[ci * Mpad + st] = v;
+          slab[ci * Mpad + st] = svalid ? act_pack8<AK>(raw[i], grouped) : make_uint4(0u, 0u, 0u, 0u);
         }
       }
     };
@@ -669,6 +918,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         }
       }
     };
+
     if (multi) {
       if (sep) run_units16(std::true_type{});
       else run_units(std::true_type{});
@@ -680,9 +930,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   }
 }
 
-template <int AK, int EPI, int OUTK, int RING>
+template <int AK, int EPI, int OUTK, int RING, int QS>
 cq_status launch_small_ring(const GemmArgs& a, int G, hipStream_t s) {
-  auto kern = gemm_small_kernel<AK, EPI, OUTK, RING>;
+  auto kern = gemm_small_kernel<AK, EPI, OUTK, RING, QS>;
   static bool configured = false;
   if (!configured) {
     hipFuncAttributes fa;
@@ -703,7 +953,10 @@ cq_status launch_small_ring(const GemmArgs& a, int G, hipStream_t s) {
 template <int AK, int EPI, int OUTK>
 cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
   const int per_wave = (a.ksteps + kWaves - 1) / kWaves;  // steps of a wavefront in the (first) K range
-  return per_wave % 8 == 0 ? launch_small_ring<AK, EPI, OUTK, 8>(a, G, s) : launch_small_ring<AK, EPI, OUTK, 4>(a, G, s);
+  if (kWaves == 8 && per_wave == 8) return launch_small_ring<AK, EPI, OUTK, 8, 8>(a, G, s);
+  if (kWaves == 8 && per_wave == 7) return launch_small_ring<AK, EPI, OUTK, 4, 7>(a, G, s);
+  return per_wave % 8 == 0 ? launch_small_ring<AK, EPI, OUTK, 8, 0>(a, G, s)
+                           : launch_small_ring<AK, EPI, OUTK, 4, 0>(a, G, s);
 }
 
 // out[m, :] = sum over the K splits of partials[s][m, :] in the order s = 0, 1, ... for the rows of the
@@ -851,8 +1104,12 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   switch (a_kind) {
     case CQ_A_INT8_CODES: st = dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s); break;
     case CQ_A_F16: st = dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s); break;
+#ifndef CQ_DEV_FAST
     case CQ_A_BF16: st = dispatch_epi<CQ_A_BF16>(a, W->G, epilogue, out_kind, s); break;
     default: st = dispatch_epi<CQ_A_F32>(a, W->G, epilogue, out_kind, s); break;
+#else
+    default: return CQ_ERR_UNSUPPORTED;
+#endif
   }
   if (st != CQ_OK) return st;
   if (a.ksplit > 1) {
