@@ -47,10 +47,19 @@ constexpr int kRedBytes = 32768;     // K partials of up to 16 token columns: 8 
 constexpr int kWaves = CQ_GEMM_WAVES;  // wavefronts per workgroup: they split K (step s -> wavefront s % kWaves)
 // K steps a wavefront keeps in flight: 4 (64 KiB per CU) or, when its step count is a multiple of 8,
 // 8 (the per-unit phases in which nothing is consumed then find more data already on its way)
-#ifndef CQ_PIPE_RING
-#define CQ_PIPE_RING 8
+// Ring depth of the pipelined unit loop in HALF steps (one 16-byte load per lane: 32 rows x 64 k) for a
+// wavefront with Q steps per unit.  It must divide 2Q so that a slot always meets the same half step of
+// every unit: 8 for even Q (4 steps = 64 KiB in flight per compute unit; 16 was measured 5 % slower), Q for
+// odd Q.
+#ifndef CQ_PIPE_HD_EVEN
+#define CQ_PIPE_HD_EVEN 8
 #endif
-constexpr int kPipeRing = CQ_PIPE_RING;  // ring depth (K steps in flight per wavefront) of the pipelined unit loop
+#ifndef CQ_PIPE_HD_ODD
+#define CQ_PIPE_HD_ODD 1
+#endif
+constexpr int pipe_ring_depth(int Q) {
+  return (2 * Q) % CQ_PIPE_HD_EVEN == 0 ? CQ_PIPE_HD_EVEN : (Q % 2 ? CQ_PIPE_HD_ODD * Q : 2);
+}
 constexpr int kSlabCheck = 16 / kWaves;  // smallest number of wavefront steps in a slab (Mpad = 32)
 
 struct GemmArgs {
@@ -233,39 +242,38 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   const uint32_t lanebase1 = (uint32_t)((32 + r32) * 4);
   const int n_tb = (Me + 31) >> 5;
 
-  // ---- up to 8 tokens, K range of QS steps per wavefront: the unit loop as a pipeline ----
-  // With few tokens the activations of a wavefront's own K steps fit in registers (QS x 2 fragments: its K
-  // steps are the same in every unit), so no slab is needed and LDS holds TWO pair tables and two buffers of
-  // K partials.  While unit u is looked up in one table, the table of unit u+1 is written into the other,
-  // a few entries per K step, and the partial sums of unit u-1 are added up, scaled, passed through the
-  // epilogue and stored: one workgroup barrier per unit, and nothing but that barrier between two units' K
-  // loops.  Hazards: table (u+1)%2 was last read in unit u-1, partial buffer u%2 last read (for unit u-2)
-  // in unit u-1 -- both before the barrier that ends unit u-1.
-  // Ring slot q % RD serves K step q and is refilled with step q + RD (of this unit, or of the next one) as
-  // soon as step q's lookups are issued.
+  // ---- up to 8 tokens, K range of exactly QS steps per wavefront: the unit loop as a pipeline ----
+  // With few tokens the activations of a wavefront's own K steps fit in registers (its K steps are the same
+  // in every unit), so no slab is needed and LDS holds TWO pair tables and two buffers of K partials.  While
+  // unit u is looked up in one table, the table of unit u+1 is written into the other, a few entries per K
+  // step, and the partial sums of unit u-1 are added up, scaled, passed through the epilogue and stored: one
+  // workgroup barrier per unit, and nothing but that barrier between two units' K loops.  Hazards: table
+  // (u+1)%2 was last read in unit u-1, partial buffer u%2 last read (for unit u-2) in unit u-1 -- both
+  // before the barrier that ends unit u-1.
+  // Ring slot hs % HD serves half step hs = 2q + row block (one 16-byte load per lane) and is refilled with
+  // half step hs + HD, of this unit or of the next one, as soon as step q's lookups are issued.
   auto run_units_pipe = [&]() {
     constexpr int Q = QS > 0 ? QS : 1;
-    constexpr int RD = kPipeRing < Q ? kPipeRing : Q;
+    constexpr int HD = pipe_ring_depth(Q);
     constexpr int TB0 = Q / 2;            // the next unit's table is written during steps TB0 .. Q-1
     const int i16 = lane & 15, g4 = lane >> 4;
     const bool tok = (i16 & 7) < Me;      // this lane holds activations of a real token
     const bool grouped = p.prepacked != 0;
-    float sc16 = 1.f;
-    size_t arow = 0;
-    if (tok) {
-      const int m = m0 + (i16 & 7);
-      const size_t src = p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
-      arow = src * K;
-      if (p.row_scale) sc16 = p.row_scale[src];
-    }
     constexpr uint32_t kRed = 2 * kTableBytes;   // partial buffers: [2][wave][16 registers][32 columns] floats
     const uint32_t slot = (uint32_t)(g4 * 8 + (i16 & 7));
     // ring loads: uniform base (unit, K step, row block) + 32-bit lane offset
     const uint32_t loff = p.prepacked ? (uint32_t)lane * 16u : (uint32_t)r32 * (uint32_t)rowbytes + (uint32_t)g2 * 16u;
     const size_t rb1 = 32 * rowbytes;            // the unit's second block of 32 rows
     const uint8_t* const kbase = gbase + (size_t)sb * sstride;
+    const size_t ubytes = 64 * rowbytes;         // index bytes of one unit
+    // units of this workgroup: its index among the group's workgroups + i * (workgroups of the group), so
+    // that the workgroups of a group read one contiguous window of the index stream at any time (measured
+    // 1-2 % faster than a contiguous run of units per workgroup)
+    const int ustep = (nUnits + upw - 1) / upw;
+    const int ufirst = u0 / upw;
+    const int ucnt = (nUnits - ufirst + ustep - 1) / ustep;
 
-    // centroid rows of a unit (raw bf16 pairs; ch: the two entries this wavefront uses as high halves)
+    // centroid rows of a unit (raw bf16 pairs; chp: the two entries this wavefront uses as high halves)
     uint32_t cp[8], chp;
     auto cent_req = [&](int u) {
       const uint16_t* crow = p.cent + ((size_t)grp * N + (size_t)u * 64 + lane) * CQ_N_CENTROIDS;
@@ -294,34 +302,36 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     };
     typedef __attribute__((ext_vector_type(2))) unsigned pair_u32;
 
-    // -- prologue: centroid rows, activations of this wavefront's K steps, the ring, the first table
-    cent_req(u0);
+    // -- prologue: what depends only on the group goes first (centroid rows, the ring), then the token rows
+    cent_req(ufirst);
+    uint4 ring[HD];
+    {
+      const uint8_t* wb = kbase + (size_t)ufirst * ubytes;
+#pragma unroll
+      for (int j = 0; j < HD; ++j)
+        ring[j] = load_stream(wb + (size_t)(wave + NW * (j >> 1)) * sstride + ((j & 1) ? rb1 : 0) + loff);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float sc16 = 1.f;
+    size_t arow = 0;
+    if (tok) {
+      const int m = m0 + (i16 & 7);
+      const size_t src = p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
+      arow = src * K;
+      if (p.row_scale) sc16 = p.row_scale[src];
+    }
     // B fragments of step q: both K halves in ONE register set -- lanes of columns 0..7 hold the first half's
     // fragment of their token, lanes of columns 8..15 the second half's fragment of token column - 8 (the
     // matrix cores' output columns 8..15 are never stored, so what their B columns hold does not matter);
     // a rotation by 8 inside each row of 16 lanes brings the second half into place.
     cq_v4u breg[Q];
-    uint4 ring[RD][2];
     {
       ActRaw raw[Q];
 #pragma unroll
       for (int q = 0; q < Q; ++q) {
-        const int gs = wave + NW * q;
-        const int chunk = (gs < nS ? gs : 0) * 8 + (g4 & 1) + 4 * (g4 >> 1) + 2 * (i16 >> 3);
+        const int chunk = (wave + NW * q) * 8 + (g4 & 1) + 4 * (g4 >> 1) + 2 * (i16 >> 3);
         raw[q] = act_load8<AK>(p.A, arow + (size_t)sb * 64 + (size_t)chunk * 8);
       }
-      __builtin_amdgcn_sched_barrier(0);
-      {
-        const uint8_t* wb = kbase + (size_t)u0 * 64 * rowbytes;
-#pragma unroll
-        for (int j = 0; j < RD; ++j) {
-          const int gs = wave + NW * j;
-          const uint8_t* sp = wb + (size_t)(gs < nS ? gs : 0) * sstride;
-          ring[j][0] = load_stream(sp + loff);
-          ring[j][1] = load_stream(sp + rb1 + loff);
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int q = 0; q < Q; ++q) {
         const uint4 v = tok ? act_pack8<AK>(raw[q], grouped) : make_uint4(0u, 0u, 0u, 0u);
@@ -373,12 +383,13 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     };
 
     uint32_t par = 0;   // table and partial buffer of the current unit
-    for (int u = u0; u < u1; ++u) {
-      const uint8_t* wb = kbase + (size_t)u * 64 * rowbytes;
-      const bool has_next = u + 1 < u1;
-      const uint8_t* wb_next = has_next ? wb + 64 * rowbytes : wb;
+    for (int ui = 0; ui < ucnt; ++ui) {
+      const int u = ufirst + ui * ustep;
+      const uint8_t* wb = kbase + (size_t)u * ubytes;
+      const bool has_next = ui + 1 < ucnt;
+      const uint8_t* wb_next = has_next ? wb + (size_t)ustep * ubytes : wb;
       // the next unit's centroid rows, requested ahead of this unit's ring refills and used from step TB0 on
-      cent_req(has_next ? u + 1 : u);
+      cent_req(has_next ? u + ustep : u);
       __builtin_amdgcn_sched_barrier(0);
       const uint32_t lbase[2] = {lanebase0 | (par << 16), lanebase1 | (par << 16)};
       const uint32_t tnext = ((par ^ 1u) << 16) + (uint32_t)(wave * 8192 + lane * 4);
@@ -391,59 +402,59 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
 
 #pragma unroll
       for (int q = 0; q < Q; ++q) {
-        const int gs = wave + NW * q;
-        constexpr int dummy = 0; (void)dummy;
-        const int sl = q % RD;
-        if (gs < nS) {
+        // The two wavefronts that share a SIMD (w and w + 4) take turns at the higher issue priority, step by
+        // step: left alone, the older one always wins and the younger one finishes each unit late.
+        if ((q ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
 #pragma unroll
-          for (int c = 0; c < 2; ++c) {
-            cq_v4u bv = breg[q];
-            if (c == 1) {
+        for (int c = 0; c < 2; ++c) {
+          cq_v4u bv = breg[q];
+          if (c == 1) {
 #pragma unroll
-              for (int i = 0; i < 4; ++i)   // row_ror:8 -- lane l of a row of 16 takes lane (l + 8) % 16
-                bv[i] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bv[i], 0x128, 0xf, 0xf, false);
+            for (int i = 0; i < 4; ++i)   // row_ror:8 -- lane l of a row of 16 takes lane (l + 8) % 16
+              bv[i] = (uint32_t)__builtin_amdgcn_update_dpp((int)bv[i], (int)bv[i], 0x128, 0xf, 0xf, false);
+          }
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb) {
+            const uint4 w = ring[(2 * q + rb) % HD];
+            const uint32_t wd[4] = {w.x, w.y, w.z, w.w};
+            cq_v4u a0, a1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              // pair index byte -> table entry, row slot -> bank, byte 2 of the lane base -> table
+              const uint32_t ox = __builtin_amdgcn_perm(wd[2 * c], lbase[rb], 0x0c020400u + (i << 8));
+              const uint32_t oy = __builtin_amdgcn_perm(wd[2 * c + 1], lbase[rb], 0x0c020400u + (i << 8));
+              const uint32_t x = lds_read_u32(ox);
+              const uint32_t y = lds_read_u32(oy);
+              const pair_u32 sw = __builtin_amdgcn_permlane16_swap(x, y, false, false);
+              a0[i] = sw[0];
+              a1[i] = sw[1];
             }
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-              const uint4 w = ring[sl][rb];
-              const uint32_t wd[4] = {w.x, w.y, w.z, w.w};
-              cq_v4u a0, a1;
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                // pair index byte -> table entry, row slot -> bank, byte 2 of the lane base -> table
-                const uint32_t ox = __builtin_amdgcn_perm(wd[2 * c], lbase[rb], 0x0c020400u + (i << 8));
-                const uint32_t oy = __builtin_amdgcn_perm(wd[2 * c + 1], lbase[rb], 0x0c020400u + (i << 8));
-                const uint32_t x = lds_read_u32(ox);
-                const uint32_t y = lds_read_u32(oy);
-                const pair_u32 sw = __builtin_amdgcn_permlane16_swap(x, y, false, false);
-                a0[i] = sw[0];
-                a1[i] = sw[1];
-              }
-              if constexpr (F16) {
-                acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                    __builtin_bit_cast(cq_v8f16, a0), __builtin_bit_cast(cq_v8f16, bv), acc[rb][0], 0, 0, 0);
-                acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                    __builtin_bit_cast(cq_v8f16, a1), __builtin_bit_cast(cq_v8f16, bv), acc[rb][1], 0, 0, 0);
-              } else {
-                acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    __builtin_bit_cast(cq_v8bf16, a0), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][0], 0, 0, 0);
-                acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    __builtin_bit_cast(cq_v8bf16, a1), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][1], 0, 0, 0);
-              }
+            if constexpr (F16) {
+              acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                  __builtin_bit_cast(cq_v8f16, a0), __builtin_bit_cast(cq_v8f16, bv), acc[rb][0], 0, 0, 0);
+              acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                  __builtin_bit_cast(cq_v8f16, a1), __builtin_bit_cast(cq_v8f16, bv), acc[rb][1], 0, 0, 0);
+            } else {
+              acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  __builtin_bit_cast(cq_v8bf16, a0), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][0], 0, 0, 0);
+              acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  __builtin_bit_cast(cq_v8bf16, a1), __builtin_bit_cast(cq_v8bf16, bv), acc[rb][1], 0, 0, 0);
             }
           }
         }
-        __builtin_amdgcn_sched_barrier(0);  // the refill must stay behind the last use of the slot
-        {
-          const int qn = q + RD;             // the step that reuses this slot
-          const bool same = qn < Q;
-          const int gn = wave + NW * (same ? qn : qn - Q);
-          const uint8_t* sp = (same ? wb : wb_next) + ((gn < nS && (same || has_next)) ? (size_t)gn * sstride : 0);
-          ring[sl][0] = load_stream(sp + loff);
-          ring[sl][1] = load_stream(sp + rb1 + loff);
+        __builtin_amdgcn_sched_barrier(0);  // the refills must stay behind the last use of their slots
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          const int hn = 2 * q + rb + HD;    // the half step that reuses this slot
+          const bool same = hn < 2 * Q;
+          const int h2 = same ? hn : hn - 2 * Q;
+          const uint8_t* sp = (same ? wb : wb_next) + ((same || has_next) ? (size_t)(wave + NW * (h2 >> 1)) * sstride : 0) +
+                              ((h2 & 1) ? rb1 : 0);
+          ring[(2 * q + rb) % HD] = load_stream(sp + loff);
         }
         // the previous unit's results (once), and this step's share of the next unit's table
-        if (q == 0 && u > u0) finish(u - 1, par ^ 1u);
+        if (q == 0 && ui > 0) finish(u - ustep, par ^ 1u);
         if (q == TB0) cent_f16();
         if (q >= TB0) table_part(tnext, ((q - TB0) * 32) / (Q - TB0), ((q - TB0 + 1) * 32) / (Q - TB0));
       }
@@ -462,14 +473,17 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
       __syncthreads();
       par ^= 1u;
     }
-    finish(u1 - 1, par ^ 1u);
+    __builtin_amdgcn_s_setprio(0);
+    finish(ufirst + (ucnt - 1) * ustep, par ^ 1u);
   };
+#ifndef CQ_NO_PIPE
   if constexpr (QS > 0) {
-    if (Me <= 8 && Qmax == QS) {
+    if (Me <= 8 && nS == QS * NW) {   // every wavefront has exactly QS real steps
       run_units_pipe();
       return;
     }
   }
+#endif
 
   for (int tb = 0; tb < n_tb; ++tb) {
     const int Mb = min(32, Me - 32 * tb);
