@@ -4,9 +4,11 @@ over one batch of synthetic tokens already resident in HBM).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral_decode]
 
-Prints ONE JSON line: whole-layer tokens/s, the roofline figure of the dominant kernel (measured
-with HIP events recorded on the launch stream at the stage boundaries), and the CPU oracle timed on
-this machine's host cores on a bounded sample of the same workload.
+Prints ONE JSON line: whole-layer tokens/s (mean, median and minimum step time), the roofline figure of the
+dominant kernel (measured with HIP events recorded on the launch stream at the stage boundaries), the CPU
+oracle timed on this machine's host cores on a bounded sample of the same workload and -- for the default
+workload, the Mixtral-shaped decode layer -- a nested "prefill" object with the same measurements for the
+Mixtral-shaped prefill layer (the matrix-core leg of the metric).
 """
 import argparse
 import json
@@ -49,6 +51,10 @@ def parse_args():
     ap.add_argument("--workload", default="mixtral_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle's expert sample")
+    ap.add_argument("--no-prefill", action="store_true",
+                    help="default workload only: skip the Mixtral-shaped prefill leg of the metric")
+    ap.add_argument("--prefill-steps", type=int, default=10)
+    ap.add_argument("--prefill-warmup", type=int, default=3)
     ap.add_argument("--compare-lut", action="store_true",
                     help="A4 workloads: also time the gate/up product in the lookup formulation (product tables)")
     return ap.parse_args()
@@ -95,6 +101,144 @@ def cpu_baseline(L, budget_s):
     }
 
 
+def clocks_as_found():
+    """Shader / memory clocks as rocm-smi reports them (not settable without root); None when it is not usable."""
+    import shutil
+    import subprocess
+    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        out = subprocess.run([exe, "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
+        card = next(iter(json.loads(out).values()))
+        return {k.split()[0]: v for k, v in card.items() if "clock" in k.lower() and ("sclk" in k or "mclk" in k)}
+    except Exception:
+        return None
+
+
+def yardsticks(B, torch, info):
+    """Measured ceilings next to the nominal peaks (run first: they also bring the clocks up before the timed
+    steps): a streaming read shaped like the product's index stream, the bare matrix-core loop, and the plain
+    copy of known size that the HBM counters of a profiled run are scaled by."""
+    probe = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    probe.random_(0, 255)
+    for _ in range(3):
+        B.cq_stream_read(probe)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        B.cq_stream_read(probe)
+    e1.record()
+    torch.cuda.synchronize()
+    read_gbps = probe.numel() * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    B.cq_mfma_loop(info["cu_count"] * 8, 200)
+    torch.cuda.synchronize()
+    e0.record()
+    mfma_flops = B.cq_mfma_loop(info["cu_count"] * 8, 2000)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_tflops = mfma_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    dst = torch.empty_like(probe)
+    dst.copy_(probe)
+    torch.cuda.synchronize()
+    del probe, dst
+    return read_gbps, mfma_tflops
+
+
+def measure(B, torch, synth, name, steps, warmup, n_stage):
+    """W warm-up steps, exactly K timed steps of cq_moe_forward (inputs resident in HBM), then n_stage runs of
+    the same launches with events at the stage boundaries.  Returns (result dict, layer inputs)."""
+    cfg = synth.CONFIGS[name]
+    t_gen = time.perf_counter()
+    L = synth.make_layer(cfg)
+    layer = B.device_layer_from_inputs(L)
+    X = torch.from_numpy(L.X).to("cuda")
+    Y = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    for _ in range(warmup):
+        B.cq_moe_forward(layer, X, Y)
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(steps):
+        B.cq_moe_forward(layer, X, Y)
+        marks[i + 1].record()     # on the launch stream (torch's current stream); no host wait
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
+
+    acc = np.zeros((n_stage, len(B.STAGES)))
+    for i in range(n_stage):
+        _, ms = B.cq_moe_forward_timed(layer, X, Y)
+        acc[i] = [ms[k] for k in B.STAGES]
+    stage = dict(zip(B.STAGES, acc.mean(axis=0).tolist()))
+    stage_median = dict(zip(B.STAGES, np.median(acc, axis=0).tolist()))
+    stage_min = dict(zip(B.STAGES, acc.min(axis=0).tolist()))
+
+    mid = B.moe_intermediates(layer, cfg.T)
+    offs = mid["offsets"].cpu().numpy()
+    counts = np.diff(offs)
+    active = int((counts > 0).sum())
+    rows = int(offs[-1])
+    # packed indices + centroid tables (one 32-byte table per row, or per group of group_k weights of a row)
+    g = getattr(cfg, "group_k", 0)
+    gu_tables, dn_tables = synth.n_blocks(cfg.H, g) or 1, synth.n_blocks(cfg.I, g) or 1
+    gu_bytes = active * (2 * cfg.I * cfg.H // 2 + 2 * cfg.I * 32 * gu_tables)
+    dn_bytes = active * (cfg.H * cfg.I // 2 + cfg.H * 32 * dn_tables)
+    gu_flops = rows * 2.0 * (2 * cfg.I) * cfg.H
+    dn_flops = rows * 2.0 * cfg.H * cfg.I
+    flop_per_byte = (gu_flops + dn_flops) / (gu_bytes + dn_bytes)
+    gu_s, dn_s = stage["gate_up"] * 1e-3, stage["down"] * 1e-3
+    gu_med, dn_med = stage_median["gate_up"] * 1e-3, stage_median["down"] * 1e-3
+    hbm_bound = flop_per_byte < MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
+    if hbm_bound:
+        ach = gu_bytes / gu_s / 1e9
+        # (block-wise tables are decoded by the large-tile kernel, at decode sizes by its narrow-tile variant)
+        kern = "gemm_narrow_kernel" if g and rows <= 64 else "gemm_large_kernel" if g else "gemm_small_kernel"
+        roofline = {"bound": "hbm", "kernel": f"{kern} (gate/up codebook product + SwiGLU)",
+                    "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
+                    "frac_at_median_duration": gu_bytes / gu_med / 1e9 / HBM_PEAK_GBPS,
+                    "algorithmic_bytes_per_launch": gu_bytes}
+    else:
+        ach = gu_flops / gu_s / 1e12
+        kern = "gemm_large_kernel"
+        roofline = {"bound": "mfma", "kernel": "gemm_large_kernel (gate/up codebook product + SwiGLU)",
+                    "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                    "frac_at_median_duration": gu_flops / gu_med / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "algorithmic_flops_per_launch": gu_flops}
+    traffic = measured_traffic(cfg.name, kern)
+    roofline.update({"avg_launch_ms": stage["gate_up"], "median_launch_ms": stage_median["gate_up"],
+                     "launches_timed": n_stage, "traffic": traffic,
+                     "traffic_source": (f"profiles/hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                        f"script, per launch of {kern}" if traffic else None)})
+    res = {
+        "tokens_per_s": cfg.T * steps / dt, "ms_per_step": dt / steps * 1e3,
+        "ms_per_step_median": float(np.median(per_step)), "ms_per_step_min": float(per_step.min()),
+        "steps": steps, "warmup": warmup,
+        "config": {"workload": f"{cfg.name} (E={cfg.E} top-{cfg.top_k} S={cfg.S} H={cfg.H} I={cfg.I} T={cfg.T} "
+                               f"A{cfg.act_bits}W4, 16 bf16 centroids per "
+                               + (f"group of {g} weights of a row (block-wise)" if g else "weight row")
+                               + (", Hadamard rotation" if getattr(cfg, "r_hadamard", False) else "")
+                               + (f", online Hadamard + A{cfg.h_bits} in front of the down projection)"
+                                  if getattr(cfg, "h_bits", 0) else ")"),
+                   "active_experts": active, "rows": rows,
+                   "max_tokens_per_expert": int(counts.max()), "mean_tokens_per_expert": float(counts.mean())},
+        "roofline": roofline,
+        "stage_ms": stage, "stage_ms_median": stage_median, "stage_ms_min": stage_min,
+        "weight_stream": {"gate_up_plus_down_GBps": (gu_bytes + dn_bytes) / (gu_s + dn_s) / 1e9,
+                          "frac_of_hbm_peak": (gu_bytes + dn_bytes) / (gu_s + dn_s) / 1e9 / HBM_PEAK_GBPS,
+                          "down_frac_of_hbm_peak": dn_bytes / dn_s / 1e9 / HBM_PEAK_GBPS},
+        "mfma": {"gate_up_plus_down_TFLOPs": (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12,
+                 "frac_of_bf16_peak": (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                 "down_frac_of_bf16_peak": dn_flops / dn_s / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "setup_s": t_gen,
+    }
+    return res, L, layer, X, Y, mid, rows
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -110,114 +254,23 @@ def main():
         sys.exit(3)
     B.load_library()
     torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.workload]
-    t_gen = time.perf_counter()
-    L = synth.make_layer(cfg)
-    layer = B.device_layer_from_inputs(L)
-    X = torch.from_numpy(L.X).to("cuda")
-    Y = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device="cuda")
-    torch.cuda.synchronize()
-    t_gen = time.perf_counter() - t_gen
     info = B.cq_device_info()
+    clocks_before = clocks_as_found()
+    read_gbps, mfma_tflops = yardsticks(B, torch, info)
 
-    for _ in range(args.warmup):
-        B.cq_moe_forward(layer, X, Y)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        B.cq_moe_forward(layer, X, Y)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    tokens_per_s = cfg.T * args.steps / dt
-
-    # per-stage durations from HIP events recorded on the launch stream at the stage boundaries
-    stage = {k: 0.0 for k in B.STAGES}
-    n_timed = max(10, min(args.steps, 100))
-    for _ in range(n_timed):
-        _, ms = B.cq_moe_forward_timed(layer, X, Y)
-        for k in stage:
-            stage[k] += ms[k] / n_timed
-
-    mid = B.moe_intermediates(layer, cfg.T)
-    offs = mid["offsets"].cpu().numpy()
-    counts = np.diff(offs)
-    active = int((counts > 0).sum())
-    rows = int(offs[-1])
-    # packed indices + centroid tables (one 32-byte table per row, or per group of group_k weights of a row)
-    g = getattr(cfg, "group_k", 0)
-    gu_tables, dn_tables = synth.n_blocks(cfg.H, g) or 1, synth.n_blocks(cfg.I, g) or 1
-    gu_bytes = active * (2 * cfg.I * cfg.H // 2 + 2 * cfg.I * 32 * gu_tables)
-    dn_bytes = active * (cfg.H * cfg.I // 2 + cfg.H * 32 * dn_tables)
-    gu_flops = rows * 2.0 * (2 * cfg.I) * cfg.H
-    dn_flops = rows * 2.0 * cfg.H * cfg.I
-    flop_per_byte = (gu_flops + dn_flops) / (gu_bytes + dn_bytes)
-    gu_s = stage["gate_up"] * 1e-3
-    dn_s = stage["down"] * 1e-3
-    if flop_per_byte < MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9):
-        ach = gu_bytes / gu_s / 1e9
-        # (block-wise tables are decoded by the large-tile kernel, at decode sizes by its narrow-tile variant)
-        kern = "gemm_narrow_kernel" if g and rows <= 64 else "gemm_large_kernel" if g else "gemm_small_kernel"
-        roofline = {"bound": "hbm", "kernel": f"{kern} (gate/up codebook product + SwiGLU)",
-                    "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
-                    "traffic": measured_traffic(cfg.name, kern),
-                    "algorithmic_bytes_per_launch": gu_bytes, "avg_launch_ms": stage["gate_up"]}
-    else:
-        ach = gu_flops / gu_s / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_large_kernel (gate/up codebook product + SwiGLU)",
-                    "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": measured_traffic(cfg.name, "gemm_large_kernel"),
-                    "algorithmic_flops_per_launch": gu_flops, "avg_launch_ms": stage["gate_up"]}
-
-    # measured streaming-read ceiling next to the nominal peak
-    probe = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-    probe.random_(0, 255)
-    for _ in range(3):
-        B.cq_stream_read(probe)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(10):
-        B.cq_stream_read(probe)
-    torch.cuda.synchronize()
-    read_gbps = probe.numel() * 10 / (time.perf_counter() - t0) / 1e9
-    # measured dense bf16 MFMA ceiling: bare matrix-core loop, 8 workgroups per CU
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    B.cq_mfma_loop(info["cu_count"] * 8, 200)
-    torch.cuda.synchronize()
-    e0.record()
-    mfma_flops = B.cq_mfma_loop(info["cu_count"] * 8, 2000)
-    e1.record()
-    torch.cuda.synchronize()
-    mfma_tflops = mfma_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
-    # a plain copy of known size (1 GiB read + 1 GiB written): the yardstick the HBM counters of a
-    # profiled run are scaled by
-    dst = torch.empty_like(probe)
-    dst.copy_(probe)
-    torch.cuda.synchronize()
-    del probe, dst
-
+    n_stage = 100 if synth.CONFIGS[args.workload].T <= 1024 else 20
+    res, L, layer, X, Y, mid, rows = measure(B, torch, synth, args.workload, args.steps, args.warmup, n_stage)
+    cfg = L.cfg
     out = {
-        "metric": "MoE-layer tokens/s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} (E={cfg.E} top-{cfg.top_k} S={cfg.S} H={cfg.H} I={cfg.I} T={cfg.T} "
-                               f"A{cfg.act_bits}W4, 16 bf16 centroids per "
-                               + (f"group of {g} weights of a row (block-wise)" if g else "weight row")
-                               + (", Hadamard rotation" if getattr(cfg, "r_hadamard", False) else "")
-                               + (f", online Hadamard + A{cfg.h_bits} in front of the down projection)"
-                                  if getattr(cfg, "h_bits", 0) else ")"),
-                   "active_experts": active, "rows": rows,
-                   "max_tokens_per_expert": int(counts.max()), "mean_tokens_per_expert": float(counts.mean())},
-        "roofline": roofline,
-        "stage_ms": stage,
-        "weight_stream": {"gate_up_plus_down_GBps": (gu_bytes + dn_bytes) / (gu_s + dn_s) / 1e9,
-                          "frac_of_hbm_peak": (gu_bytes + dn_bytes) / (gu_s + dn_s) / 1e9 / HBM_PEAK_GBPS,
-                          "measured_stream_read_GBps": read_gbps},
-        "mfma": {"gate_up_plus_down_TFLOPs": (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12,
-                 "frac_of_bf16_peak": (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                 "measured_mfma_loop_TFLOPs": mfma_tflops},
-        "device": info, "setup_s": t_gen,
+        "metric": "MoE-layer tokens/s", "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "ms_per_step_median": res["ms_per_step_median"], "ms_per_step_min": res["ms_per_step_min"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": res["config"], "roofline": res["roofline"],
+        "stage_ms": res["stage_ms"], "stage_ms_median": res["stage_ms_median"], "stage_ms_min": res["stage_ms_min"],
+        "weight_stream": dict(res["weight_stream"], measured_stream_read_GBps=read_gbps),
+        "mfma": dict(res["mfma"], measured_mfma_loop_TFLOPs=mfma_tflops),
+        "device": info, "clocks_as_found": clocks_before, "setup_s": res["setup_s"],
     }
     if args.compare_lut and cfg.act_bits == 4 and not getattr(cfg, "h_bits", 0):
         # the gate/up product of this step's sorted rows, once on the matrix cores and once by table lookup
@@ -240,6 +293,16 @@ def main():
                                  "matrix_core_ms": mm, "lookup_ms": lut, "lookup_over_matrix_core": lut / mm}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L, args.cpu_seconds)
+    del layer, X, Y, mid, L
+    torch.cuda.empty_cache()
+    if args.workload == "mixtral_decode" and not args.no_prefill:
+        # the third leg of the metric: matrix-core utilisation of the Mixtral-shaped prefill layer (T = 4096, A4)
+        pre, _, _, _, _, _, _ = measure(B, torch, synth, "mixtral_prefill", args.prefill_steps, args.prefill_warmup, 10)
+        out["prefill"] = {k: pre[k] for k in ("tokens_per_s", "ms_per_step", "ms_per_step_median", "ms_per_step_min",
+                                              "steps", "warmup", "config", "roofline", "stage_ms", "stage_ms_median",
+                                              "mfma", "setup_s")}
+        out["prefill"]["mfma"]["measured_mfma_loop_TFLOPs"] = mfma_tflops
+    out["clocks_after"] = clocks_as_found()
     print(json.dumps(out))
 
 

@@ -262,17 +262,6 @@ cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y,
 cq_status cq_moe_forward_static(const cq_layer* L, const float* X, int T, float* Y, cq_stream stream);
 
 /*
- * Measurement variant of cq_moe_forward: same launches, with HIP events recorded on `stream` at the
- * stage boundaries.  It waits for the last event (so, unlike cq_moe_forward, it synchronises the
- * host) and writes the elapsed milliseconds of the CQ_N_STAGES stages to stage_ms (host memory):
- * [0] rotate+quantize, [1] route+permute, [2] gate/up product, [3] down product, [4] combine.
- */
-#define CQ_N_STAGES 5
-cq_status cq_moe_forward_timed(const cq_layer* L, const float* X, int T, float* Y,
-                               void* workspace, size_t workspace_bytes, cq_stream stream,
-                               float* stage_ms);
-
-/*
  * Offline, one-time re-layout of canonical indices into the kernel-native tile order described at
  * cq_codebook_weights (the paper's pipeline is fully offline, so the stored order is free; the
  * byte count streamed is unchanged).  dst must hold cq_prepack_bytes(W) bytes.
@@ -285,20 +274,6 @@ cq_status cq_prepack(const cq_codebook_weights* W, void* dst, size_t dst_bytes, 
  * reading `prepacked` if present, else `idx` (Eq. W_c).
  */
 cq_status cq_decode_dense(const cq_codebook_weights* W, int g, uint16_t* Wc_bf16, cq_stream stream);
-
-/* Device facts used for rooflines: writes CU count, max clock (kHz), memory clock (kHz), memory
- * bus width (bits), LDS bytes per workgroup. Returns CQ_ERR_HIP when no device is present. */
-cq_status cq_device_info(int* cu_count, int* clock_khz, int* mem_clock_khz, int* bus_bits, int* lds_bytes);
-
-/* Plain streaming read of `bytes` bytes (16-byte multiples) used to measure the achievable HBM
- * read ceiling next to the nominal one; the 16-byte XOR of everything read lands in sink[0..3]. */
-cq_status cq_stream_read(const void* src, size_t bytes, uint32_t* sink, cq_stream stream);
-
-/* Bare matrix-core loop used to measure the achievable dense bf16 MFMA ceiling next to the nominal
- * one: `workgroups` workgroups of 4 wavefronts, each wavefront issuing iters x 16 independent
- * v_mfma_f32_32x32x16_bf16 (32768 flops each) on register operands.  sink[workgroups * 256] f32
- * receives one value per thread (keeps the loop alive).  Flops = workgroups * 4 * iters * 16 * 32768. */
-cq_status cq_mfma_loop(int workgroups, int iters, float* sink, cq_stream stream);
 
 #ifdef __cplusplus
 }

@@ -36,7 +36,7 @@ def sources():
 def _stale(src: str, obj: str) -> bool:
     if not os.path.exists(obj):
         return True
-    deps = [os.path.join(CSRC, src), os.path.join(INCLUDE, "cq.h")]
+    deps = [os.path.join(CSRC, src), os.path.join(INCLUDE, "cq.h"), os.path.join(INCLUDE, "cq_measure.h")]
     deps += [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
 

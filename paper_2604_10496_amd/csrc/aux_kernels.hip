@@ -146,21 +146,42 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, float* __rest
   sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
-                                                          uint32_t* __restrict__ sink) {
-  uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc.x ^= a.x ^ b.x ^ c.x ^ d.x; acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
-    acc.z ^= a.z ^ b.z ^ c.z ^ d.z; acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+// Streaming-read yardstick, shaped like the product kernel's index stream: one workgroup of 8 wavefronts per
+// contiguous chunk of 512 KiB; a wavefront load is one contiguous KiB (16 bytes per lane, non-temporal); the
+// wavefronts take the chunk's KiB steps in turn and keep 8 of them in flight each (64 KiB per workgroup).
+constexpr int kReadChunk = 512 << 10;
+__global__ __launch_bounds__(512, 1) void stream_read_kernel(const uint4* __restrict__ src, uint32_t* __restrict__ sink) {
+  constexpr int NW = 8, D = 8, kSteps = kReadChunk / 1024, Q = kSteps / NW;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const cq_v4u* base = reinterpret_cast<const cq_v4u*>(src) + (size_t)blockIdx.x * (kReadChunk / 16) + lane;
+  cq_v4u ring[D];
+#pragma unroll
+  for (int j = 0; j < D; ++j) ring[j] = __builtin_nontemporal_load(base + (size_t)(wave + NW * j) * 64);
+  cq_v4u acc = {0u, 0u, 0u, 0u};
+  for (int q0 = 0; q0 < Q; q0 += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      const cq_v4u w = ring[j];
+      const int qn = q0 + j + D;   // (clamped re-reads of step 0 at the end: cache hits, a few per cent of the loads)
+      ring[j] = __builtin_nontemporal_load(base + (size_t)(qn < Q ? wave + NW * qn : 0) * 64);
+      acc ^= w;
+    }
   }
-  for (; i < n16; i += stride) {
+  // keeps the loads alive; the branch is practically never taken
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) {
+    sink[0] = acc[0]; sink[1] = acc[1]; sink[2] = acc[2]; sink[3] = acc[3];
+  }
+}
+
+// the bytes past the last whole chunk
+__global__ __launch_bounds__(256) void stream_read_tail_kernel(const uint4* __restrict__ src, size_t n16,
+                                                               uint32_t* __restrict__ sink) {
+  uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
     const uint4 a = src[i];
     acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
   }
-  // keeps the loads alive; the branch is practically never taken
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) {
     sink[0] = acc.x; sink[1] = acc.y; sink[2] = acc.z; sink[3] = acc.w;
   }
@@ -267,7 +288,14 @@ extern "C" cq_status cq_mfma_loop(int workgroups, int iters, float* sink, cq_str
 extern "C" cq_status cq_stream_read(const void* src, size_t bytes, uint32_t* sink, cq_stream stream) {
   if (!src || !sink) return CQ_ERR_NULL;
   if (bytes == 0 || bytes % 16 != 0) return CQ_ERR_SHAPE;
-  hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
-                     bytes / 16, sink);
+  const size_t chunks = bytes / kReadChunk;
+  if (chunks > 0x7fffffffu) return CQ_ERR_SHAPE;
+  if (chunks > 0)
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)chunks), dim3(512), 0, (hipStream_t)stream, (const uint4*)src,
+                       sink);
+  const size_t rest16 = (bytes - chunks * kReadChunk) / 16;
+  if (rest16 > 0)
+    hipLaunchKernelGGL(stream_read_tail_kernel, dim3((unsigned)((rest16 + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, (const uint4*)src + chunks * (kReadChunk / 16), rest16, sink);
   return cq_check_launch();
 }

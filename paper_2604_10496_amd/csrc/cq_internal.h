@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "cq.h"
+#include "cq_measure.h"
 
 #define CQ_WAVE 64
 

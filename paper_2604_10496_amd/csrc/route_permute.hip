@@ -14,8 +14,11 @@ namespace {
 constexpr int kMaxSlots = 16;       // experts per lane: E <= 1024
 constexpr int kPermBlock = 256;     // assignments per counting-sort block (one wavefront, 4 rounds)
 
+// Order-preserving key of a logit.  -0 is folded into +0 first (they are equal logits: the lower expert id
+// wins), and a NaN, whatever its sign, gets the smallest key (it is never preferred to a number).
 __device__ __forceinline__ uint32_t order_key(float x) {
-  const uint32_t u = __float_as_uint(x);
+  if (x != x) return 0u;
+  const uint32_t u = __float_as_uint(x + 0.0f);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 

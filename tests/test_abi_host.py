@@ -15,9 +15,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "cq.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(cq_[a-z0-9_]+)\s*\(", text)))
+    found = set()
+    for header in ("cq.h", "cq_measure.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        found |= set(re.findall(r"\b(cq_[a-z0-9_]+)\s*\(", text))
+    return sorted(found)
 
 
 def test_header_and_library_agree():

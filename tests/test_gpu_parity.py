@@ -190,6 +190,9 @@ def test_route_exact_ties_and_empty_experts(B):
     T, E, k = 50, 16, 4
     logits = rng.integers(-3, 4, size=(T, E)).astype(np.float32)      # many exact ties
     logits[:, 12:] = -100.0                                            # experts 12..15 never chosen
+    zeros = logits == 0.0
+    logits[zeros & (rng.random(logits.shape) < 0.5)] = -0.0           # -0 and +0 are one value: ties by expert id
+    assert np.signbit(logits[zeros]).any() and not np.signbit(logits[zeros]).all()
     ids, w = O.route_topk(logits, k)
     off, perm, inv = O.permute_by_expert(ids, E)
     got = B.cq_route_permute(None, None, None, k, logits_in=_dev(logits))
