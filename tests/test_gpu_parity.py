@@ -717,38 +717,49 @@ def test_gemm_lut_swiglu_gather_scale_and_matrix_core_kernel(B, out_kind):
 # ---------------------------------------------------------------------------------------------
 # the whole layer
 # ---------------------------------------------------------------------------------------------
-H_TOL = 2e-3   # intermediate h against the oracle, relative to the row maximum
+H_TOL = 1e-5   # intermediate h (fp32 in this variant) against the oracle, relative to the row maximum
+
+
+def _patch_tie_tokens(L, ref, q_gpu, toks):
+    """Online-Hadamard variant: for tokens whose first-stage codes differ from the oracle's at a rounding tie
+    (allowed), the per-row references (h, rotated h, its codes and scale) are re-evaluated by the oracle on the
+    codes the GPU chose, so that everything downstream is compared like with like.  Returns those tokens."""
+    cfg = L.cfg
+    tie = [int(t) for t in toks if np.any(q_gpu[t] != ref["q"][t])]
+    inv = ref["inv_perm"].reshape(cfg.T, cfg.top_k)
+    for t in tie:
+        a = ref["scale"][t] * q_gpu[t].astype(np.float64)[None, :]
+        rows = [(int(inv[t, j]), int(ref["ids"][t, j])) for j in range(cfg.top_k)]
+        rows += [(cfg.T * cfg.top_k + s_ * cfg.T + t, cfg.E + s_) for s_ in range(cfg.S)]
+        for m, e in rows:
+            r = O.expert_ffn(a, L.experts[e], cfg.h_bits, cfg.group_k)
+            ref["h_sorted"][m], ref["hr_sorted"][m] = r["h"][0], r["hr"][0]
+            ref["hq_sorted"][m], ref["hs_sorted"][m] = r["hq"][0], r["hs"][0]
+    return tie
 
 
 def _check_had_codes(mid, ref, bits, rows=None):
-    """Online-Hadamard variant, per sorted row.  The gate/up product accumulates on bf16 matrix cores, whose
-    sums of cancelling terms carry errors far above fp32 rounding of the result (seen: 8e-4 of a row's
-    maximum), so the codes of the rotated intermediate cannot be compared with codes computed from the
-    oracle's own h.  Instead (a) h itself is compared with the oracle's, to the tolerance of this path, and
-    (b) the new step is checked exactly: the codes must be those of the oracle's transform + quantization
-    applied to the SAME h (the one the GPU produced), equal except +-1 at rounding ties."""
-    sel = slice(None) if rows is None else rows
+    """Online-Hadamard variant, per sorted row, against the PURE oracle: the intermediate h to fp32-class
+    accuracy, the scales, and the codes of the rotated intermediate -- equal to the oracle's own codes except
+    +-1 where the oracle's own h' / s lies within the tie window of a rounding tie.  Returns the sorted rows in
+    which such a tie code occurs."""
+    sel = np.arange(mid["h"].shape[0]) if rows is None else np.asarray(rows)
     h = mid["h"].cpu().numpy().astype(np.float64)[sel]
     h_ref = ref["h_sorted"][sel]
     herr = np.abs(h - h_ref).max(axis=1) / np.maximum(np.abs(h_ref).max(axis=1), 1e-300)
-    hr = O.hadamard_rows(h)
-    q_ref, s_ref = O.quantize(hr, bits)
-    n = Hp.check_codes(mid["hq"].cpu().numpy()[sel], q_ref, hr, s_ref)
-    assert np.allclose(mid["hscale"].cpu().numpy()[sel], s_ref, rtol=1e-5)
-    _say(f"  intermediate: max |h error| / row max = {herr.max():.2e}; rotated codes differing at ties: {n} of {hr.size}")
+    hq = mid["hq"].cpu().numpy()[sel]
+    n = Hp.check_codes(hq, ref["hq_sorted"][sel], ref["hr_sorted"][sel], ref["hs_sorted"][sel])
+    assert np.allclose(mid["hscale"].cpu().numpy()[sel], ref["hs_sorted"][sel], rtol=1e-5)
+    _say(f"  intermediate: max |h error| / row max = {herr.max():.2e}; rotated codes differing at ties: {n} of {hq.size}")
     assert herr.max() <= H_TOL
-    assert n <= max(2, hr.size // 500)
-
-
-HAD_END_TO_END_TOL = 2e-2   # online-Hadamard variant against the pure oracle (see _had_reference_output)
+    assert n <= max(2, hq.size // 500)
+    return sel[np.any(hq != ref["hq_sorted"][sel], axis=1)]
 
 
 def _had_reference_output(L, ref, mid, toks):
     """Online-Hadamard variant: the layer output the oracle's functions give for the codes and scales the GPU
-    produced (down projection by the dense definition, weighted sum in the fixed order).  The second
-    quantizer turns the accumulation error of the gate/up product into code flips, so the output is compared
-    (to the usual tolerance) with this reference, and with the pure oracle only to a bound that allows for
-    those flips."""
+    produced (down projection by the dense definition, weighted sum in the fixed order): the reference for the
+    tokens in whose rows a code differs at a tie."""
     cfg = L.cfg
     hq = mid["hq"].cpu().numpy().astype(np.float64)
     hs = mid["hscale"].cpu().numpy().astype(np.float64)
@@ -771,6 +782,31 @@ def _had_reference_output(L, ref, mid, toks):
             m = cfg.T * cfg.top_k + s_ * cfg.T + t
             Y[n] += hs[m] * (dense[e] @ hq[m])
     return Y
+
+
+def _check_had_output(L, ref, mid, Yh, toks, q_gpu):
+    """Online-Hadamard variant, layer output: every checked token against the pure oracle at the layer's bar,
+    except tokens with a tie code in either quantizer, which are compared with the oracle evaluated on the codes
+    the GPU chose (one step of a code moves the output by more than fp32 rounding does)."""
+    cfg = L.cfg
+    toks = np.asarray(toks)
+    tie1 = _patch_tie_tokens(L, ref, q_gpu, toks)
+    a_rows = ref["inv_perm"].reshape(cfg.T, cfg.top_k)[toks].reshape(-1)
+    s_rows = np.array([cfg.T * cfg.top_k + s_ * cfg.T + t for s_ in range(cfg.S) for t in toks], dtype=np.int64)
+    flipped = _check_had_codes(mid, ref, cfg.h_bits, rows=np.sort(np.concatenate([a_rows, s_rows]).astype(np.int64)))
+    src = mid["src_token"].cpu().numpy()
+    special = np.union1d(np.asarray(tie1, dtype=np.int64), src[flipped] if flipped.size else np.array([], dtype=np.int64))
+    plain = np.setdiff1d(toks, special)
+    err = Hp.row_rel_l2(Yh[plain], ref["Y"][plain]) if plain.size else np.zeros(1)
+    _say(f"  output: {plain.size} tokens against the pure oracle, max row rel L2={err.max():.3e}; "
+         f"{special.size} tokens with a tie code compared on the GPU's codes")
+    assert err.max() <= OUT_TOL
+    special = np.intersect1d(special, toks)
+    if special.size:
+        err2 = Hp.row_rel_l2(Yh[special], _had_reference_output(L, ref, mid, special))
+        assert err2.max() <= OUT_TOL
+        err = np.concatenate([err, err2])
+    return err
 
 
 def _reference_rows_on_gpu_codes(L, ref, q_gpu, toks):
@@ -799,8 +835,6 @@ def _check_layer(B, cfg, only_tokens=None, label=""):
     Y = B.cq_moe_forward(layer, _dev(L.X))
     torch.cuda.synchronize()
     mid = B.moe_intermediates(layer, cfg.T)
-    if cfg.h_bits and only_tokens is None:
-        _check_had_codes(mid, ref, cfg.h_bits)
     n_tie = Hp.check_codes(mid["Q"].cpu().numpy(), ref["q"], ref["XR"], ref["scale"])
     # the rotation itself (fp32 matrix cores, or the split f16 product for many tokens): fp32-class error,
     # measured against the largest entry of the row
@@ -822,13 +856,12 @@ def _check_layer(B, cfg, only_tokens=None, label=""):
         q_gpu = mid["Q"].cpu().numpy()
         tie_rows = [int(t) for t in rows if np.any(q_gpu[t] != ref["q"][t])]
         ref["Y"][tie_rows] = _reference_rows_on_gpu_codes(L, ref, q_gpu, tie_rows)
-    err = Hp.row_rel_l2(Yh[rows], ref["Y"][rows])
-    _say(f"  tie codes={n_tie} max row rel L2={err.max():.3e} mean={err.mean():.3e}")
     assert np.all(np.isfinite(Yh))
     if cfg.h_bits:
-        assert err.max() <= HAD_END_TO_END_TOL
-        err = Hp.row_rel_l2(Yh[rows], _had_reference_output(L, ref, mid, rows))
-        _say(f"  against the oracle on the GPU's codes of the rotated intermediate: max row rel L2={err.max():.3e}")
+        err = _check_had_output(L, ref, mid, Yh, rows, mid["Q"].cpu().numpy())
+    else:
+        err = Hp.row_rel_l2(Yh[rows], ref["Y"][rows])
+    _say(f"  tie codes={n_tie} max row rel L2={err.max():.3e} mean={err.mean():.3e}")
     assert err.max() <= OUT_TOL
     # run twice: bit-identical (no atomics anywhere on the path)
     Y2 = B.cq_moe_forward(layer, _dev(L.X)).cpu().numpy()
@@ -994,9 +1027,6 @@ def _full_size(B, name, n_sample, tile_rows=0):
     ref = Hp.oracle_forward(L, only_tokens=toks, keep_expert_outputs=bool(cfg.h_bits) or bool(tile_rows))
     mid = B.moe_intermediates(layer, cfg.T)
     n_tie = Hp.check_codes(mid["Q"].cpu().numpy(), ref["q"], ref["XR"], ref["scale"])
-    if cfg.h_bits:   # sorted rows that belong to the sampled tokens
-        a_rows = ref["inv_perm"].reshape(cfg.T, cfg.top_k)[toks].reshape(-1)
-        _check_had_codes(mid, ref, cfg.h_bits, rows=np.sort(a_rows))
     assert np.array_equal(mid["ids"].cpu().numpy(), ref["ids"])
     assert np.array_equal(mid["offsets"].cpu().numpy()[:cfg.E + 1], ref["offsets"])
     assert np.array_equal(mid["perm"].cpu().numpy(), ref["perm"])
@@ -1008,14 +1038,13 @@ def _full_size(B, name, n_sample, tile_rows=0):
         q_gpu = mid["Q"].cpu().numpy()
         tie_rows = [int(t) for t in toks if np.any(q_gpu[t] != ref["q"][t])]
         ref["Y"][tie_rows] = _reference_rows_on_gpu_codes(L, ref, q_gpu, tie_rows)
-    err = Hp.row_rel_l2(Yh[toks], ref["Y"][toks])
+    if cfg.h_bits:
+        err = _check_had_output(L, ref, mid, Yh, toks, mid["Q"].cpu().numpy())
+    else:
+        err = Hp.row_rel_l2(Yh[toks], ref["Y"][toks])
     counts = np.diff(ref["offsets"])
     _say(f"  {name}: redrawn={L.redrawn_rows} tie codes={n_tie} sampled rows={toks.size} "
          f"max row rel L2={err.max():.3e} expert load min/mean/max={counts.min()}/{counts.mean():.1f}/{counts.max()}")
-    if cfg.h_bits:
-        assert err.max() <= HAD_END_TO_END_TOL
-        err = Hp.row_rel_l2(Yh[toks], _had_reference_output(L, ref, mid, toks))
-        _say(f"  against the oracle on the GPU's codes of the rotated intermediate: max row rel L2={err.max():.3e}")
     assert err.max() <= OUT_TOL
     if tile_rows and not cfg.h_bits:
         # stage a7 in place: the expert outputs of every sorted row that belongs to a checked token

@@ -555,6 +555,47 @@ def test_online_hadamard_expert_and_layer_consistency(h_bits):
     assert out["hq_sorted"].shape == (cfg.T * cfg.top_k, cfg.I) and np.abs(out["hq_sorted"]).max() == qmax
 
 
+@pytest.mark.parametrize("h_bits", [4, 8])
+def test_online_hadamard_expert_against_a_dense_ffn_with_the_quantizer_bound(h_bits):
+    """The h_bits branch of expert_ffn as a whole, against quantities built WITHOUT the oracle's Hadamard,
+    quantizer or decode routines: SciPy's Hadamard matrix, a loop-decoded dense down matrix and plain matmuls.
+    With h' = h H / sqrt(I) exact, every de-quantized code is within s/2 of h'_i (s = max|h'| / qmax), so
+    |o[n] - sum_i W[n,i] h'_i| <= (s/2) sum_i |W[n,i]|; the arg-max element is represented exactly, the bound is
+    not vacuous (the rounding really happens), and the variant differs from the plain FFN on the same weights
+    (the rotation really is applied in front of the down projection)."""
+    import scipy.linalg
+    cfg = synth.small_variant(synth.CONFIGS["tiny"], T=4, H=64, I=128, E=2, top_k=1, outlier_channels=(3, 41))   # I a power of two
+    L = synth.make_layer(cfg)
+    rng = np.random.default_rng(99)
+    a = rng.standard_normal((5, cfg.H))
+    res = O.expert_ffn(a, L.experts[1], h_bits)
+
+    def dense(pair):   # Eq. W_c by loops: row n, weight j -> centroid table entry of its 4-bit index
+        idx, cent = pair
+        c = synth.bf16_bits_to_f32(cent).astype(np.float64)
+        W = np.empty((idx.shape[0], idx.shape[1] * 2))
+        for n in range(idx.shape[0]):
+            for j in range(idx.shape[1]):
+                W[n, 2 * j], W[n, 2 * j + 1] = c[n, idx[n, j] & 15], c[n, idx[n, j] >> 4]
+        return W
+    Wg, Wu, Wd = dense(L.experts[1]["gate"]), dense(L.experts[1]["up"]), dense(L.experts[1]["down"])
+    g, u = a @ Wg.T, a @ Wu.T
+    h = g / (1.0 + np.exp(-g)) * u
+    hr = h @ scipy.linalg.hadamard(cfg.I).astype(np.float64) / math.sqrt(cfg.I)
+    o_exact = hr @ Wd.T
+    qmax = 2 ** (h_bits - 1) - 1
+    s = np.abs(hr).max(axis=1) / qmax
+    bound = 0.5 * s[:, None] * np.abs(Wd).sum(axis=1)[None, :]
+    dev = np.abs(res["o"] - o_exact)
+    assert np.all(dev <= bound * (1 + 1e-9) + 1e-12)
+    assert dev.max() > 1e-3 * bound.max()                       # the second quantizer is really there
+    assert np.allclose(res["hs"], s, rtol=1e-12)
+    assert np.all(np.abs(res["hs"][:, None] * res["hq"] - hr) <= 0.5 * s[:, None] * (1 + 1e-9))
+    assert np.array_equal(np.abs(res["hq"]).max(axis=1), np.full(5, qmax))
+    # without the rotation the same weights give something else entirely
+    assert np.abs(res["o"] - h @ Wd.T).max() > 2 * bound.max()
+
+
 def test_generator_properties():
     cfg = synth.CONFIGS["tiny"]
     L = synth.make_layer(cfg)
