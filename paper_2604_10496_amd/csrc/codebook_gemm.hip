@@ -39,7 +39,10 @@ namespace {
 constexpr int kSmallMaxRows = CQ_SMALL_MAX_ROWS;  // groups with more rows go to the large-tile kernel
 constexpr int kTableBytes = 65536;   // 256 entries x 64 row slots x 4 bytes
 constexpr int kSlabBytes = 65536;    // activation slab
-constexpr int kListedWorkgroups = 512;  // grid of a launch that runs off the device-built group list
+#ifndef CQ_LISTED_WGS
+#define CQ_LISTED_WGS 512
+#endif
+constexpr int kListedWorkgroups = CQ_LISTED_WGS;  // grid of a launch that runs off the device-built group list
 constexpr int kRedBytes = 32768;     // K partials of up to 16 token columns: 8 wavefronts x 16 registers x 64 lanes
 #ifndef CQ_GEMM_WAVES
 #define CQ_GEMM_WAVES 8
