@@ -255,15 +255,20 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   // before the barrier that ends unit u-1.
   // Ring slot hs % HD serves half step hs = 2q + row block (one 16-byte load per lane) and is refilled with
   // half step hs + HD, of this unit or of the next one, as soon as step q's lookups are issued.
-  auto run_units_pipe = [&]() {
+  auto run_units_pipe = [&](auto wide_tag) {
+    constexpr bool WIDE = decltype(wide_tag)::value;   // 9..16 tokens: see below
     constexpr int Q = QS > 0 ? QS : 1;
     constexpr int HD = pipe_ring_depth(Q);
     constexpr int TB0 = Q / 2;            // the next unit's table is written during steps TB0 .. Q-1
     const int i16 = lane & 15, g4 = lane >> 4;
-    const bool tok = (i16 & 7) < Me;      // this lane holds activations of a real token
+    const int tcol = WIDE ? i16 : (i16 & 7);   // token column whose activations this lane holds
+    const bool tok = tcol < Me;             // ... a real token
     const bool grouped = p.prepacked != 0;
     constexpr uint32_t kRed = 2 * kTableBytes;   // partial buffers: [2][wave][16 registers][32 columns] floats
-    const uint32_t slot = (uint32_t)(g4 * 8 + (i16 & 7));
+    const uint32_t slot = WIDE ? (uint32_t)lane : (uint32_t)(g4 * 8 + (i16 & 7));
+    constexpr uint32_t kRegStride = WIDE ? 256u : 128u;    // bytes between two accumulator registers' partials
+    constexpr uint32_t kWaveStride = 16u * kRegStride;     // ... between two wavefronts'
+    const bool pcol = WIDE || i16 < 8;                     // this lane's output column carries partial sums
     // ring loads: uniform base (unit, K step, row block) + 32-bit lane offset
     const uint32_t loff = p.prepacked ? (uint32_t)lane * 16u : (uint32_t)r32 * (uint32_t)rowbytes + (uint32_t)g2 * 16u;
     const size_t rb1 = 32 * rowbytes;            // the unit's second block of 32 rows
@@ -318,28 +323,34 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     float sc16 = 1.f;
     size_t arow = 0;
     if (tok) {
-      const int m = m0 + (i16 & 7);
+      const int m = m0 + tcol;
       const size_t src = p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
       arow = src * K;
       if (p.row_scale) sc16 = p.row_scale[src];
     }
-    // B fragments of step q: both K halves in ONE register set -- lanes of columns 0..7 hold the first half's
+    // B fragments of step q (up to 8 tokens): both K halves in ONE register set -- lanes of columns 0..7 hold the first half's
     // fragment of their token, lanes of columns 8..15 the second half's fragment of token column - 8 (the
     // matrix cores' output columns 8..15 are never stored, so what their B columns hold does not matter);
     // a rotation by 8 inside each row of 16 lanes brings the second half into place.
-    cq_v4u breg[Q];
+    // With 9..16 tokens every column is real: one register set per K half, no rotation.
+    constexpr int NB = WIDE ? 2 : 1;
+    cq_v4u breg[Q][NB];
     {
-      ActRaw raw[Q];
+      ActRaw raw[Q][NB];
 #pragma unroll
-      for (int q = 0; q < Q; ++q) {
-        const int chunk = (wave + NW * q) * 8 + (g4 & 1) + 4 * (g4 >> 1) + 2 * (i16 >> 3);
-        raw[q] = act_load8<AK>(p.A, arow + (size_t)sb * 64 + (size_t)chunk * 8);
-      }
+      for (int q = 0; q < Q; ++q)
 #pragma unroll
-      for (int q = 0; q < Q; ++q) {
-        const uint4 v = tok ? act_pack8<AK>(raw[q], grouped) : make_uint4(0u, 0u, 0u, 0u);
-        breg[q] = cq_v4u{v.x, v.y, v.z, v.w};
-      }
+        for (int c = 0; c < NB; ++c) {
+          const int chunk = (wave + NW * q) * 8 + (g4 & 1) + 4 * (g4 >> 1) + 2 * (WIDE ? c : (i16 >> 3));
+          raw[q][c] = act_load8<AK>(p.A, arow + (size_t)sb * 64 + (size_t)chunk * 8);
+        }
+#pragma unroll
+      for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+          const uint4 v = tok ? act_pack8<AK>(raw[q][c], grouped) : make_uint4(0u, 0u, 0u, 0u);
+          breg[q][c] = cq_v4u{v.x, v.y, v.z, v.w};
+        }
     }
     cent_f16();
     table_part((uint32_t)(wave * 8192 + lane * 4), 0, 32);
@@ -348,17 +359,18 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     // finish of a unit: this wavefront adds up accumulator registers 2*wave and 2*wave+1 (a gate/up pair of
     // rows) of all wavefronts' partials in buffer pb, in wavefront order
     auto finish = [&](const int uu, const uint32_t pb) {
-      if (i16 < 8) {
-        const uint32_t rb0 = kRed + pb * 16384u + (uint32_t)(2 * wave) * 128u + slot * 4u;
+      if (pcol) {
+        const uint32_t rb0 = kRed + pb * 16384u + (uint32_t)(2 * wave) * kRegStride + slot * 4u;
         float val[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-          float sum = __uint_as_float(lds_read_u32(rb0 + (uint32_t)(i * 128)));
+          float sum = __uint_as_float(lds_read_u32(rb0 + (uint32_t)i * kRegStride));
 #pragma unroll
-          for (int w = 1; w < NW; ++w) sum += __uint_as_float(lds_read_u32(rb0 + (uint32_t)(w * 2048 + i * 128)));
+          for (int w = 1; w < NW; ++w)
+            sum += __uint_as_float(lds_read_u32(rb0 + (uint32_t)w * kWaveStride + (uint32_t)i * kRegStride));
           val[i] = sum;
         }
-        if (tok) {
+        if (i16 < Me) {
           const int m = m0 + i16;
           const int r = 2 * wave;
           const int row = uu * 64 + (r >> 3) * 32 + ((r >> 2) & 1) * 16 + g4 * 4 + (r & 3);
@@ -411,8 +423,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
         else __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-          cq_v4u bv = breg[q];
-          if (c == 1) {
+          cq_v4u bv = breg[q][WIDE ? c : 0];
+          if (!WIDE && c == 1) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)   // row_ror:8 -- lane l of a row of 16 takes lane (l + 8) % 16
               bv[i] = (uint32_t)__builtin_amdgcn_update_dpp((int)bv[i], (int)bv[i], 0x128, 0xf, 0xf, false);
@@ -457,13 +469,17 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
           ring[(2 * q + rb) % HD] = load_stream(sp + loff);
         }
         // the previous unit's results (once), and this step's share of the next unit's table
-        if (q == 0 && ui > 0) finish(u - ustep, par ^ 1u);
+        if (q == 0 && ui > 0) finish(u - ustep, WIDE ? 0u : par ^ 1u);
         if (q == TB0) cent_f16();
         if (q >= TB0) table_part(tnext, ((q - TB0) * 32) / (Q - TB0), ((q - TB0 + 1) * 32) / (Q - TB0));
       }
       // this unit's K partials: register r = rb*8 + h*4 + v of wavefront w at [par][w][r][column]
-      if (i16 < 8) {
-        const uint32_t wbase = kRed + par * 16384u + (uint32_t)wave * 2048u + slot * 4u;
+      // (9..16 tokens: the 32 KiB hold ONE buffer, so a barrier separates these writes from the reads of the
+      // previous unit's partials at the top of this loop; it comes right before the unit's own barrier and
+      // costs little)
+      if constexpr (WIDE) __syncthreads();
+      if (pcol) {
+        const uint32_t wbase = kRed + (WIDE ? 0u : par * 16384u) + (uint32_t)wave * kWaveStride + slot * 4u;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -471,18 +487,19 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
 #pragma unroll
             for (int v = 0; v < 4; ++v)
               *reinterpret_cast<__attribute__((address_space(3))) float*>(
-                  (uintptr_t)(wbase + (uint32_t)((rb * 8 + h * 4 + v) * 128))) = acc[rb][h][v];
+                  (uintptr_t)(wbase + (uint32_t)(rb * 8 + h * 4 + v) * kRegStride)) = acc[rb][h][v];
       }
       __syncthreads();
       par ^= 1u;
     }
     __builtin_amdgcn_s_setprio(0);
-    finish(ufirst + (ucnt - 1) * ustep, par ^ 1u);
+    finish(ufirst + (ucnt - 1) * ustep, WIDE ? 0u : par ^ 1u);
   };
 #ifndef CQ_NO_PIPE
   if constexpr (QS > 0) {
-    if (Me <= 8 && nS == QS * NW) {   // every wavefront has exactly QS real steps
-      run_units_pipe();
+    if (Me <= 16 && nS == QS * NW) {   // every wavefront has exactly QS real steps
+      if (Me <= 8) run_units_pipe(std::false_type{});
+      else run_units_pipe(std::true_type{});
       return;
     }
   }

@@ -472,7 +472,7 @@ def test_gemm_streaming_pipeline_many_units(B, shape):
     gate/up-shaped (K = 4096: 8 K steps per wavefront, SiLU-gated, f16 output) and down-shaped (K = 14336 cut
     into four ranges of 7 steps per wavefront, f16 rows, partial sums added afterwards).  Exact integers."""
     rng = np.random.default_rng(77)
-    counts = [8, 1, 0, 5, 3, 8, 2, 7]
+    counts = [8, 12, 0, 5, 16, 1, 9, 7]      # up to 8 tokens and 9..16 tokens: the two forms of the pipelined loop
     G, M = len(counts), sum(counts)
     N, K = (6144, 4096) if shape == "gate_up" else (1024, 14336)
     idx = rng.integers(0, 256, size=(G, N, K // 2), dtype=np.uint8)
