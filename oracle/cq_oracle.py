@@ -182,7 +182,13 @@ def _tables(cent: np.ndarray, K: int, group_k: int) -> np.ndarray:
 
 
 def decode_weights(idx_packed: np.ndarray, cent_bits: np.ndarray, group_k: int = 0) -> np.ndarray:
-    """W_c [N, K] float64: every weight is the centroid its 4-bit index points at (Eq. W_c)."""
+    """W_c [N, K] float64: every weight is the centroid its 4-bit index points at (Eq. W_c).
+    Tables of 4 or 8 entries (the smaller budgets of the ablation on centroid budgets) mean 2- / 3-bit index
+    streams: those go through decode_weights_budget."""
+    n_cent = np.asarray(cent_bits).shape[-1]
+    if n_cent != N_CENTROIDS:
+        bits = {4: 2, 8: 3}[n_cent]
+        return decode_weights_budget(idx_packed, cent_bits, bits, np.asarray(idx_packed).shape[1] * 8 // bits, group_k)
     idx = unpack_indices(idx_packed).astype(np.int64)
     K = idx.shape[1]
     C = bf16_bits_to_f64(_tables(cent_bits, K, group_k))

@@ -53,6 +53,8 @@ class LayerConfig:
     group_k: int = 0     # > 0: block-wise centroid tables, one per group_k consecutive weights of a row
     r_hadamard: bool = False  # the rotation is the Hadamard matrix H/sqrt(H): no R is drawn (callers that
                               # need the dense matrix build it themselves and pass it as R_override)
+    index_bits: int = 4  # 2: the W2 budget of the ablation on centroid budgets -- idx [N, K/4] (2-bit stream,
+                         # weight j in bits 2(j%4).. of byte j/4), cent [N, 4]
 
     @property
     def seed(self) -> int:
@@ -86,6 +88,9 @@ CONFIGS: Dict[str, LayerConfig] = {
                     outlier_channels=(), n_outliers=8, outlier_scale=100.0, group_k=1024),
         LayerConfig("mixtral_prefill_blockwise", 2, E=8, top_k=2, S=0, H=4096, I=14336, T=4096, act_bits=4,
                     outlier_channels=(), n_outliers=8, outlier_scale=100.0, group_k=1024),
+        # the decode workload with the W2 budget (four centroids per row, 2-bit indices streamed as stored)
+        LayerConfig("mixtral_decode_w2", 1, E=8, top_k=2, S=0, H=4096, I=14336, T=16, act_bits=8,
+                    outlier_channels=(), n_outliers=8, outlier_scale=100.0, index_bits=2),
         # the decode workload with 4-bit activations (what the lookup formulation of the product needs)
         LayerConfig("mixtral_decode_a4", 1, E=8, top_k=2, S=0, H=4096, I=14336, T=16, act_bits=4,
                     outlier_channels=(), n_outliers=8, outlier_scale=100.0),
@@ -203,13 +208,16 @@ def make_layer(cfg: LayerConfig, with_experts: bool = True,
     bias = zipf_bias(cfg, rng) if cfg.zipf_s > 0 else None
     experts: List[Dict[str, Tuple[np.ndarray, np.ndarray]]] = []
     if with_experts:
+        per_byte = 8 // cfg.index_bits   # weights per index byte: uniform bytes are uniform indices at any width
         for _ in range(cfg.E + cfg.S):
-            gi = rng.integers(0, 256, size=(cfg.I, cfg.H // 2), dtype=np.uint8)
-            ui = rng.integers(0, 256, size=(cfg.I, cfg.H // 2), dtype=np.uint8)
-            di = rng.integers(0, 256, size=(cfg.H, cfg.I // 2), dtype=np.uint8)
+            gi = rng.integers(0, 256, size=(cfg.I, cfg.H // per_byte), dtype=np.uint8)
+            ui = rng.integers(0, 256, size=(cfg.I, cfg.H // per_byte), dtype=np.uint8)
+            di = rng.integers(0, 256, size=(cfg.H, cfg.I // per_byte), dtype=np.uint8)
             gc = draw_centroids(rng, cfg.I, n_blocks=n_blocks(cfg.H, cfg.group_k))
             uc = draw_centroids(rng, cfg.I, n_blocks=n_blocks(cfg.H, cfg.group_k))
             dc = draw_centroids(rng, cfg.H, n_blocks=n_blocks(cfg.I, cfg.group_k))
+            if cfg.index_bits == 2:   # four of the sixteen sorted draws, both ends included (the scaled outlier is an end)
+                gc, uc, dc = (np.ascontiguousarray(c[..., [0, 5, 10, 15]]) for c in (gc, uc, dc))
             experts.append({"gate": (gi, gc), "up": (ui, uc), "down": (di, dc)})
     return LayerInputs(cfg, X, channels, R, Wr, bias, experts)
 

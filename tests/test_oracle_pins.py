@@ -596,6 +596,40 @@ def test_online_hadamard_expert_against_a_dense_ffn_with_the_quantizer_bound(h_b
     assert np.abs(res["o"] - h @ Wd.T).max() > 2 * bound.max()
 
 
+def test_decode_weights_takes_the_smaller_budgets_by_table_width():
+    """Tables of four entries = the W2 budget, 2-bit indices as a little-endian bit stream: checked against
+    loops over bytes and bit fields, and through the layer generator's W2 variant (expert_ffn on such weights
+    equals the dense FFN on the loop-decoded matrices)."""
+    rng = np.random.default_rng(202)
+    N, K = 6, 32
+    packed = rng.integers(0, 256, size=(N, K // 4), dtype=np.uint8)
+    cent = synth.f32_to_bf16_bits(rng.standard_normal((N, 4)).astype(np.float32))
+    W = O.decode_weights(packed, cent)
+    c = synth.bf16_bits_to_f32(cent).astype(np.float64)
+    for n in range(N):
+        for j in range(K):
+            want = c[n, (int(packed[n, j // 4]) >> (2 * (j % 4))) & 3]
+            assert W[n, j] == want
+    cfg = synth.small_variant(synth.CONFIGS["tiny"], T=4, H=64, I=128, E=2, top_k=1, outlier_channels=(3, 41),
+                              index_bits=2)
+    L = synth.make_layer(cfg)
+    gi, gc = L.experts[0]["gate"]
+    assert gi.shape == (cfg.I, cfg.H // 4) and gc.shape == (cfg.I, 4) and np.all(np.diff(synth.bf16_bits_to_f32(gc), axis=1) >= 0)
+
+    def dense(pair):
+        idx, cb = pair
+        cc = synth.bf16_bits_to_f32(cb).astype(np.float64)
+        Wd = np.empty((idx.shape[0], idx.shape[1] * 4))
+        for n in range(idx.shape[0]):
+            for j in range(Wd.shape[1]):
+                Wd[n, j] = cc[n, (int(idx[n, j // 4]) >> (2 * (j % 4))) & 3]
+        return Wd
+    a = rng.standard_normal((3, cfg.H))
+    g, u = a @ dense(L.experts[0]["gate"]).T, a @ dense(L.experts[0]["up"]).T
+    want = (g / (1.0 + np.exp(-g)) * u) @ dense(L.experts[0]["down"]).T
+    assert np.allclose(O.expert_ffn(a, L.experts[0])["o"], want, rtol=1e-12, atol=1e-12)
+
+
 def test_generator_properties():
     cfg = synth.CONFIGS["tiny"]
     L = synth.make_layer(cfg)
