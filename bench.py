@@ -172,8 +172,9 @@ def measure(B, torch, synth, name, steps, warmup, n_stage):
     # packed indices + centroid tables (one 32-byte table per row, or per group of group_k weights of a row)
     g = getattr(cfg, "group_k", 0)
     gu_tables, dn_tables = synth.n_blocks(cfg.H, g) or 1, synth.n_blocks(cfg.I, g) or 1
-    gu_bytes = active * (2 * cfg.I * cfg.H // 2 + 2 * cfg.I * 32 * gu_tables)
-    dn_bytes = active * (cfg.H * cfg.I // 2 + cfg.H * 32 * dn_tables)
+    bits = getattr(cfg, "index_bits", 4)              # index bits per weight; a table has 2^bits bf16 entries
+    gu_bytes = active * (2 * cfg.I * cfg.H * bits // 8 + 2 * cfg.I * (2 << bits) * gu_tables)
+    dn_bytes = active * (cfg.H * cfg.I * bits // 8 + cfg.H * (2 << bits) * dn_tables)
     gu_flops = rows * 2.0 * (2 * cfg.I) * cfg.H
     dn_flops = rows * 2.0 * cfg.H * cfg.I
     flop_per_byte = (gu_flops + dn_flops) / (gu_bytes + dn_bytes)
@@ -183,7 +184,8 @@ def measure(B, torch, synth, name, steps, warmup, n_stage):
     if hbm_bound:
         ach = gu_bytes / gu_s / 1e9
         # (block-wise tables are decoded by the large-tile kernel, at decode sizes by its narrow-tile variant)
-        kern = "gemm_narrow_kernel" if g and rows <= 64 else "gemm_large_kernel" if g else "gemm_small_kernel"
+        kern = ("gemm_w2_kernel" if bits == 2 else "gemm_narrow_kernel" if g and rows <= 64
+                else "gemm_large_kernel" if g else "gemm_small_kernel")
         roofline = {"bound": "hbm", "kernel": f"{kern} (gate/up codebook product + SwiGLU)",
                     "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
                     "frac_at_median_duration": gu_bytes / gu_med / 1e9 / HBM_PEAK_GBPS,
@@ -206,7 +208,7 @@ def measure(B, torch, synth, name, steps, warmup, n_stage):
         "ms_per_step_median": float(np.median(per_step)), "ms_per_step_min": float(per_step.min()),
         "steps": steps, "warmup": warmup,
         "config": {"workload": f"{cfg.name} (E={cfg.E} top-{cfg.top_k} S={cfg.S} H={cfg.H} I={cfg.I} T={cfg.T} "
-                               f"A{cfg.act_bits}W4, 16 bf16 centroids per "
+                               f"A{cfg.act_bits}W{bits}, {1 << bits} bf16 centroids per "
                                + (f"group of {g} weights of a row (block-wise)" if g else "weight row")
                                + (", Hadamard rotation" if getattr(cfg, "r_hadamard", False) else "")
                                + (f", online Hadamard + A{cfg.h_bits} in front of the down projection)"

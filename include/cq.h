@@ -75,6 +75,17 @@ enum { CQ_OUT_F32 = 0, CQ_OUT_F16 = 1 };
  *             [G, N, ceil(K/g), 16] and weight k of a row is decoded through table k / g (the last group
  *             is shorter when g does not divide K).  g must be a multiple of 512 and N of 256
  *             (other values: CQ_ERR_UNSUPPORTED).
+ *   index_bits 0 or 4: the format above.  2: the smallest budget of the ablation on centroid budgets (W2, four
+ *             centroids per row) streamed as stored, at half the bytes: idx is [G, N, K/4] bytes, the indices
+ *             of a row as one little-endian bit stream (weight j in bits 2(j%4), 2(j%4)+1 of byte j/4), cent is
+ *             [G, N, 4] bf16.  Prepacked copy (cq_prepack; same byte count): rows 32 at a time, K 128 weights
+ *             at a time; the 1 KiB tile of row block rb and K step s is at ((rb*(K/128) + s) * 1024) and holds,
+ *             for l = 0..63, the 16 canonical bytes of row rb*32 + l%32, byte columns s*32 + (l/32)*16 .. +15,
+ *             at l*16, unchanged.  Taken by cq_codebook_grouped_gemm and cq_moe_forward for group_k = 0, K a
+ *             multiple of 4096 or of 7168 (with the SiLU-gated epilogue: K = 4096 or 7168) and int8-code, f16
+ *             or bf16 operands; anything else returns CQ_ERR_UNSUPPORTED (expand such weights once with
+ *             cq_expand_centroid_budget).  Meant for decode-sized groups: groups of more than 8 rows are
+ *             processed 8 rows at a time, re-reading the indices.
  */
 typedef struct {
   const uint8_t* idx;
@@ -82,6 +93,7 @@ typedef struct {
   const void* prepacked;
   int G, N, K;
   int group_k;
+  int index_bits;
 } cq_codebook_weights;
 
 /* One MoE expert layer.  Groups 0..E-1 are routed experts, E..E+S-1 always-on shared experts. */
@@ -188,7 +200,7 @@ cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W,
  *   idx4_out  [G, N, K/2] canonical 4-bit bytes;  cent16_out [G, N, tables_per_row, 16]: entries >= 2^bits,
  *             which no index addresses, repeat the table's last entry.
  * The products then run on the 4-bit kernels: the results are those of the smaller budget exactly, the bytes
- * streamed per weight are those of W4 (kernels that read the 2-/3-bit stream directly are not built).
+ * streamed per weight are those of W4.  (W2 weights can also be streamed as stored: cq_codebook_weights.index_bits.)
  */
 cq_status cq_expand_centroid_budget(const uint8_t* idx_bits, const uint16_t* cent_bits, int bits, int G, int N, int K,
                                     int tables_per_row, uint8_t* idx4_out, uint16_t* cent16_out, cq_stream stream);
@@ -271,7 +283,8 @@ cq_status cq_prepack(const cq_codebook_weights* W, void* dst, size_t dst_bytes, 
 
 /*
  * Test hook for the bit-exact decode check: writes W_c of group g as bf16 bit patterns [N, K],
- * reading `prepacked` if present, else `idx` (Eq. W_c).
+ * reading `prepacked` if present, else `idx` (Eq. W_c); index_bits = 2 weights are decoded through their
+ * 4-entry tables.
  */
 cq_status cq_decode_dense(const cq_codebook_weights* W, int g, uint16_t* Wc_bf16, cq_stream stream);
 

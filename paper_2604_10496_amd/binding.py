@@ -32,7 +32,8 @@ EXPORTS = [
 
 class CodebookWeights(ctypes.Structure):
     _fields_ = [("idx", ctypes.c_void_p), ("cent", ctypes.c_void_p), ("prepacked", ctypes.c_void_p),
-                ("G", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int), ("group_k", ctypes.c_int)]
+                ("G", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int), ("group_k", ctypes.c_int),
+                ("index_bits", ctypes.c_int)]
 
 
 class Layer(ctypes.Structure):
@@ -161,9 +162,11 @@ def _ws(nbytes: int):
 class DeviceCodebook:
     """Device-resident [G, N, K/2] indices + [G, N, 16] bf16 tables, optionally prepacked.
 
-    group_k = g > 0: block-wise tables, cent is [G, N, ceil(K/g), 16]."""
+    group_k = g > 0: block-wise tables, cent is [G, N, ceil(K/g), 16].
+    index_bits = 2: the W2 budget streamed as stored, idx [G, N, K/4] (2-bit stream), cent [G, N, 4]."""
 
-    def __init__(self, idx, cent, prepack: bool = True, keep_canonical: bool = True, group_k: int = 0):
+    def __init__(self, idx, cent, prepack: bool = True, keep_canonical: bool = True, group_k: int = 0,
+                 index_bits: int = 4):
         torch = _torch()
         import numpy as np
         if isinstance(idx, np.ndarray):
@@ -171,9 +174,13 @@ class DeviceCodebook:
         if isinstance(cent, np.ndarray):
             cent = torch.from_numpy(np.ascontiguousarray(cent).view(np.int16))
         assert idx.dtype == torch.uint8 and idx.dim() == 3 and cent.dtype == torch.int16
-        self.G, self.N, self.K = int(idx.shape[0]), int(idx.shape[1]), int(idx.shape[2]) * 2
+        self.index_bits = int(index_bits)
+        per_byte = 4 if self.index_bits == 2 else 2
+        self.G, self.N, self.K = int(idx.shape[0]), int(idx.shape[1]), int(idx.shape[2]) * per_byte
         self.group_k = int(group_k)
-        if self.group_k > 0:
+        if self.index_bits == 2:
+            assert self.group_k == 0 and tuple(cent.shape) == (self.G, self.N, 4)
+        elif self.group_k > 0:
             assert tuple(cent.shape) == (self.G, self.N, -(-self.K // self.group_k), 16)
         else:
             assert tuple(cent.shape) == (self.G, self.N, 16)
@@ -187,7 +194,8 @@ class DeviceCodebook:
 
     def struct(self, use_prepacked: bool = True) -> CodebookWeights:
         pre = self.prepacked if use_prepacked else None
-        return CodebookWeights(_ptr(self.idx), _ptr(self.cent), _ptr(pre), self.G, self.N, self.K, self.group_k)
+        return CodebookWeights(_ptr(self.idx), _ptr(self.cent), _ptr(pre), self.G, self.N, self.K, self.group_k,
+                               self.index_bits)
 
 
 def cq_prepack(W: DeviceCodebook):
@@ -464,8 +472,9 @@ def device_layer_from_inputs(inputs, use_prepacked: bool = True) -> DeviceLayer:
     from . import synth
     st = synth.stack_experts(inputs)
     g = getattr(inputs.cfg, "group_k", 0)
-    gu = DeviceCodebook(st["gate_up_idx"], st["gate_up_cent"], prepack=use_prepacked, group_k=g)
-    dn = DeviceCodebook(st["down_idx"], st["down_cent"], prepack=use_prepacked, group_k=g)
+    bits = getattr(inputs.cfg, "index_bits", 4)
+    gu = DeviceCodebook(st["gate_up_idx"], st["gate_up_cent"], prepack=use_prepacked, group_k=g, index_bits=bits)
+    dn = DeviceCodebook(st["down_idx"], st["down_cent"], prepack=use_prepacked, group_k=g, index_bits=bits)
     return DeviceLayer(inputs.cfg, inputs.R, inputs.Wr, inputs.bias, gu, dn, use_prepacked)
 
 

@@ -49,8 +49,9 @@ __device__ __forceinline__ uint32_t regroup_nibbles(uint32_t d) {
   return x | (y << 4);
 }
 
+// (regroup = 0: the bytes are moved unchanged -- the 2-bit stream, whose rows of K/4 bytes are passed as K/2 "weights")
 __global__ __launch_bounds__(256) void prepack_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                                      size_t n_rows, int K) {
+                                                      size_t n_rows, int K, int regroup) {
   const size_t n16 = n_rows * (size_t)(K / 32);  // 16-byte pieces in total
   const int steps = K / 64;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
@@ -61,7 +62,8 @@ __global__ __launch_bounds__(256) void prepack_kernel(const uint4* __restrict__ 
     const size_t row = rb * 32 + (l & 31);
     const size_t piece = (size_t)s * 2 + (l >> 5);  // 16-byte piece inside the row
     const uint4 v = src[row * (size_t)(K / 32) + piece];
-    dst[i] = make_uint4(regroup_nibbles(v.x), regroup_nibbles(v.y), regroup_nibbles(v.z), regroup_nibbles(v.w));
+    dst[i] = regroup ? make_uint4(regroup_nibbles(v.x), regroup_nibbles(v.y), regroup_nibbles(v.z), regroup_nibbles(v.w))
+                     : v;
   }
 }
 
@@ -89,6 +91,29 @@ __global__ __launch_bounds__(256) void decode_dense_kernel(const uint8_t* __rest
     }
     out[n * K + 2 * bc] = c[i0];
     out[n * K + 2 * bc + 1] = c[i1];
+  }
+}
+
+// index_bits = 2: W_c[n, k] = C[n, (byte k/4 of row n >> 2(k%4)) & 3], from canonical bytes or from the prepacked
+// tiles (32 rows x 128 weights: lane l = row%32 + 32 * ((k%128)/64) holds 16 bytes at l*16); one thread per byte
+__global__ __launch_bounds__(256) void decode_dense_w2_kernel(const uint8_t* __restrict__ idx, int prepacked,
+                                                              const uint16_t* __restrict__ cent, int N, int K,
+                                                              uint16_t* __restrict__ out) {
+  const size_t rowbytes = (size_t)K / 4, total = (size_t)N * rowbytes;
+  const int steps = K / 128;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t n = i / rowbytes;
+    const int bc = (int)(i - n * rowbytes);   // canonical byte column: weights 4 bc .. 4 bc + 3
+    uint32_t b;
+    if (prepacked) {
+      const int s = bc >> 5, g = (bc >> 4) & 1, within = bc & 15;
+      b = idx[(((n >> 5) * steps + s) * 64 + g * 32 + (n & 31)) * 16 + within];
+    } else {
+      b = idx[i];
+    }
+    const uint16_t* c = cent + n * 4;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) out[n * K + 4 * (size_t)bc + w] = c[(b >> (2 * w)) & 3u];
   }
 }
 
@@ -217,18 +242,21 @@ extern "C" cq_status cq_combine(const float* O, const float* topk_w, const int32
 
 extern "C" size_t cq_prepack_bytes(const cq_codebook_weights* W) {
   if (!W || W->G <= 0 || W->N <= 0 || W->K <= 0) return 0;
-  return (size_t)W->G * W->N * (W->K / 2);
+  return (size_t)W->G * W->N * (W->K / (cq_is_w2(W) ? 4 : 2));
 }
 
 extern "C" cq_status cq_prepack(const cq_codebook_weights* W, void* dst, size_t dst_bytes, cq_stream stream) {
   if (!W || !W->idx || !dst) return CQ_ERR_NULL;
   if (W->G <= 0 || W->N <= 0 || W->K <= 0 || W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;
+  if (W->index_bits != 0 && W->index_bits != 4 && W->index_bits != 2) return CQ_ERR_UNSUPPORTED;
+  if (cq_is_w2(W) && W->K % 128 != 0) return CQ_ERR_SHAPE;
   if (dst_bytes < cq_prepack_bytes(W)) return CQ_ERR_WORKSPACE;
   const size_t rows = (size_t)W->G * W->N;
-  const size_t n16 = rows * (W->K / 32);
+  const int k_eff = cq_is_w2(W) ? W->K / 2 : W->K;   // a row of K/4 bytes tiles like a 4-bit row of K/2 weights
+  const size_t n16 = rows * (k_eff / 32);
   const unsigned grid = (unsigned)((n16 + 255) / 256 < 65536 ? (n16 + 255) / 256 : 65536);
   hipLaunchKernelGGL(prepack_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)W->idx,
-                     (uint4*)dst, rows, W->K);
+                     (uint4*)dst, rows, k_eff, cq_is_w2(W) ? 0 : 1);
   return cq_check_launch();
 }
 
@@ -252,6 +280,15 @@ extern "C" cq_status cq_decode_dense(const cq_codebook_weights* W, int g, uint16
   if (!W || (!W->idx && !W->prepacked) || !W->cent || !Wc_bf16) return CQ_ERR_NULL;
   if (W->G <= 0 || W->N <= 0 || W->K <= 0 || W->N % 64 != 0 || W->K % 64 != 0) return CQ_ERR_SHAPE;
   if (g < 0 || g >= W->G || W->group_k < 0 || W->group_k % 2 != 0) return CQ_ERR_SHAPE;
+  if (cq_is_w2(W)) {
+    if (W->K % 128 != 0 || cq_tables_per_row(W) > 1) return CQ_ERR_UNSUPPORTED;
+    const size_t gb = (size_t)W->N * (W->K / 4);
+    const uint8_t* src2 = (W->prepacked ? (const uint8_t*)W->prepacked : W->idx) + (size_t)g * gb;
+    const unsigned grid2 = (unsigned)((gb + 255) / 256 < 65536 ? (gb + 255) / 256 : 65536);
+    hipLaunchKernelGGL(decode_dense_w2_kernel, dim3(grid2), dim3(256), 0, (hipStream_t)stream, src2,
+                       W->prepacked ? 1 : 0, W->cent + (size_t)g * W->N * 4, W->N, W->K, Wc_bf16);
+    return cq_check_launch();
+  }
   const int nblk = cq_tables_per_row(W);
   const size_t gbytes = (size_t)W->N * (W->K / 2);
   const uint8_t* src = (W->prepacked ? (const uint8_t*)W->prepacked : W->idx) + (size_t)g * gbytes;

@@ -84,6 +84,14 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
 size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue);
 // K split of a product: ksplit ranges of ksteps K steps (of 64) each; 1 and K/64 when K is not split
 void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue, int* ksplit, int* ksteps);
+// W2 weights streamed as stored (index_bits = 2): quadruple tables in LDS, decode-sized groups
+static inline bool cq_is_w2(const cq_codebook_weights* W) { return W->index_bits == 2; }
+int cq_gemm_w2_range_steps(int K);   // K steps (of 128) per K range, 0 if K cannot be split that way
+bool cq_gemm_w2_supported(const cq_codebook_weights* W, int a_kind, int epilogue);
+size_t cq_gemm_w2_partials_bytes(const cq_codebook_weights* W, int M_total);
+cq_status cq_gemm_w2_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
+                            const int32_t* row_gather, const int32_t* group_offsets, int M_total, int epilogue,
+                            void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left);
 // weighted combine over `slices` partial copies of O that are `slice_stride` floats apart
 cq_status cq_combine_launch(const float* O, int slices, size_t slice_stride, const float* topk_w,
                             const int32_t* inv_perm, int T, int H, int top_k, int n_shared, float* Y, hipStream_t s);

@@ -41,6 +41,13 @@ cq_status validate_layer(const cq_layer* L, int T) {
   if (L->gate_up.G != G || L->gate_up.N != 2 * L->I || L->gate_up.K != L->H) return CQ_ERR_SHAPE;
   if (L->down.G != G || L->down.N != L->H || L->down.K != L->I) return CQ_ERR_SHAPE;
   if (L->gate_up.group_k < 0 || L->down.group_k < 0) return CQ_ERR_SHAPE;
+  for (const cq_codebook_weights* W : {&L->gate_up, &L->down})
+    if (W->index_bits != 0 && W->index_bits != 4 && W->index_bits != 2) return CQ_ERR_UNSUPPORTED;
+  // W2 weights streamed as stored: int8 codes into the SiLU-gated gate/up product, f16 (or, in the online-Hadamard
+  // variant, int8 codes) into the plain down product
+  if (cq_is_w2(&L->gate_up) && !cq_gemm_w2_supported(&L->gate_up, CQ_A_INT8_CODES, CQ_EPI_SWIGLU)) return CQ_ERR_UNSUPPORTED;
+  if (cq_is_w2(&L->down) && !cq_gemm_w2_supported(&L->down, L->h_bits ? CQ_A_INT8_CODES : CQ_A_F16, CQ_EPI_NONE))
+    return CQ_ERR_UNSUPPORTED;
   if ((cq_tables_per_row(&L->gate_up) > 1 && !cq_gemm_large_supported(&L->gate_up)) ||
       (cq_tables_per_row(&L->down) > 1 && !cq_gemm_large_supported(&L->down)))
     return CQ_ERR_UNSUPPORTED;

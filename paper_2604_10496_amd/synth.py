@@ -216,8 +216,11 @@ def make_layer(cfg: LayerConfig, with_experts: bool = True,
             gc = draw_centroids(rng, cfg.I, n_blocks=n_blocks(cfg.H, cfg.group_k))
             uc = draw_centroids(rng, cfg.I, n_blocks=n_blocks(cfg.H, cfg.group_k))
             dc = draw_centroids(rng, cfg.H, n_blocks=n_blocks(cfg.I, cfg.group_k))
-            if cfg.index_bits == 2:   # four of the sixteen sorted draws, both ends included (the scaled outlier is an end)
-                gc, uc, dc = (np.ascontiguousarray(c[..., [0, 5, 10, 15]]) for c in (gc, uc, dc))
+            if cfg.index_bits == 2:
+                # four of the sixteen sorted draws, the two ends left out: the x20 outlier of 1 % of the rows is always
+                # an end, and with uniform 2-bit indices a quarter of such a row's weights would carry it -- the
+                # intermediate h would leave the f16 range (a real 4-centroid clustering has no such centroid)
+                gc, uc, dc = (np.ascontiguousarray(c[..., [1, 5, 10, 14]]) for c in (gc, uc, dc))
             experts.append({"gate": (gi, gc), "up": (ui, uc), "down": (di, dc)})
     return LayerInputs(cfg, X, channels, R, Wr, bias, experts)
 

@@ -647,6 +647,114 @@ def test_smaller_centroid_budgets(B, bits, N, K, g, counts):
         assert Hp.row_rel_l2(out[rows], ref).max() < 2e-5
 
 
+# ---------------------------------------------------------------------------------------------
+# the W2 budget streamed as stored (index_bits = 2): quadruple tables in LDS
+# ---------------------------------------------------------------------------------------------
+def _w2_weights(rng, G, N, K, integer=True):
+    packed = rng.integers(0, 256, size=(G, N, K // 4), dtype=np.uint8)
+    if integer:   # four small integers per row, a different set in every row: exact in bf16 and f16
+        base = np.array([-3.0, -1.0, 2.0, 5.0], dtype=np.float32)
+        cent = synth.f32_to_bf16_bits(base[None, None, :] * rng.integers(1, 4, size=(G, N, 1)).astype(np.float32))
+    else:
+        cent = np.stack([synth.draw_centroids(rng, N)[:, [0, 5, 10, 15]] for _ in range(G)])
+    return packed, np.ascontiguousarray(cent)
+
+
+@pytest.mark.parametrize("prepacked", [True, False])
+@pytest.mark.parametrize("N,K", [(64, 4096), (192, 7168)])
+def test_decode_dense_w2_bit_exact(B, N, K, prepacked):
+    rng = np.random.default_rng(N + K)
+    packed, cent = _w2_weights(rng, 2, N, K, integer=False)
+    W = B.DeviceCodebook(packed, cent, index_bits=2)
+    for g in range(2):
+        got = B.cq_decode_dense(W, g, use_prepacked=prepacked).cpu().numpy().view(np.uint16)
+        want = O.decode_weights_budget(packed[g], cent[g], 2, K)
+        assert np.array_equal(synth.bf16_bits_to_f32(got).astype(np.float64), want)
+
+
+@pytest.mark.parametrize("prepacked", [True, False])
+@pytest.mark.parametrize("out_kind", ["f32", "f16"])
+@pytest.mark.parametrize("a_kind", ["int8", "f16", "bf16"])
+@pytest.mark.parametrize("N,K,counts", [(64, 4096, [1]), (192, 4096, [8, 0, 3, 9, 20]), (128, 14336, [5, 0, 8]),
+                                        (2048, 4096, [2, 7, 1, 8, 4, 6, 3, 5]),        # two units per workgroup and more
+                                        (1024, 14336, [8, 3, 1, 6, 2, 7, 5, 4])])
+def test_gemm_w2_integer_centroids_exact(B, N, K, counts, a_kind, out_kind, prepacked):
+    """Integer centroids, integer activations, power-of-two scales: exact in any summation order.  K = 4096 runs 4
+    K steps per wavefront, K = 14336 two ranges of 7 (partial sums added afterwards); groups of more than 8 rows
+    are processed in blocks of 8."""
+    if N >= 1024 and (a_kind == "bf16" or out_kind == "f16" or not prepacked):
+        pytest.skip("large shapes: one operand / output / index layout each")
+    rng = np.random.default_rng(N + K + len(counts))
+    G, M = len(counts), int(sum(counts))
+    packed, cent = _w2_weights(rng, G, N, K)
+    acts = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    gather = rng.permutation(M).astype(np.int32)
+    scale = (2.0 ** -rng.integers(4, 8, size=M)).astype(np.float32)
+    off = _group_offsets(counts)
+    W = B.DeviceCodebook(packed, cent, index_bits=2)
+    if a_kind == "int8":
+        A, kind = _dev(acts), B.CQ_A_INT8_CODES
+    elif a_kind == "f16":
+        A, kind = _dev(acts.astype(np.float16)), B.CQ_A_F16
+    else:
+        A, kind = _dev(synth.f32_to_bf16_bits(acts.astype(np.float32)).view(np.int16)), B.CQ_A_BF16
+    _say(f"gemm W2 N={N} K={K} counts={counts} a={a_kind} out={out_kind} prepacked={prepacked}")
+    out = B.cq_codebook_grouped_gemm(W, A, kind, _dev(scale), _dev(gather), _dev(off), M, B.CQ_EPI_NONE,
+                                     B.CQ_OUT_F16 if out_kind == "f16" else B.CQ_OUT_F32,
+                                     use_prepacked=prepacked).cpu().numpy()
+    a = scale[gather, None].astype(np.float64) * acts[gather].astype(np.float64)
+    for g in range(G):
+        rows = slice(off[g], off[g + 1])
+        if rows.start == rows.stop:
+            continue
+        ref = a[rows] @ O.decode_weights_budget(packed[g], cent[g], 2, K).T
+        want = ref.astype(np.float16) if out_kind == "f16" else ref.astype(np.float32)
+        assert np.array_equal(out[rows], want), f"group {g}"
+
+
+@pytest.mark.parametrize("out_kind", ["f16", "f32"])
+@pytest.mark.parametrize("K", [4096, 7168])
+def test_gemm_w2_swiglu_epilogue(B, K, out_kind):
+    rng = np.random.default_rng(K)
+    I, counts = 160, [6, 0, 11, 1]
+    G, M = len(counts), sum(counts)
+    gate = [tuple(x[0] for x in _w2_weights(rng, 1, I, K, integer=False)) for _ in range(G)]
+    up = [tuple(x[0] for x in _w2_weights(rng, 1, I, K, integer=False)) for _ in range(G)]
+    fused = [synth.interleave_gate_up(gate[g], up[g]) for g in range(G)]
+    W = B.DeviceCodebook(np.stack([f[0] for f in fused]), np.stack([f[1] for f in fused]), index_bits=2)
+    codes = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    scale = rng.uniform(0.001, 0.02, size=M).astype(np.float32)
+    off = _group_offsets(counts)
+    out = B.cq_codebook_grouped_gemm(W, _dev(codes), B.CQ_A_INT8_CODES, _dev(scale), None, _dev(off), M,
+                                     B.CQ_EPI_SWIGLU, B.CQ_OUT_F16 if out_kind == "f16" else B.CQ_OUT_F32)
+    out = out.cpu().numpy().astype(np.float64)
+    assert out.shape == (M, I)
+    for g in range(G):
+        rows = slice(off[g], off[g + 1])
+        if rows.start == rows.stop:
+            continue
+        a = scale[rows, None].astype(np.float64) * codes[rows].astype(np.float64)
+        ref = O.silu(O.codebook_matmul(a, *gate[g])) * O.codebook_matmul(a, *up[g])
+        assert Hp.row_rel_l2(out[rows], ref).max() < (1e-3 if out_kind == "f16" else 2e-5)
+
+
+def test_gemm_w2_unsupported_shapes_are_refused(B):
+    rng = np.random.default_rng(3)
+    packed, cent = _w2_weights(rng, 1, 64, 2048)       # K = 2048: no range of 32 or 56 steps
+    W = B.DeviceCodebook(packed, cent, prepack=False, index_bits=2)
+    off = _dev(_group_offsets([2]))
+    with pytest.raises(B.CqError) as e:
+        B.cq_codebook_grouped_gemm(W, _dev(np.zeros((2, 2048), dtype=np.int8)), B.CQ_A_INT8_CODES, None, None, off, 2,
+                                   B.CQ_EPI_NONE, B.CQ_OUT_F32, use_prepacked=False)
+    assert e.value.status == 3
+    packed, cent = _w2_weights(rng, 1, 64, 8192)       # SiLU-gated product: the whole of K must be one range
+    W = B.DeviceCodebook(packed, cent, prepack=False, index_bits=2)
+    with pytest.raises(B.CqError) as e:
+        B.cq_codebook_grouped_gemm(W, _dev(np.zeros((2, 8192), dtype=np.int8)), B.CQ_A_INT8_CODES, None, None, off, 2,
+                                   B.CQ_EPI_SWIGLU, B.CQ_OUT_F32, use_prepacked=False)
+    assert e.value.status == 3
+
+
 # the lookup formulation (product tables in LDS, accumulate without multiplying)
 def test_gemm_lut_tiny_against_python_loops(B):
     """Against the oracle's own lookup formulation (pure-Python loops): tiny sizes."""
@@ -992,6 +1100,12 @@ def test_layer_blockwise(B, name, over):
     _check_layer(B, cfg, label=f"{name} block-wise {over}")
 
 
+def test_layer_w2_budget(B):
+    """A whole layer on W2 weights streamed as stored (gate/up K = 4096 in one range, down K = 7168 in one range)."""
+    cfg = synth.small_variant(synth.CONFIGS["mixtral_decode_w2"], H=4096, I=7168, E=4, T=12)
+    _check_layer(B, cfg, label="mixtral_decode_w2-reduced")
+
+
 def test_layer_without_prepack(B):
     cfg = synth.small_variant(synth.CONFIGS["tiny"], T=20)
     L = Hp.make_inputs(cfg)
@@ -1065,6 +1179,10 @@ def test_full_mixtral_decode(B):
 
 def test_full_mixtral_decode_online_hadamard(B):
     _full_size(B, "mixtral_decode_had", 16)
+
+
+def test_full_mixtral_decode_w2(B):
+    _full_size(B, "mixtral_decode_w2", 16)
 
 
 def test_full_mixtral_decode_blockwise(B):
