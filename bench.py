@@ -131,7 +131,26 @@ def yardsticks(B, torch, info):
     return read_gbps, mfma_tflops
 
 
-def measure(B, torch, synth, name, steps, warmup, n_stage):
+def prime(B, torch, info, seconds=0.1):
+    """Keeps the device busy with the two yardstick kernels (streaming read, matrix-core loop) for about
+    `seconds`, immediately before the warm-up steps: setting up a layer's inputs leaves the GPU idle for
+    seconds, and the first 10-20 ms after an idle phase run at the clocks of an idle device (measured: regions
+    of 20 decode steps after 5 warm-up steps went 0.184, 0.183, 0.170, 0.168 ms per step without this, and
+    0.159, 0.159, 0.158, 0.158 with it; priming with the layer itself gives the same).  The timed region is
+    meant to show a busy device."""
+    probe = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    probe.zero_()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            B.cq_stream_read(probe)
+        B.cq_mfma_loop(info["cu_count"] * 8, 100)
+        torch.cuda.synchronize()
+    del probe
+
+
+def measure(B, torch, synth, info, name, steps, warmup, n_stage):
     """W warm-up steps, exactly K timed steps of cq_moe_forward (inputs resident in HBM), then n_stage runs of
     the same launches with events at the stage boundaries.  Returns (result dict, layer inputs)."""
     cfg = synth.CONFIGS[name]
@@ -143,18 +162,22 @@ def measure(B, torch, synth, name, steps, warmup, n_stage):
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
+    prime(B, torch, info)
     for _ in range(warmup):
         B.cq_moe_forward(layer, X, Y)
     torch.cuda.synchronize()
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-    t0 = time.perf_counter()
-    marks[0].record()
-    for i in range(steps):
-        B.cq_moe_forward(layer, X, Y)
-        marks[i + 1].record()     # on the launch stream (torch's current stream); no host wait
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
+
+    def region():
+        """K steps enqueued back to back, a host synchronisation on both sides; seconds by the host clock."""
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.cq_moe_forward(layer, X, Y)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+    dt = region()                                   # THE timed region: exactly K steps, nothing else in it
+    # four more regions of K steps, for the spread only (an event per step would put a marker packet and
+    # its few microseconds between every two steps of a 0.15 ms layer)
+    per_step = np.array([dt] + [region() for _ in range(4)]) / steps * 1e3
 
     acc = np.zeros((n_stage, len(B.STAGES)))
     for i in range(n_stage):
@@ -247,7 +270,7 @@ def main():
     read_gbps, mfma_tflops = yardsticks(B, torch, info)
 
     n_stage = 100 if synth.CONFIGS[args.workload].T <= 1024 else 20
-    res, L, layer, X, Y, mid, rows = measure(B, torch, synth, args.workload, args.steps, args.warmup, n_stage)
+    res, L, layer, X, Y, mid, rows = measure(B, torch, synth, info, args.workload, args.steps, args.warmup, n_stage)
     cfg = L.cfg
     out = {
         "metric": "MoE-layer tokens/s", "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
@@ -287,7 +310,7 @@ def main():
     torch.cuda.empty_cache()
     if args.workload == "mixtral_decode" and not args.no_prefill:
         # the third leg of the metric: matrix-core utilisation of the Mixtral-shaped prefill layer (T = 4096, A4)
-        pre, _, _, _, _, _, _ = measure(B, torch, synth, "mixtral_prefill", args.prefill_steps, args.prefill_warmup, 10)
+        pre, _, _, _, _, _, _ = measure(B, torch, synth, info, "mixtral_prefill", args.prefill_steps, args.prefill_warmup, 10)
         out["prefill"] = {k: pre[k] for k in ("tokens_per_s", "ms_per_step", "ms_per_step_median", "ms_per_step_min",
                                               "steps", "warmup", "config", "roofline", "stage_ms", "stage_ms_median",
                                               "mfma", "setup_s")}

@@ -2,28 +2,35 @@
 // token blocks of up to 32 rows per pass -- the decode (GEMV-like) regime, where the kernel is
 // bound by streaming the packed 4-bit indices from HBM.
 //
-// Design (gfx950), one workgroup of 4 wavefronts per (expert, 64 weight rows):
+// Design (gfx950), one workgroup of 8 wavefronts per run of 64-row units of one expert:
 //   * Table.  A weight row has 16 centroids, so a BYTE of packed indices (two weights) has only 256
-//     possible decoded values.  The workgroup builds, for each of its 64 rows, the 256-entry table of
-//     decoded PAIRS (two 16-bit operands in one dword) in LDS, entry-major: entry b of row slot r is
-//     the dword at b*256 + r*4.  A wavefront's 32-lane LDS pass then touches 32 different banks
+//     possible decoded values.  The workgroup builds, for each of the 64 rows of a unit, the 256-entry
+//     table of decoded PAIRS (two 16-bit operands in one dword) in LDS, entry-major: entry b of row slot r
+//     is the dword at b*256 + r*4.  A wavefront's 32-lane LDS pass then touches 32 different banks
 //     whatever the indices are (bank = row slot), which removes the bank conflicts that random table
 //     indexing causes -- the paper's stated obstacle for LUT kernels -- without replicating tables.
 //     One v_perm_b32 builds the LDS address of a pair, one ds_read_b32 returns two MFMA operands.
-//   * Stream.  Indices are read with 16-byte loads per lane, 8 steps ahead, straight into registers;
-//     lane (r = lane%32, g = lane/32) reads the 32 weights [64 s + 32 g, +32) of row r in K step s,
-//     which are four 8-wide MFMA A fragments.  With prepacked storage a wavefront load covers 1 KiB
-//     of contiguous memory.  The four wavefronts split K (step s goes to wavefront s%4).
-//   * Math.  v_mfma_f32_32x32x16 with the decoded weights as A (32 rows x 16 k) and the activations
-//     as B (16 k x 32 tokens): integer codes and bf16 centroids are exact bf16 operands; f16
-//     activations (the down projection) use f16 MFMA with centroids converted to f16.  Both operands
-//     number K identically, so the sum over K is the plain dot product.
-//   * Activations of the block's tokens are staged in LDS one K slab at a time, already in fragment
-//     order (16 bytes = 8 consecutive k of one token); token columns past the block are never stored,
-//     and an MFMA output column depends only on its own B column.
-//   * Epilogue.  The four partial accumulators are summed through LDS in a fixed order (deterministic),
-//     scaled per token, optionally passed through SiLU(gate)*up (gate/up rows interleaved so both sit in
-//     one lane), and stored.
+//   * Stream.  Indices are read with 16-byte loads per lane through a register ring; lane
+//     (r = lane%32, g = lane/32) reads the 32 weights [64 s + 32 g, +32) of row r in K step s, which are
+//     four 8-wide MFMA A fragments.  With prepacked storage a wavefront load covers 1 KiB of contiguous
+//     memory.  The wavefronts split K (step s goes to wavefront s % 8); K longer than 4096 is cut into
+//     ranges handled by different workgroups (blockIdx.z) whose scaled fp32 partial sums are added later
+//     in a fixed order.
+//   * Math.  Token blocks of up to 16 columns: v_mfma_f32_16x16x32 (the 32x32x16 shape would spend half
+//     its time on padding columns).  Every lane looks up the row it loaded and v_permlane16_swap sorts
+//     each pair of looked-up dwords into the two 16-row halves; the lane rows then carry the k groups in
+//     the order 2c + g%2 + 4(g/2), and the B operand is held in that order.  17..32 columns:
+//     v_mfma_f32_32x32x16 with the decoded weights as A.  Integer codes and bf16 centroids are exact bf16
+//     operands; f16 activations (the down projection) use f16 MFMA with centroids converted to f16.  Both
+//     operands number K identically, so the sum over K is the plain dot product.
+//   * Two unit loops.  Pipelined (groups of up to 16 tokens whose wavefronts have exactly 8 or 7 K steps
+//     per unit -- run_units_pipe): activations of a wavefront's own K steps in registers, two tables and
+//     the K partials in LDS, the next unit's table written and the previous unit finished inside the K
+//     loop, one barrier per unit.  Plain (everything else): activations staged in a 64 KiB LDS slab one K
+//     slab at a time, already in fragment order, one table rebuilt between units.
+//   * Epilogue.  The wavefronts' partial accumulators are summed through LDS in a fixed order
+//     (deterministic), scaled per token, optionally passed through SiLU(gate)*up (gate/up rows interleaved
+//     so both sit in one lane), and stored.
 #include <type_traits>
 
 #include "cq_internal.h"
@@ -84,6 +91,8 @@ struct GemmArgs {
   // the group and blockIdx.x * upw the first unit
   const int32_t* small_hdr; // {number of listed groups, units per workgroup, workgroups per group}
   const int32_t* small_ids; // the listed groups
+  // grouping by expert folded into the launch (pipelined unit loop only), else route.ids == NULL
+  cq_route_fuse route;
 };
 
 template <bool F16>
@@ -99,7 +108,7 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
 }
 
 
-// QS > 0: a workgroup whose token block has at most 8 rows and whose wavefronts have exactly QS K steps per unit
+// QS > 0: a workgroup whose group has at most 16 rows and whose wavefronts have exactly QS K steps per unit
 // runs the pipelined unit loop (run_units_pipe below); 0: that path is left out of the instantiation.
 template <int AK, int EPI, int OUTK, int kRing, int QS>
 __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmArgs p) {
@@ -130,8 +139,57 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     upw = p.upw;
     u0 = blockIdx.x * upw;
   }
-  const int m0 = p.group_offsets[grp];
-  const int Me = p.group_offsets[grp + 1] - m0;
+  // Rows of this group: from the grouped layout, or -- a5 folded into this launch -- from the selected
+  // expert ids themselves.  There are at most 64 assignments (token, choice), one per lane, numbered
+  // a = token * top_k + choice; the rows of expert e are the assignments that chose e, in ascending a, and
+  // the experts' row ranges follow each other in ascending e (the stable grouping of the routing step), so
+  // two ballots give the first row and the row count, and one lane permutation hands row i's token to
+  // lane i.  Shared experts take every token, in token order, behind the routed rows.
+  int m0, Me, row_token = 0;
+  bool fused = false;
+  if constexpr (QS > 0) fused = p.route.ids != nullptr;
+  if (fused) {
+    const cq_route_fuse& rt = p.route;
+    const int n_assign = rt.T * rt.top_k;
+    const bool va = lane < n_assign;
+    const int id = va ? rt.ids[lane] : 0x7fffffff;
+    const uint64_t lt = (1ull << lane) - 1ull;
+    if (grp < rt.E) {
+      const uint64_t mine = __ballot(va && id == grp);
+      m0 = __popcll(__ballot(va && id < grp));
+      Me = __popcll(mine);
+      const int before = __popcll(mine & lt);
+      // members go to lanes 0 .. Me-1 in order, the others fill the lanes behind them: a permutation
+      const int dest = ((mine >> lane) & 1ull) ? before : Me + lane - before;
+      row_token = __builtin_amdgcn_ds_permute(dest << 2, lane / rt.top_k);
+    } else {
+      m0 = n_assign + (grp - rt.E) * rt.T;
+      Me = rt.T;
+      row_token = lane;
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && wave == 0) {
+      // one wavefront of the launch leaves the grouping behind for the launches that follow
+      int pos = 0, base = 0, my_off = 0;
+      for (int e = 0; e < rt.E; ++e) {
+        const uint64_t m = __ballot(va && id == e);
+        if (va && id == e) pos = base + __popcll(m & lt);
+        if (lane == e) my_off = base;
+        base += __popcll(m);
+      }
+      if (lane < rt.E) rt.offsets[lane] = my_off;
+      if (lane == 0) rt.offsets[rt.E] = n_assign;
+      for (int sh = lane; sh < rt.S; sh += 64) rt.offsets[rt.E + sh + 1] = n_assign + (sh + 1) * rt.T;
+      if (va) {
+        rt.perm[pos] = lane;
+        rt.inv_perm[lane] = pos;
+        rt.src_token[pos] = lane / rt.top_k;
+      }
+      for (int i = lane; i < rt.S * rt.T; i += 64) rt.src_token[n_assign + i] = i % rt.T;
+    }
+  } else {
+    m0 = p.group_offsets[grp];
+    Me = p.group_offsets[grp + 1] - m0;
+  }
   if (Me <= 0 || Me > p.max_rows) return;
   const int u1 = min(nUnits, u0 + upw);
   if (u0 >= u1) return;
@@ -161,7 +219,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   const uint32_t lanebase1 = (uint32_t)((32 + r32) * 4);
   const int n_tb = (Me + 31) >> 5;
 
-  // ---- up to 8 tokens, K range of exactly QS steps per wavefront: the unit loop as a pipeline ----
+  // ---- up to 16 tokens, K range of exactly QS steps per wavefront: the unit loop as a pipeline ----
+  // (described for up to 8 tokens; the form for 9..16 differs where WIDE says so)
   // With few tokens the activations of a wavefront's own K steps fit in registers (its K steps are the same
   // in every unit), so no slab is needed and LDS holds TWO pair tables and two buffers of K partials.  While
   // unit u is looked up in one table, the table of unit u+1 is written into the other, a few entries per K
@@ -238,9 +297,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     __builtin_amdgcn_sched_barrier(0);
     float sc16 = 1.f;
     size_t arow = 0;
+    const int col_token = __shfl(row_token, tcol);   // (folded grouping: the token of this lane's column)
     if (tok) {
       const int m = m0 + tcol;
-      const size_t src = p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
+      const size_t src = fused ? (size_t)col_token : p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
       arow = src * K;
       if (p.row_scale) sc16 = p.row_scale[src];
     }
@@ -985,15 +1045,31 @@ size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epi
   return ksplit > 1 ? cq_align_up((size_t)ksplit * M_total * W->N * sizeof(float), 256) : 0;
 }
 
+// The grouping by expert can be folded into a launch when every workgroup of it runs the pipelined unit loop
+// (at most 16 rows per group, a K range of exactly 8 or 7 steps per wavefront) and one lane per assignment
+// suffices: at most 16 tokens (a group has at most one row per token), at most 64 assignments and experts.
+bool cq_gemm_can_fuse_route(const cq_codebook_weights* W, int T, int E, int S, int top_k, int epilogue) {
+  if (cq_is_w2(W) || cq_tables_per_row(W) > 1 || kWaves != 8) return false;
+  if (T < 1 || T > 16 || top_k < 1 || T * top_k > 64 || E < 1 || E > 64 || S < 0 || W->G != E + S) return false;
+  const int M_total = T * (top_k + S);
+  if (cq_gemm_uses_large_tiles(W, M_total)) return false;
+  int ksplit, ksteps;
+  cq_gemm_split_plan(W, M_total, epilogue, &ksplit, &ksteps);
+  return ksplit == 1 && (ksteps == 8 * kWaves || ksteps == 7 * kWaves);
+}
+
 cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                                   const int32_t* row_gather, const int32_t* group_offsets, int M_total,
                                   int epilogue, void* out, int out_kind, void* workspace, hipStream_t s,
-                                  int* ksplit_left) {
+                                  int* ksplit_left, const cq_route_fuse* route) {
+  if (route && !cq_gemm_can_fuse_route(W, route->T, route->E, route->S, route->top_k, epilogue))
+    return CQ_ERR_UNSUPPORTED;
   if (cq_is_w2(W))
     return cq_gemm_w2_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, epilogue, out, out_kind,
                              workspace, s, ksplit_left);
   if (ksplit_left) *ksplit_left = 1;
   GemmArgs a;
+  a.route = route ? *route : cq_route_fuse{nullptr, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr};
   a.idx = W->prepacked ? (const uint8_t*)W->prepacked : W->idx;
   a.cent = W->cent;
   a.prepacked = W->prepacked ? 1 : 0;
@@ -1058,12 +1134,8 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   switch (a_kind) {
     case CQ_A_INT8_CODES: st = dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s); break;
     case CQ_A_F16: st = dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s); break;
-#ifndef CQ_DEV_FAST
     case CQ_A_BF16: st = dispatch_epi<CQ_A_BF16>(a, W->G, epilogue, out_kind, s); break;
     default: st = dispatch_epi<CQ_A_F32>(a, W->G, epilogue, out_kind, s); break;
-#else
-    default: return CQ_ERR_UNSUPPORTED;
-#endif
   }
   if (st != CQ_OK) return st;
   if (a.ksplit > 1) {

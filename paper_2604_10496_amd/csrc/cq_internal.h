@@ -50,10 +50,11 @@ cq_status cq_rotate_quant_ex(const float* X, const float* R, int T, int H, int a
 
 // Decode-sized batches: quantization of the rotated rows (given as K-split partial sums) and the router
 // logits in one launch.  Supported sizes also fit the one-workgroup routing kernel that follows.
+// topk_ids / topk_w [T, top_k]: NULL, or the launch also selects every token's experts (a4).
 bool cq_front_small_supported(int T, int H, int E, int top_k);
 cq_status cq_front_small_launch(const float* partials, int ksplit, int T, int H, int act_bits, const float* Wr,
                                 const float* bias, int E, float* XR, int8_t* Q, uint16_t* Q16, float* scale,
-                                float* logits, hipStream_t s);
+                                float* logits, int top_k, int32_t* topk_ids, float* topk_w, hipStream_t s);
 
 // X_R = X R on f16 matrix cores from a split copy of R (cq_rotation_split), accurate to about fp32
 bool cq_rotate_split_supported(int T, int H);
@@ -77,10 +78,21 @@ cq_status cq_permute_launch(const int32_t* topk_ids, int T, int E, int top_k, in
 // ksplit_left: NULL, or receives the number of K splits whose partial sums [ksplit][M_total][N] (fp32,
 // at the start of `workspace`) the caller must add itself; 1 means `out` is final.  With NULL the
 // launcher always finishes `out`.
+// route: NULL, or the grouping by expert (a5) is folded into this launch (cq_gemm_can_fuse_route): every
+// workgroup derives its group's rows from the selected expert ids, row_gather and group_offsets are not
+// read, rows gather by token, and the launch leaves offsets / perm / inv_perm / src_token behind for the
+// launches that follow.
+struct cq_route_fuse {
+  const int32_t* ids;                               // [T, top_k] selected experts (a4)
+  int T, E, S, top_k;
+  int32_t *offsets, *perm, *inv_perm, *src_token;   // written as cq_route_permute writes them
+};
+bool cq_gemm_can_fuse_route(const cq_codebook_weights* W, int T, int E, int S, int top_k, int epilogue);
 cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, int a_kind,
                                   const float* row_scale, const int32_t* row_gather,
                                   const int32_t* group_offsets, int M_total, int epilogue,
-                                  void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left);
+                                  void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left,
+                                  const cq_route_fuse* route = nullptr);
 size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue);
 // K split of a product: ksplit ranges of ksteps K steps (of 64) each; 1 and K/64 when K is not split
 void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue, int* ksplit, int* ksteps);

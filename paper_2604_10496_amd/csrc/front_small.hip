@@ -7,10 +7,15 @@
 // (up to 16 partial sums and the router rows of up to 8 experts) are issued before the first use: the
 // kernel costs about one memory latency.
 //
-// (Letting the workgroup that finishes last also do the top-k and the grouping, behind a device-scope
-// fence and a ticket counter, was measured and is slower than a second launch: the fence writes back
-// the L2, which still holds the rotation's partial sums.)
+// A token's top-k (a4) needs nothing but the token's own logits, so the same workgroup can select the
+// experts and form their weights (topk_ids given); the grouping by expert (a5), which needs every token's
+// choice, is then left to the launch that follows.
+//
+// (Letting the workgroup that finishes last also do the grouping, behind a device-scope fence and a ticket
+// counter, was measured and is slower than a second launch: the fence writes back the L2, which still
+// holds the rotation's partial sums.)
 #include "cq_internal.h"
+#include "cq_route.h"
 
 namespace {
 
@@ -23,9 +28,14 @@ template <int NC>
 __global__ __launch_bounds__(kFrontThreads) void front_small_kernel(
     const float* part, int ksplit, int in_place, int T, int H, float qmax, const float* __restrict__ Wr,
     const float* __restrict__ bias, int E, float* XR, int8_t* __restrict__ Q, uint16_t* __restrict__ Q16,
-    float* __restrict__ scale, float* __restrict__ logits) {
+    float* __restrict__ scale, float* __restrict__ logits, int top_k, int32_t* __restrict__ topk_ids,
+    float* __restrict__ topk_w) {
   __shared__ float red[16];
   __shared__ float lred[16][kFrontMaxE];
+  __shared__ float s_logit[64];
+  __shared__ uint32_t s_key[64];
+  __shared__ int s_id[64];
+  __shared__ float s_val[64], s_sorted[64];
   const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
   float4 v[NC];
@@ -91,6 +101,14 @@ __global__ __launch_bounds__(kFrontThreads) void front_small_kernel(
     for (int i = 1; i < 16; ++i) x += lred[i][tid];
     if (bias) x += bias[tid];
     logits[(size_t)t * E + tid] = x;
+    s_logit[tid] = x;
+  }
+  if (topk_ids) {  // (uniform) a4 for this token: wavefront 0 selects, the others only keep the barriers company
+    __syncthreads();
+    const bool sel = wave == 0;
+    const float val[1] = {(sel && lane < E) ? s_logit[lane] : 0.f};
+    cq_route::wave_topk<1>(val, 1, E, top_k, sel, lane, s_key, s_id, s_val, s_sorted, topk_ids + (size_t)t * top_k,
+                           topk_w + (size_t)t * top_k, nullptr);
   }
 
   // ---- integer codes: round to nearest, ties to even (v_rndne_f32) ----
@@ -123,14 +141,14 @@ bool cq_front_small_supported(int T, int H, int E, int top_k) {
 
 cq_status cq_front_small_launch(const float* partials, int ksplit, int T, int H, int act_bits, const float* Wr,
                                 const float* bias, int E, float* XR, int8_t* Q, uint16_t* Q16, float* scale,
-                                float* logits, hipStream_t s) {
+                                float* logits, int top_k, int32_t* topk_ids, float* topk_w, hipStream_t s) {
   const float qmax = (float)((1 << (act_bits - 1)) - 1);
   const int in_place = (partials == XR && ksplit == 1) ? 1 : 0;
   if (H <= 4 * kFrontThreads)
     hipLaunchKernelGGL(front_small_kernel<1>, dim3(T), dim3(kFrontThreads), 0, s, partials, ksplit, in_place, T, H, qmax,
-                       Wr, bias, E, XR, Q, Q16, scale, logits);
+                       Wr, bias, E, XR, Q, Q16, scale, logits, top_k, topk_ids, topk_w);
   else
     hipLaunchKernelGGL(front_small_kernel<2>, dim3(T), dim3(kFrontThreads), 0, s, partials, ksplit, in_place, T, H, qmax,
-                       Wr, bias, E, XR, Q, Q16, scale, logits);
+                       Wr, bias, E, XR, Q, Q16, scale, logits, top_k, topk_ids, topk_w);
   return cq_check_launch();
 }

@@ -159,6 +159,7 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
 
   if (!mark(0)) return CQ_ERR_HIP;
   const bool bf16_codes = use_bf16_codes(L, T);
+  bool fuse_route = false;   // a5 folded into the gate/up launch (decode-sized batches)
   uint16_t* Q16 = bf16_codes ? (uint16_t*)(ws + lay.Q16) : nullptr;
   if (L->r_hadamard) {
     // the rotation is a Hadamard matrix: transform and quantization in one launch, no matrix is read
@@ -177,12 +178,17 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
     st = cq_gemm_f32_launch(X, L->R, 0, T, L->H, L->H, p, part, nullptr, 0, hs);
     if (st != CQ_OK) return st;
     if (!mark(1)) return CQ_ERR_HIP;
+    // when the gate/up launch can do the grouping itself, the front launch also selects the experts and
+    // the routing launch falls away
+    fuse_route = cq_gemm_can_fuse_route(&L->gate_up, T, L->E, L->S, L->top_k, CQ_EPI_SWIGLU);
     st = cq_front_small_launch(part, p.ksplit, T, L->H, L->act_bits, L->Wr, L->bias, L->E, XR, Q, Q16, scale, logits,
-                               hs);
+                               L->top_k, fuse_route ? ids : nullptr, fuse_route ? tw : nullptr, hs);
     if (st != CQ_OK) return st;
-    st = cq_route_permute(nullptr, nullptr, nullptr, logits, T, L->H, L->E, L->top_k, L->S, logits, ids, tw, offsets,
-                          perm, inv_perm, src_token, scratch, scratch_bytes, stream);
-    if (st != CQ_OK) return st;
+    if (!fuse_route) {
+      st = cq_route_permute(nullptr, nullptr, nullptr, logits, T, L->H, L->E, L->top_k, L->S, logits, ids, tw,
+                            offsets, perm, inv_perm, src_token, scratch, scratch_bytes, stream);
+      if (st != CQ_OK) return st;
+    }
     if (!mark(2)) return CQ_ERR_HIP;
   } else {
     if (use_split_rotation(L, T)) {
@@ -200,9 +206,11 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
     if (!mark(2)) return CQ_ERR_HIP;
   }
   // (internal launcher: the layer was validated above and the scratch area is sized for 16-bit operands)
+  const cq_route_fuse route = {ids, T, L->E, L->S, L->top_k, offsets, perm, inv_perm, src_token};
   st = cq_gemm_codebook_launch(&L->gate_up, bf16_codes ? (const void*)Q16 : (const void*)Q,
                                bf16_codes ? CQ_A_BF16 : CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU,
-                               Hbuf, L->h_bits ? CQ_OUT_F32 : CQ_OUT_F16, scratch, hs, nullptr);
+                               Hbuf, L->h_bits ? CQ_OUT_F32 : CQ_OUT_F16, scratch, hs, nullptr,
+                               fuse_route ? &route : nullptr);
   if (st != CQ_OK) return st;
   if (!mark(3)) return CQ_ERR_HIP;
   int down_splits = 1;  // > 1: the down projection left K-split partial sums in the scratch area

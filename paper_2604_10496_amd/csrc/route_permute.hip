@@ -8,92 +8,14 @@
 // of 256 assignments whose in-block ranks come from ballot match masks, so the order inside every
 // expert is ascending assignment number (a stable sort) and the result is unique.
 #include "cq_internal.h"
+#include "cq_route.h"
 
 namespace {
 
+using namespace cq_route;
+
 constexpr int kMaxSlots = 16;       // experts per lane: E <= 1024
 constexpr int kPermBlock = 256;     // assignments per counting-sort block (one wavefront, 4 rounds)
-
-// Order-preserving key of a logit.  -0 is folded into +0 first (they are equal logits: the lower expert id
-// wins), and a NaN, whatever its sign, gets the smallest key (it is never preferred to a number).
-__device__ __forceinline__ uint32_t order_key(float x) {
-  if (x != x) return 0u;
-  const uint32_t u = __float_as_uint(x + 0.0f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-__device__ __forceinline__ uint64_t lanemask_lt(int lane) { return (1ull << lane) - 1ull; }
-
-// Top-k of one token by one wavefront.  val[s] is the logit of expert s*64 + lane.  Called by all
-// wavefronts of the workgroup together (it contains workgroup barriers); sk/si/sv/ss are this
-// wavefront's 64-entry LDS scratch arrays.  Writes ids (descending logit, ties -> lower id) and the
-// softmax over the selected logits; lds_ids, if given, also receives the ids.
-template <int NSLOT>
-__device__ __forceinline__ void wave_topk(const float (&val)[NSLOT], int nslot, int E, int k, bool active, int lane,
-                                          uint32_t* sk, int* si, float* sv, float* ss, int32_t* ids_out,
-                                          float* w_out, int* lds_ids) {
-  const uint64_t lt = lanemask_lt(lane);
-  uint32_t key[NSLOT];
-#pragma unroll
-  for (int s = 0; s < NSLOT; ++s) key[s] = (s < nslot && (s * 64 + lane) < E) ? order_key(val[s]) : 0u;
-  // k-th largest key: keep the largest prefix such that at least k keys are >= it.
-  uint32_t kth = 0u;
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t cand = kth | (1u << bit);
-    int cnt = 0;
-#pragma unroll
-    for (int s = 0; s < NSLOT; ++s)
-      if (s < nslot) cnt += __popcll(__ballot((s * 64 + lane) < E && key[s] >= cand));
-    if (cnt >= k) kth = cand;
-  }
-  int n_gt = 0;
-#pragma unroll
-  for (int s = 0; s < NSLOT; ++s)
-    if (s < nslot) n_gt += __popcll(__ballot((s * 64 + lane) < E && key[s] > kth));
-  const int need = k - n_gt;  // how many of the keys equal to kth are admitted (lowest ids first)
-  int base = 0, ties_seen = 0;
-#pragma unroll
-  for (int s = 0; s < NSLOT; ++s) {
-    if (s < nslot) {
-      const bool valid = (s * 64 + lane) < E;
-      const bool eq = valid && key[s] == kth;
-      const uint64_t m_eq = __ballot(eq);
-      const int tie_rank = ties_seen + __popcll(m_eq & lt);
-      const bool sel = valid && (key[s] > kth || (eq && tie_rank < need));
-      const uint64_t m_sel = __ballot(sel);
-      const int pos = base + __popcll(m_sel & lt);
-      if (sel && active) {
-        sk[pos] = key[s];
-        si[pos] = s * 64 + lane;
-        sv[pos] = val[s];
-      }
-      base += __popcll(m_sel);
-      ties_seen += __popcll(m_eq);
-    }
-  }
-  __syncthreads();
-  if (active && lane < k) {
-    const uint32_t mk = sk[lane];
-    const int mi = si[lane];
-    int rank = 0;
-    for (int p = 0; p < k; ++p) {
-      const uint32_t ok = sk[p];
-      const int oi = si[p];
-      rank += (ok > mk || (ok == mk && oi < mi)) ? 1 : 0;
-    }
-    ids_out[rank] = mi;
-    if (lds_ids) lds_ids[rank] = mi;
-    ss[rank] = sv[lane];
-  }
-  __syncthreads();
-  float ex = 0.f;
-  if (active && lane < k) ex = expf(ss[lane] - ss[0]);
-  float sum = ex;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-  if (active && lane < k) w_out[lane] = ex / sum;
-  __syncthreads();  // the scratch arrays may be reused by the caller's next token
-}
 
 __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ part, int ksplit,
                                                    const float* __restrict__ bias, int T, int E, int k,

@@ -956,6 +956,10 @@ def _check_layer(B, cfg, only_tokens=None, label=""):
     assert np.array_equal(mid["offsets"].cpu().numpy()[:cfg.E + 1], ref["offsets"])
     assert np.array_equal(mid["perm"].cpu().numpy(), ref["perm"])
     assert np.array_equal(mid["inv_perm"].cpu().numpy(), ref["inv_perm"])
+    A = cfg.T * cfg.top_k
+    want_src = np.concatenate([ref["perm"] // cfg.top_k, np.tile(np.arange(cfg.T), cfg.S)])
+    assert np.array_equal(mid["src_token"].cpu().numpy(), want_src)
+    assert np.array_equal(mid["offsets"].cpu().numpy()[cfg.E:], A + cfg.T * np.arange(cfg.S + 1))
     Yh = Y.cpu().numpy()
     rows = np.arange(cfg.T) if only_tokens is None else np.asarray(only_tokens)
     if n_tie and not cfg.h_bits:
@@ -1044,6 +1048,23 @@ def test_layer_tiny(B):
 def test_layer_reduced_shapes(B, name, over):
     cfg = synth.small_variant(synth.CONFIGS[name], **over)
     _check_layer(B, cfg, label=f"{name}-reduced")
+
+
+@pytest.mark.parametrize("name,over", [
+    ("mixtral_decode", dict(H=4096, I=256, T=16)),                         # the decode shape's front end and gate/up K
+    ("mixtral_decode", dict(H=4096, I=128, T=1)),                          # one token: six experts without rows
+    ("mixtral_decode", dict(H=4096, I=128, T=5, E=16, top_k=1)),           # most experts empty
+    ("mixtral_decode", dict(H=4096, I=128, T=16, E=2, top_k=2)),           # every group has 16 rows: the wide form
+    ("mixtral_decode", dict(H=4096, I=192, T=16, E=16, top_k=4, S=1)),     # 64 assignments, a shared expert
+    ("mixtral_decode", dict(H=3584, I=128, T=13, E=4, top_k=2)),           # 7 K steps per wavefront, 9..13-row groups
+    ("mixtral_decode", dict(H=3584, I=192, T=7, E=8, top_k=3, S=2)),
+])
+def test_layer_grouping_folded_into_gate_up(B, name, over):
+    """Decode-sized batches whose gate/up product has K = 4096 or 3584: the front launch selects the experts and
+    the gate/up launch groups the rows itself (no routing launch); ids, weights, offsets, perm, inv_perm,
+    src_token and the output are held to the oracle like everywhere else."""
+    cfg = synth.small_variant(synth.CONFIGS[name], **over)
+    _check_layer(B, cfg, label=f"{name}-folded")
 
 
 @pytest.mark.parametrize("name,over", [
