@@ -131,23 +131,17 @@ def yardsticks(B, torch, info):
     return read_gbps, mfma_tflops
 
 
-def prime(B, torch, info, seconds=0.1):
-    """Keeps the device busy with the two yardstick kernels (streaming read, matrix-core loop) for about
-    `seconds`, immediately before the warm-up steps: setting up a layer's inputs leaves the GPU idle for
-    seconds, and the first 10-20 ms after an idle phase run at the clocks of an idle device (measured: regions
-    of 20 decode steps after 5 warm-up steps went 0.184, 0.183, 0.170, 0.168 ms per step without this, and
-    0.159, 0.159, 0.158, 0.158 with it; priming with the layer itself gives the same).  The timed region is
-    meant to show a busy device."""
-    probe = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
-    probe.zero_()
-    torch.cuda.synchronize()
+def prime(B, torch, info, seconds=0.3):
+    """Keeps the device busy with the matrix-core yardstick loop for about `seconds`, immediately before the
+    warm-up steps: setting up a layer's inputs leaves the GPU idle for seconds, and the first 10-20 ms after
+    an idle phase run at the clocks of an idle device (measured: regions of 20 decode steps after 5 warm-up
+    steps went 0.184, 0.183, 0.170, 0.168 ms per step without this, 0.156, 0.157, 0.151, 0.153, 0.153 with it;
+    priming with the layer itself: 0.152, 0.151, 0.151, 0.151, 0.154).  The timed region is meant to show a
+    busy device."""
     t0 = time.perf_counter()
     while time.perf_counter() - t0 < seconds:
-        for _ in range(10):
-            B.cq_stream_read(probe)
-        B.cq_mfma_loop(info["cu_count"] * 8, 100)
+        B.cq_mfma_loop(info["cu_count"] * 8, 200)
         torch.cuda.synchronize()
-    del probe
 
 
 def measure(B, torch, synth, info, name, steps, warmup, n_stage):
@@ -207,8 +201,10 @@ def measure(B, torch, synth, info, name, steps, warmup, n_stage):
     if hbm_bound:
         ach = gu_bytes / gu_s / 1e9
         # (block-wise tables are decoded by the large-tile kernel, at decode sizes by its narrow-tile variant)
-        kern = ("gemm_w2_kernel" if bits == 2 else "gemm_narrow_kernel" if g and rows <= 64
-                else "gemm_large_kernel" if g else "gemm_small_kernel")
+        # (block-wise tables: tables of 1024 weights at decode sizes run on the streaming kernel, other block-wise
+        # products on the large-tile kernel or, with at most 64 rows in all, its narrow-tile variant)
+        kern = ("gemm_w2_kernel" if bits == 2 else "gemm_small_kernel" if not g or (g == 1024 and cfg.T <= 16)
+                else "gemm_narrow_kernel" if rows <= 64 else "gemm_large_kernel")
         roofline = {"bound": "hbm", "kernel": f"{kern} (gate/up codebook product + SwiGLU)",
                     "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
                     "frac_at_median_duration": gu_bytes / gu_med / 1e9 / HBM_PEAK_GBPS,
@@ -229,6 +225,7 @@ def measure(B, torch, synth, info, name, steps, warmup, n_stage):
     res = {
         "tokens_per_s": cfg.T * steps / dt, "ms_per_step": dt / steps * 1e3,
         "ms_per_step_median": float(np.median(per_step)), "ms_per_step_min": float(per_step.min()),
+        "ms_per_step_regions": [float(v) for v in per_step],
         "steps": steps, "warmup": warmup,
         "config": {"workload": f"{cfg.name} (E={cfg.E} top-{cfg.top_k} S={cfg.S} H={cfg.H} I={cfg.I} T={cfg.T} "
                                f"A{cfg.act_bits}W{bits}, {1 << bits} bf16 centroids per "
@@ -276,6 +273,7 @@ def main():
         "metric": "MoE-layer tokens/s", "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "ms_per_step_median": res["ms_per_step_median"], "ms_per_step_min": res["ms_per_step_min"],
+        "ms_per_step_regions": res["ms_per_step_regions"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": res["config"], "roofline": res["roofline"],
         "stage_ms": res["stage_ms"], "stage_ms_median": res["stage_ms_median"], "stage_ms_min": res["stage_ms_min"],
@@ -311,7 +309,7 @@ def main():
     if args.workload == "mixtral_decode" and not args.no_prefill:
         # the third leg of the metric: matrix-core utilisation of the Mixtral-shaped prefill layer (T = 4096, A4)
         pre, _, _, _, _, _, _ = measure(B, torch, synth, info, "mixtral_prefill", args.prefill_steps, args.prefill_warmup, 10)
-        out["prefill"] = {k: pre[k] for k in ("tokens_per_s", "ms_per_step", "ms_per_step_median", "ms_per_step_min",
+        out["prefill"] = {k: pre[k] for k in ("tokens_per_s", "ms_per_step", "ms_per_step_median", "ms_per_step_min", "ms_per_step_regions",
                                               "steps", "warmup", "config", "roofline", "stage_ms", "stage_ms_median",
                                               "mfma", "setup_s")}
         out["prefill"]["mfma"]["measured_mfma_loop_TFLOPs"] = mfma_tflops

@@ -74,7 +74,9 @@ enum { CQ_OUT_F32 = 0, CQ_OUT_F16 = 1 };
  *             g > 0: "Block-wise" tables, one per group of g consecutive weights of a row; cent is then
  *             [G, N, ceil(K/g), 16] and weight k of a row is decoded through table k / g (the last group
  *             is shorter when g does not divide K).  g must be a multiple of 512 and N of 256
- *             (other values: CQ_ERR_UNSUPPORTED).
+ *             (other values: CQ_ERR_UNSUPPORTED).  Which kernel runs is the library's choice (prefill-sized
+ *             groups: large token tiles; g = 1024 with at most 16 rows per group and K a multiple of 2048:
+ *             the streaming kernel); the results do not depend on it beyond fp32 summation order.
  *   index_bits 0 or 4: the format above.  2: the smallest budget of the ablation on centroid budgets (W2, four
  *             centroids per row) streamed as stored, at half the bytes: idx is [G, N, K/4] bytes, the indices
  *             of a row as one little-endian bit stream (weight j in bits 2(j%4), 2(j%4)+1 of byte j/4), cent is

@@ -110,7 +110,9 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
 
 // QS > 0: a workgroup whose group has at most 16 rows and whose wavefronts have exactly QS K steps per unit
 // runs the pipelined unit loop (run_units_pipe below); 0: that path is left out of the instantiation.
-template <int AK, int EPI, int OUTK, int kRing, int QS>
+// QT > 0: block-wise centroid tables, one per 512 * QT weights of a row (QT K steps per wavefront and table; QT
+// divides QS); the instantiation then holds nothing but the pipelined loop.  0: one table per row.
+template <int AK, int EPI, int OUTK, int kRing, int QS, int QT = 0>
 __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmArgs p) {
   constexpr bool F16 = (AK == CQ_A_F16 || AK == CQ_A_F32);
   constexpr int NW = kWaves;
@@ -234,7 +236,13 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     constexpr bool WIDE = decltype(wide_tag)::value;   // 9..16 tokens: see below
     constexpr int Q = QS > 0 ? QS : 1;
     constexpr int HD = pipe_ring_depth(Q);
-    constexpr int TB0 = Q / 2;            // the next unit's table is written during steps TB0 .. Q-1
+    // A unit's K loop is a run of NSUB sub-units of QL steps, one per centroid table of the K range (one
+    // sub-unit = the whole unit when a row has one table).  The next sub-unit's table is written during steps
+    // TB0 .. QL-1 of the current one, and a workgroup barrier separates two sub-units like it separates two units.
+    constexpr int QL = QT > 0 ? QT : Q;
+    constexpr int NSUB = Q / QL;
+    static_assert(Q % QL == 0, "whole tables per K range");
+    constexpr int TB0 = QL / 2;
     const int i16 = lane & 15, g4 = lane >> 4;
     const int tcol = WIDE ? i16 : (i16 & 7);   // token column whose activations this lane holds
     const bool tok = tcol < Me;             // ... a real token
@@ -258,8 +266,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
 
     // centroid rows of a unit (raw bf16 pairs; chp: the two entries this wavefront uses as high halves)
     uint32_t cp[8], chp;
-    auto cent_req = [&](int u) {
-      const uint16_t* crow = p.cent + ((size_t)grp * N + (size_t)u * 64 + lane) * CQ_N_CENTROIDS;
+    const int nblk = QT > 0 ? K / (512 * QL) : 1;      // tables per row
+    const int blk0 = QT > 0 ? sb / (NW * QL) : 0;      // first table of this workgroup's K range
+    auto cent_req = [&](int u, int sub) {
+      const uint16_t* crow = p.cent + (((size_t)grp * N + (size_t)u * 64 + lane) * nblk + blk0 + sub) * CQ_N_CENTROIDS;
       const uint4 a = reinterpret_cast<const uint4*>(crow)[0];
       const uint4 b = reinterpret_cast<const uint4*>(crow)[1];
       cp[0] = a.x; cp[1] = a.y; cp[2] = a.z; cp[3] = a.w; cp[4] = b.x; cp[5] = b.y; cp[6] = b.z; cp[7] = b.w;
@@ -286,7 +296,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     typedef __attribute__((ext_vector_type(2))) unsigned pair_u32;
 
     // -- prologue: what depends only on the group goes first (centroid rows, the ring), then the token rows
-    cent_req(ufirst);
+    cent_req(ufirst, 0);
     uint4 ring[HD];
     {
       const uint8_t* wb = kbase + (size_t)ufirst * ubytes;
@@ -373,17 +383,20 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
       }
     };
 
-    uint32_t par = 0;   // table and partial buffer of the current unit
+    uint32_t par = 0;    // table of the current sub-unit
+    uint32_t upar = 0;   // partial buffer of the current unit
     for (int ui = 0; ui < ucnt; ++ui) {
       const int u = ufirst + ui * ustep;
       const uint8_t* wb = kbase + (size_t)u * ubytes;
       const bool has_next = ui + 1 < ucnt;
       const uint8_t* wb_next = has_next ? wb + (size_t)ustep * ubytes : wb;
-      // the next unit's centroid rows, requested ahead of this unit's ring refills and used from step TB0 on
-      cent_req(has_next ? u + ustep : u);
+      // the centroid rows of the next table (this unit's second one, else the next unit's first), requested
+      // ahead of the ring refills and used from step TB0 on
+      if constexpr (NSUB > 1) cent_req(u, 1);
+      else cent_req(has_next ? u + ustep : u, 0);
       __builtin_amdgcn_sched_barrier(0);
-      const uint32_t lbase[2] = {lanebase0 | (par << 16), lanebase1 | (par << 16)};
-      const uint32_t tnext = ((par ^ 1u) << 16) + (uint32_t)(wave * 8192 + lane * 4);
+      uint32_t lbase[2] = {lanebase0 | (par << 16), lanebase1 | (par << 16)};
+      uint32_t tnext = ((par ^ 1u) << 16) + (uint32_t)(wave * 8192 + lane * 4);
 
       cq_v4f acc[2][2];
 #pragma unroll
@@ -393,6 +406,20 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
 
 #pragma unroll
       for (int q = 0; q < Q; ++q) {
+        const int ql = q % QL;   // step within the sub-unit (a constant once the loop is unrolled)
+        if (NSUB > 1 && ql == 0 && q > 0) {
+          // the next table of this row block: every wavefront is done with the previous sub-unit's lookups,
+          // whose table the coming steps overwrite, and has written its share of the table that is read now
+          __syncthreads();
+          par ^= 1u;
+          lbase[0] = lanebase0 | (par << 16);
+          lbase[1] = lanebase1 | (par << 16);
+          tnext = ((par ^ 1u) << 16) + (uint32_t)(wave * 8192 + lane * 4);
+          const int sub_next = q / QL + 1;
+          if (sub_next < NSUB) cent_req(u, sub_next);
+          else cent_req(has_next ? u + ustep : u, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         // The two wavefronts that share a SIMD (w and w + 4) take turns at the higher issue priority, step by
         // step: left alone, the older one always wins and the younger one finishes each unit late.
         if ((q ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
@@ -445,9 +472,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
           ring[(2 * q + rb) % HD] = load_stream(sp + loff);
         }
         // the previous unit's results (once), and this step's share of the next unit's table
-        if (q == 0 && ui > 0) finish(u - ustep, WIDE ? 0u : par ^ 1u);
-        if (q == TB0) cent_f16();
-        if (q >= TB0) table_part(tnext, ((q - TB0) * 32) / (Q - TB0), ((q - TB0 + 1) * 32) / (Q - TB0));
+        if (q == 0 && ui > 0) finish(u - ustep, WIDE ? 0u : upar ^ 1u);
+        if (ql == TB0) cent_f16();
+        if (ql >= TB0) table_part(tnext, ((ql - TB0) * 32) / (QL - TB0), ((ql - TB0 + 1) * 32) / (QL - TB0));
       }
       // this unit's K partials: register r = rb*8 + h*4 + v of wavefront w at [par][w][r][column]
       // (9..16 tokens: the 32 KiB hold ONE buffer, so a barrier separates these writes from the reads of the
@@ -455,7 +482,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
       // costs little)
       if constexpr (WIDE) __syncthreads();
       if (pcol) {
-        const uint32_t wbase = kRed + (WIDE ? 0u : par * 16384u) + (uint32_t)wave * kWaveStride + slot * 4u;
+        const uint32_t wbase = kRed + (WIDE ? 0u : upar * 16384u) + (uint32_t)wave * kWaveStride + slot * 4u;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -467,9 +494,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
       }
       __syncthreads();
       par ^= 1u;
+      upar ^= 1u;
     }
     __builtin_amdgcn_s_setprio(0);
-    finish(ufirst + (ucnt - 1) * ustep, WIDE ? 0u : par ^ 1u);
+    finish(ufirst + (ucnt - 1) * ustep, WIDE ? 0u : upar ^ 1u);
   };
 #ifndef CQ_NO_PIPE
   if constexpr (QS > 0) {
@@ -480,6 +508,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     }
   }
 #endif
+  if constexpr (QT > 0) return;   // (block-wise tables exist in the pipelined loop only; the launcher sees to that)
 
   for (int tb = 0; tb < n_tb; ++tb) {
     const int Mb = min(32, Me - 32 * tb);
@@ -940,9 +969,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   }
 }
 
-template <int AK, int EPI, int OUTK, int RING, int QS>
+template <int AK, int EPI, int OUTK, int RING, int QS, int QT = 0>
 cq_status launch_small_ring(const GemmArgs& a, int G, hipStream_t s) {
-  auto kern = gemm_small_kernel<AK, EPI, OUTK, RING, QS>;
+  auto kern = gemm_small_kernel<AK, EPI, OUTK, RING, QS, QT>;
   static bool configured = false;
   if (!configured) {
     hipFuncAttributes fa;
@@ -960,9 +989,15 @@ cq_status launch_small_ring(const GemmArgs& a, int G, hipStream_t s) {
   return cq_check_launch();
 }
 
+// qt: 0, or block-wise tables of 512 * qt weights (every K range then gives each wavefront exactly 8 or 4 steps)
 template <int AK, int EPI, int OUTK>
-cq_status launch_small(const GemmArgs& a, int G, hipStream_t s) {
+cq_status launch_small(const GemmArgs& a, int G, int qt, hipStream_t s) {
   const int per_wave = (a.ksteps + kWaves - 1) / kWaves;  // steps of a wavefront in the (first) K range
+  if (qt != 0) {
+    if (kWaves == 8 && qt == 2 && a.ksteps == 8 * kWaves) return launch_small_ring<AK, EPI, OUTK, 8, 8, 2>(a, G, s);
+    if (kWaves == 8 && qt == 2 && a.ksteps == 4 * kWaves) return launch_small_ring<AK, EPI, OUTK, 8, 4, 2>(a, G, s);
+    return CQ_ERR_UNSUPPORTED;
+  }
   if (kWaves == 8 && per_wave == 8) return launch_small_ring<AK, EPI, OUTK, 8, 8>(a, G, s);
   if (kWaves == 8 && per_wave == 7) return launch_small_ring<AK, EPI, OUTK, 4, 7>(a, G, s);
   return per_wave % 8 == 0 ? launch_small_ring<AK, EPI, OUTK, 8, 0>(a, G, s)
@@ -997,13 +1032,13 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restri
 }
 
 template <int AK>
-cq_status dispatch_epi(const GemmArgs& a, int G, int epilogue, int out_kind, hipStream_t s) {
+cq_status dispatch_epi(const GemmArgs& a, int G, int qt, int epilogue, int out_kind, hipStream_t s) {
   if (epilogue == CQ_EPI_SWIGLU) {
-    return out_kind == CQ_OUT_F16 ? launch_small<AK, CQ_EPI_SWIGLU, CQ_OUT_F16>(a, G, s)
-                                  : launch_small<AK, CQ_EPI_SWIGLU, CQ_OUT_F32>(a, G, s);
+    return out_kind == CQ_OUT_F16 ? launch_small<AK, CQ_EPI_SWIGLU, CQ_OUT_F16>(a, G, qt, s)
+                                  : launch_small<AK, CQ_EPI_SWIGLU, CQ_OUT_F32>(a, G, qt, s);
   }
-  return out_kind == CQ_OUT_F16 ? launch_small<AK, CQ_EPI_NONE, CQ_OUT_F16>(a, G, s)
-                                : launch_small<AK, CQ_EPI_NONE, CQ_OUT_F32>(a, G, s);
+  return out_kind == CQ_OUT_F16 ? launch_small<AK, CQ_EPI_NONE, CQ_OUT_F16>(a, G, qt, s)
+                                : launch_small<AK, CQ_EPI_NONE, CQ_OUT_F32>(a, G, qt, s);
 }
 
 }  // namespace
@@ -1012,11 +1047,27 @@ cq_status dispatch_epi(const GemmArgs& a, int G, int epilogue, int out_kind, hip
 // its 64-row units; with few tokens (the decode regime) a long K (the down projection) is therefore cut
 // into ranges of at most 4096 that different workgroups stream, and their partial sums are added in a
 // fixed order afterwards.  Plain products only (a nonlinear epilogue needs the whole sum).
-void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue, int* ksplit, int* ksteps) {
+// Block-wise tables on the streaming kernel's pipelined loop: tables of 1024 weights (two K steps per wavefront
+// and table), groups of at most 16 rows (the loop's limit), and K ranges of whole tables that give every wavefront
+// exactly 8 steps (4096 weights) or 4 (2048); a nonlinear epilogue needs all of K in one range.
+bool cq_gemm_blockwise_streams(const cq_codebook_weights* W, int M_total, int epilogue, int max_group_rows) {
+  if (kWaves != 8 || cq_is_w2(W) || W->group_k != 1024 || W->K % 2048 != 0) return false;
+  const int bound = max_group_rows > 0 && max_group_rows < M_total ? max_group_rows : M_total;
+  if (bound > 16) return false;
+  return epilogue == CQ_EPI_NONE || W->K == 4096;
+}
+
+void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue, int* ksplit, int* ksteps,
+                        int max_group_rows) {
   const int nS = W->K / 64;
   *ksplit = 1;
   *ksteps = nS;
   const int nblk = cq_tables_per_row(W);
+  if (nblk > 1 && cq_gemm_blockwise_streams(W, M_total, epilogue, max_group_rows)) {
+    *ksteps = W->K % 4096 == 0 ? 64 : 32;
+    *ksplit = nS / *ksteps;
+    return;
+  }
   if (nblk > 1) {
     // Block-wise tables run on the large-tile kernel, one workgroup per 256 rows and group of tokens.  With
     // at most 64 rows in all (one 64-token tile per group) and a short N there are too few of those to fill
@@ -1038,10 +1089,10 @@ void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue,
   *ksplit = (nS + per - 1) / per;
 }
 
-size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue) {
+size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue, int max_group_rows) {
   if (cq_is_w2(W)) return epilogue == CQ_EPI_NONE ? cq_gemm_w2_partials_bytes(W, M_total) : 0;
   int ksplit, ksteps;
-  cq_gemm_split_plan(W, M_total, epilogue, &ksplit, &ksteps);
+  cq_gemm_split_plan(W, M_total, epilogue, &ksplit, &ksteps, max_group_rows);
   return ksplit > 1 ? cq_align_up((size_t)ksplit * M_total * W->N * sizeof(float), 256) : 0;
 }
 
@@ -1049,19 +1100,20 @@ size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epi
 // (at most 16 rows per group, a K range of exactly 8 or 7 steps per wavefront) and one lane per assignment
 // suffices: at most 16 tokens (a group has at most one row per token), at most 64 assignments and experts.
 bool cq_gemm_can_fuse_route(const cq_codebook_weights* W, int T, int E, int S, int top_k, int epilogue) {
-  if (cq_is_w2(W) || cq_tables_per_row(W) > 1 || kWaves != 8) return false;
+  if (cq_is_w2(W) || kWaves != 8) return false;
   if (T < 1 || T > 16 || top_k < 1 || T * top_k > 64 || E < 1 || E > 64 || S < 0 || W->G != E + S) return false;
   const int M_total = T * (top_k + S);
-  if (cq_gemm_uses_large_tiles(W, M_total)) return false;
+  if (cq_tables_per_row(W) > 1 && !cq_gemm_blockwise_streams(W, M_total, epilogue, T)) return false;
+  if (cq_gemm_uses_large_tiles(W, M_total, epilogue, T)) return false;
   int ksplit, ksteps;
-  cq_gemm_split_plan(W, M_total, epilogue, &ksplit, &ksteps);
-  return ksplit == 1 && (ksteps == 8 * kWaves || ksteps == 7 * kWaves);
+  cq_gemm_split_plan(W, M_total, epilogue, &ksplit, &ksteps, T);
+  return ksplit == 1 && (ksteps == 8 * kWaves || (ksteps == 7 * kWaves && cq_tables_per_row(W) == 1));
 }
 
 cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                                   const int32_t* row_gather, const int32_t* group_offsets, int M_total,
                                   int epilogue, void* out, int out_kind, void* workspace, hipStream_t s,
-                                  int* ksplit_left, const cq_route_fuse* route) {
+                                  int* ksplit_left, const cq_route_fuse* route, int max_group_rows) {
   if (route && !cq_gemm_can_fuse_route(W, route->T, route->E, route->S, route->top_k, epilogue))
     return CQ_ERR_UNSUPPORTED;
   if (cq_is_w2(W))
@@ -1084,26 +1136,31 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   {
     // about one workgroup per compute unit: the per-workgroup prologue (activation staging, first
     // table, ring fill) is paid once and there is no partially filled last round of workgroups
-    cq_gemm_split_plan(W, M_total, epilogue, &a.ksplit, &a.ksteps);
+    cq_gemm_split_plan(W, M_total, epilogue, &a.ksplit, &a.ksteps, max_group_rows);
     a.partials = (float*)workspace;  // partial sums first, then the large-tile kernel's lists
     a.part_stride = (size_t)M_total * W->N;
-    const long units = (long)(W->N / 64) * W->G * a.ksplit;
-    long upw = (units + 255) / 256;
+    // (a whole number of workgroups per (group, K range), at most 256 in all: 56 pairs take 4 each, not 5 --
+    // 280 workgroups would run as a full round and a nearly empty one)
+    const long pairs = (long)W->G * a.ksplit;
+    const long per_pair = pairs < 256 ? 256 / pairs : 1;
+    long upw = (W->N / 64 + per_pair - 1) / per_pair;
     if (upw < 1) upw = 1;
-    if (upw > W->N / 64) upw = W->N / 64;
     a.upw = (int)upw;
   }
   // Groups of up to 32 rows go to the streaming kernel above; larger ones to the large-tile kernel (when
   // the row count allows its 256-row tiles), which runs off a device-built tile list.  Block-wise tables
-  // exist in the large-tile kernel only: every group goes there.
-  const bool blockwise = cq_tables_per_row(W) > 1;
-  const bool large = cq_gemm_uses_large_tiles(W, M_total);
+  // go to the large-tile kernel with every group, except tables of 1024 weights at decode sizes, which the
+  // streaming kernel's pipelined loop takes (cq_gemm_blockwise_streams).
+  const bool bw_streams = cq_gemm_blockwise_streams(W, M_total, epilogue, max_group_rows) && cq_tables_per_row(W) > 1;
+  const bool blockwise = cq_tables_per_row(W) > 1 && !bw_streams;
+  const bool large = cq_gemm_uses_large_tiles(W, M_total, epilogue, max_group_rows);
   if (blockwise && !large) return CQ_ERR_UNSUPPORTED;
   const int small_max = blockwise ? 0 : kSmallMaxRows;
+  const int qt = bw_streams ? W->group_k / 512 : 0;
   a.max_rows = large ? small_max : 0x7fffffff;
   a.small_hdr = nullptr;
   a.small_ids = nullptr;
-  void* large_ws = (char*)workspace + cq_gemm_partials_bytes(W, M_total, epilogue);
+  void* large_ws = (char*)workspace + cq_gemm_partials_bytes(W, M_total, epilogue, max_group_rows);
   cq_status st;
   if (large) {
     // the host does not know which groups are small: a device-built list spreads exactly those over
@@ -1132,10 +1189,10 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     return cq_check_launch();
   }
   switch (a_kind) {
-    case CQ_A_INT8_CODES: st = dispatch_epi<CQ_A_INT8_CODES>(a, W->G, epilogue, out_kind, s); break;
-    case CQ_A_F16: st = dispatch_epi<CQ_A_F16>(a, W->G, epilogue, out_kind, s); break;
-    case CQ_A_BF16: st = dispatch_epi<CQ_A_BF16>(a, W->G, epilogue, out_kind, s); break;
-    default: st = dispatch_epi<CQ_A_F32>(a, W->G, epilogue, out_kind, s); break;
+    case CQ_A_INT8_CODES: st = dispatch_epi<CQ_A_INT8_CODES>(a, W->G, qt, epilogue, out_kind, s); break;
+    case CQ_A_F16: st = dispatch_epi<CQ_A_F16>(a, W->G, qt, epilogue, out_kind, s); break;
+    case CQ_A_BF16: st = dispatch_epi<CQ_A_BF16>(a, W->G, qt, epilogue, out_kind, s); break;
+    default: st = dispatch_epi<CQ_A_F32>(a, W->G, qt, epilogue, out_kind, s); break;
   }
   if (st != CQ_OK) return st;
   if (a.ksplit > 1) {
@@ -1159,16 +1216,21 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
 }
 
 
-bool cq_gemm_uses_large_tiles(const cq_codebook_weights* W, int M_total) {
+bool cq_gemm_uses_large_tiles(const cq_codebook_weights* W, int M_total, int epilogue, int max_group_rows) {
+  if (cq_tables_per_row(W) > 1 && cq_gemm_blockwise_streams(W, M_total, epilogue, max_group_rows)) return false;
   return !cq_is_w2(W) && cq_gemm_large_supported(W) && (M_total > kSmallMaxRows || cq_tables_per_row(W) > 1);
 }
 
 extern "C" size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, int M_total) {
   if (!W || W->G <= 0 || W->N <= 0 || W->K <= 0 || M_total <= 0) return 0;
-  size_t n = cq_gemm_partials_bytes(W, M_total, CQ_EPI_NONE);
-  if (cq_gemm_uses_large_tiles(W, M_total))
-    n += cq_gemm_large_workspace_bytes(W->G, M_total, W->K, true);  // worst case over the operand kinds
-  return n;
+  size_t need = 0;
+  for (const int epi : {CQ_EPI_NONE, CQ_EPI_SWIGLU}) {   // the kernel, and with it the need, can depend on the epilogue
+    size_t n = cq_gemm_partials_bytes(W, M_total, epi);
+    if (cq_gemm_uses_large_tiles(W, M_total, epi))
+      n += cq_gemm_large_workspace_bytes(W->G, M_total, W->K, true);  // worst case over the operand kinds
+    if (n > need) need = n;
+  }
+  return need;
 }
 
 extern "C" cq_status cq_codebook_grouped_gemm(const cq_codebook_weights* W, const void* A, int a_kind,

@@ -92,10 +92,15 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
                                   const float* row_scale, const int32_t* row_gather,
                                   const int32_t* group_offsets, int M_total, int epilogue,
                                   void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left,
-                                  const cq_route_fuse* route = nullptr);
-size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue);
+                                  const cq_route_fuse* route = nullptr, int max_group_rows = 0);
+// max_group_rows (here and below): an upper bound on the rows of any one group if the caller has one (the
+// layer: a group has at most one row per token), else 0 = M_total.
+size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epilogue, int max_group_rows = 0);
 // K split of a product: ksplit ranges of ksteps K steps (of 64) each; 1 and K/64 when K is not split
-void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue, int* ksplit, int* ksteps);
+void cq_gemm_split_plan(const cq_codebook_weights* W, int M_total, int epilogue, int* ksplit, int* ksteps,
+                        int max_group_rows = 0);
+// block-wise tables of 1024 weights on the streaming kernel (groups of at most 16 rows, K ranges of whole tables)
+bool cq_gemm_blockwise_streams(const cq_codebook_weights* W, int M_total, int epilogue, int max_group_rows = 0);
 // W2 weights streamed as stored (index_bits = 2): quadruple tables in LDS, decode-sized groups
 static inline bool cq_is_w2(const cq_codebook_weights* W) { return W->index_bits == 2; }
 int cq_gemm_w2_range_steps(int K);   // K steps (of 128) per K range, 0 if K cannot be split that way
@@ -112,7 +117,8 @@ cq_status cq_combine_launch(const float* O, int slices, size_t slice_stride, con
 bool cq_gemm_large_supported(const cq_codebook_weights* W);
 // whether a product over M_total rows launches it (more rows than the streaming kernel takes per group, or
 // block-wise tables, which only the large-tile kernel decodes)
-bool cq_gemm_uses_large_tiles(const cq_codebook_weights* W, int M_total);
+bool cq_gemm_uses_large_tiles(const cq_codebook_weights* W, int M_total, int epilogue = CQ_EPI_NONE,
+                              int max_group_rows = 0);
 // with_conversion: include room for a 16-bit copy of the activation rows (needed for CQ_A_INT8_CODES
 // and CQ_A_F32 operands; bf16 / f16 operands are read in place)
 size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion);

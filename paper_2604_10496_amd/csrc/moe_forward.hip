@@ -60,7 +60,7 @@ bool use_split_rotation(const cq_layer* L, int T) { return L->R_split && cq_rota
 // Batches large enough for the large-tile product get the codes a second time as bf16, so that staging
 // them into LDS is a plain copy.
 bool use_bf16_codes(const cq_layer* L, int T) {
-  return cq_gemm_uses_large_tiles(&L->gate_up, (int)((long)T * (L->top_k + L->S)));
+  return cq_gemm_uses_large_tiles(&L->gate_up, (int)((long)T * (L->top_k + L->S)), CQ_EPI_SWIGLU, T);
 }
 
 void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
@@ -84,7 +84,7 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   o->src_token = take(M * 4);
   o->Hbuf = take(M * L->I * (L->h_bits ? 4 : 2));  // f16, or fp32 when it is rotated and quantized next
   o->Obuf = take(M * L->H * 4);
-  const bool hq16 = L->h_bits && cq_gemm_uses_large_tiles(&L->down, (int)M);
+  const bool hq16 = L->h_bits && cq_gemm_uses_large_tiles(&L->down, (int)M, CQ_EPI_NONE, T);
   o->HQ = take(L->h_bits ? M * L->I : 0);
   o->HQ16 = take(hq16 ? M * L->I * 2 : 0);
   o->hscale = take(L->h_bits ? M * 4 : 0);
@@ -101,8 +101,8 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
     if (g1 > scratch) scratch = g1;
   }
   {
-    size_t g2 = cq_gemm_partials_bytes(&L->down, (int)M, CQ_EPI_NONE);
-    if (cq_gemm_uses_large_tiles(&L->down, (int)M))  // (16-bit operands in either variant: f16 h or bf16 codes)
+    size_t g2 = cq_gemm_partials_bytes(&L->down, (int)M, CQ_EPI_NONE, T);   // (a group has at most T rows)
+    if (cq_gemm_uses_large_tiles(&L->down, (int)M, CQ_EPI_NONE, T))  // (16-bit operands in either variant: f16 h or bf16 codes)
       g2 += cq_gemm_large_workspace_bytes(L->down.G, (int)M, L->down.K, false);
     if (g2 > scratch) scratch = g2;
   }
@@ -210,7 +210,7 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
   st = cq_gemm_codebook_launch(&L->gate_up, bf16_codes ? (const void*)Q16 : (const void*)Q,
                                bf16_codes ? CQ_A_BF16 : CQ_A_INT8_CODES, scale, src_token, offsets, M, CQ_EPI_SWIGLU,
                                Hbuf, L->h_bits ? CQ_OUT_F32 : CQ_OUT_F16, scratch, hs, nullptr,
-                               fuse_route ? &route : nullptr);
+                               fuse_route ? &route : nullptr, T);
   if (st != CQ_OK) return st;
   if (!mark(3)) return CQ_ERR_HIP;
   int down_splits = 1;  // > 1: the down projection left K-split partial sums in the scratch area
@@ -219,16 +219,16 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
     // down projection reads integer codes and per-row scales like the gate/up projection does
     int8_t* HQ = (int8_t*)(ws + lay.HQ);
     float* hscale = (float*)(ws + lay.hscale);
-    const bool hq16 = cq_gemm_uses_large_tiles(&L->down, (int)M);
+    const bool hq16 = cq_gemm_uses_large_tiles(&L->down, (int)M, CQ_EPI_NONE, T);
     uint16_t* HQ16 = hq16 ? (uint16_t*)(ws + lay.HQ16) : nullptr;
     st = cq_hadamard_quant_launch((const float*)Hbuf, M, L->I, L->h_bits, HQ, HQ16, hscale, nullptr, hs);
     if (st != CQ_OK) return st;
     st = cq_gemm_codebook_launch(&L->down, hq16 ? (const void*)HQ16 : (const void*)HQ,
                                  hq16 ? CQ_A_BF16 : CQ_A_INT8_CODES, hscale, nullptr, offsets, M, CQ_EPI_NONE, Obuf,
-                                 CQ_OUT_F32, scratch, hs, &down_splits);
+                                 CQ_OUT_F32, scratch, hs, &down_splits, nullptr, T);
   } else {
     st = cq_gemm_codebook_launch(&L->down, Hbuf, CQ_A_F16, nullptr, nullptr, offsets, M, CQ_EPI_NONE, Obuf, CQ_OUT_F32,
-                                 scratch, hs, &down_splits);
+                                 scratch, hs, &down_splits, nullptr, T);
   }
   if (st != CQ_OK) return st;
   if (!mark(4)) return CQ_ERR_HIP;

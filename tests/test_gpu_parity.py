@@ -533,7 +533,11 @@ def test_gemm_full_gate_up_shape_exact(B):
 BLOCKWISE_CASES = [(256, 1024, 512, [3, 40]), (256, 1408, 1024, [1, 0, 33, 300]), (512, 4096, 1024, [5, 129, 257]),
                    (256, 14336, 1024, [7, 70]), (256, 1536, 512, [64, 65, 128, 256]),
                    # at most 64 rows in all: K is cut into ranges of whole groups, partial sums added afterwards
-                   (256, 14336, 1024, [7, 30]), (512, 4096, 1024, [64]), (256, 1408, 1024, [0, 5])]
+                   (256, 14336, 1024, [7, 30]), (512, 4096, 1024, [64]), (256, 1408, 1024, [0, 5]),
+                   # tables of 1024 weights, at most 16 rows in all, K a multiple of 2048: the streaming kernel's
+                   # pipelined loop with a table switch every two steps (K ranges of 4096 or 2048 weights)
+                   (256, 2048, 1024, [3, 0, 9, 4]), (512, 4096, 1024, [16]), (256, 6144, 1024, [1, 8]),
+                   (256, 14336, 1024, [7, 5]), (256, 8192, 1024, [2, 12])]
 
 
 @pytest.mark.parametrize("prepacked", [True, False])
@@ -583,12 +587,13 @@ def test_gemm_blockwise_float_rows_against_oracle(B, a_kind, N, K, g, counts):
         assert Hp.row_rel_l2(out[rows], ref).max() < 2e-5
 
 
-@pytest.mark.parametrize("counts", [[9, 140], [9, 40], [9, 20]])   # no group above 64 / 32 rows: the narrow-tile kernels
-def test_gemm_blockwise_swiglu_epilogue(B, counts):
+@pytest.mark.parametrize("K,g,counts", [(1024, 512, [9, 140]), (1024, 512, [9, 40]), (1024, 512, [9, 20]),   # the narrow-tile kernels
+                                        (4096, 1024, [9, 0, 5]), (4096, 1024, [16]), (4096, 1024, [1])])     # the streaming kernel
+def test_gemm_blockwise_swiglu_epilogue(B, K, g, counts):
     rng = np.random.default_rng(61)
-    I, K, g = 128, 1024, 512
+    I = 128
     G, M = len(counts), sum(counts)
-    draw = lambda: (rng.integers(0, 256, size=(I, K // 2), dtype=np.uint8), synth.draw_centroids(rng, I, n_blocks=2))
+    draw = lambda: (rng.integers(0, 256, size=(I, K // 2), dtype=np.uint8), synth.draw_centroids(rng, I, n_blocks=K // g))
     gate, up = [draw() for _ in range(G)], [draw() for _ in range(G)]
     fused = [synth.interleave_gate_up(gate[i], up[i]) for i in range(G)]
     W = B.DeviceCodebook(np.stack([f[0] for f in fused]), np.stack([f[1] for f in fused]), group_k=g)
@@ -599,6 +604,8 @@ def test_gemm_blockwise_swiglu_epilogue(B, counts):
                                      B.CQ_EPI_SWIGLU, B.CQ_OUT_F32).cpu().numpy().astype(np.float64)
     for grp in range(G):
         rows = slice(off[grp], off[grp + 1])
+        if rows.start == rows.stop:
+            continue
         a = scale[rows, None].astype(np.float64) * codes[rows].astype(np.float64)
         ref = O.silu(O.codebook_matmul(a, *gate[grp], g)) * O.codebook_matmul(a, *up[grp], g)
         assert Hp.row_rel_l2(out[rows], ref).max() < 2e-5
@@ -1112,6 +1119,10 @@ def test_hadamard_quant(B, M, I, bits):
     ("mixtral_prefill", dict(H=1024, I=1408, T=400, group_k=1024)),         # short last group (1408 = 1024 + 384)
     ("dsv2lite", dict(H=512, I=1024, T=64, E=16, group_k=512)),             # shared experts
     ("mixtral_decode", dict(H=1024, I=512, T=16, group_k=2048)),            # group >= K: one table per row
+    # decode sizes, tables of 1024 weights, K multiples of 2048: both products on the streaming kernel
+    ("mixtral_decode", dict(H=4096, I=2048, T=16, group_k=1024)),
+    ("mixtral_decode", dict(H=4096, I=6144, T=9, group_k=1024, E=4)),       # down product in 3 K ranges; 9-row groups possible
+    ("mixtral_decode", dict(H=4096, I=2048, T=16, group_k=1024, h_bits=8)), # ... reading integer codes of h
     # with the online-Hadamard variant: the down product reads integer codes through block-wise tables
     ("mixtral_decode", dict(H=1024, I=1536, T=16, group_k=512, h_bits=8)),
     ("mixtral_prefill", dict(H=512, I=1024, T=300, group_k=512, h_bits=4, r_hadamard=True, outlier_channels=(3, 41))),
