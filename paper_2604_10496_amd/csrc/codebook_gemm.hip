@@ -34,6 +34,7 @@
 #include <type_traits>
 
 #include "cq_internal.h"
+#include "cq_route.h"
 #include "cq_stream.h"
 
 namespace {
@@ -141,53 +142,14 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     upw = p.upw;
     u0 = blockIdx.x * upw;
   }
-  // Rows of this group: from the grouped layout, or -- a5 folded into this launch -- from the selected
-  // expert ids themselves.  There are at most 64 assignments (token, choice), one per lane, numbered
-  // a = token * top_k + choice; the rows of expert e are the assignments that chose e, in ascending a, and
-  // the experts' row ranges follow each other in ascending e (the stable grouping of the routing step), so
-  // two ballots give the first row and the row count, and one lane permutation hands row i's token to
-  // lane i.  Shared experts take every token, in token order, behind the routed rows.
+  // Rows of this group: from the grouped layout, or -- a5 folded into this launch -- from the selected expert
+  // ids themselves (cq_route::group_rows_from_ids).
   int m0, Me, row_token = 0;
   bool fused = false;
   if constexpr (QS > 0) fused = p.route.ids != nullptr;
   if (fused) {
-    const cq_route_fuse& rt = p.route;
-    const int n_assign = rt.T * rt.top_k;
-    const bool va = lane < n_assign;
-    const int id = va ? rt.ids[lane] : 0x7fffffff;
-    const uint64_t lt = (1ull << lane) - 1ull;
-    if (grp < rt.E) {
-      const uint64_t mine = __ballot(va && id == grp);
-      m0 = __popcll(__ballot(va && id < grp));
-      Me = __popcll(mine);
-      const int before = __popcll(mine & lt);
-      // members go to lanes 0 .. Me-1 in order, the others fill the lanes behind them: a permutation
-      const int dest = ((mine >> lane) & 1ull) ? before : Me + lane - before;
-      row_token = __builtin_amdgcn_ds_permute(dest << 2, lane / rt.top_k);
-    } else {
-      m0 = n_assign + (grp - rt.E) * rt.T;
-      Me = rt.T;
-      row_token = lane;
-    }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && wave == 0) {
-      // one wavefront of the launch leaves the grouping behind for the launches that follow
-      int pos = 0, base = 0, my_off = 0;
-      for (int e = 0; e < rt.E; ++e) {
-        const uint64_t m = __ballot(va && id == e);
-        if (va && id == e) pos = base + __popcll(m & lt);
-        if (lane == e) my_off = base;
-        base += __popcll(m);
-      }
-      if (lane < rt.E) rt.offsets[lane] = my_off;
-      if (lane == 0) rt.offsets[rt.E] = n_assign;
-      for (int sh = lane; sh < rt.S; sh += 64) rt.offsets[rt.E + sh + 1] = n_assign + (sh + 1) * rt.T;
-      if (va) {
-        rt.perm[pos] = lane;
-        rt.inv_perm[lane] = pos;
-        rt.src_token[pos] = lane / rt.top_k;
-      }
-      for (int i = lane; i < rt.S * rt.T; i += 64) rt.src_token[n_assign + i] = i % rt.T;
-    }
+    cq_route::group_rows_from_ids(p.route, grp, lane,
+                                  blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && wave == 0, m0, Me, row_token);
   } else {
     m0 = p.group_offsets[grp];
     Me = p.group_offsets[grp + 1] - m0;
@@ -972,16 +934,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
 template <int AK, int EPI, int OUTK, int RING, int QS, int QT = 0>
 cq_status launch_small_ring(const GemmArgs& a, int G, hipStream_t s) {
   auto kern = gemm_small_kernel<AK, EPI, OUTK, RING, QS, QT>;
-  static bool configured = false;
-  if (!configured) {
-    hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
-    if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kTableBytes + kSlabBytes + kRedBytes) != hipSuccess)
-      return CQ_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<bool> configured{false};
+  const cq_status cst = cq_configure_lds(kern, kTableBytes + kSlabBytes + kRedBytes, configured, true);
+  if (cst != CQ_OK) return cst;
   const int n_units = a.N / 64;
   const dim3 grid = a.small_hdr ? dim3(G > kListedWorkgroups ? G : kListedWorkgroups, 1, a.ksplit)
                                 : dim3((n_units + a.upw - 1) / a.upw, G, a.ksplit);
@@ -1100,8 +1055,10 @@ size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epi
 // (at most 16 rows per group, a K range of exactly 8 or 7 steps per wavefront) and one lane per assignment
 // suffices: at most 16 tokens (a group has at most one row per token), at most 64 assignments and experts.
 bool cq_gemm_can_fuse_route(const cq_codebook_weights* W, int T, int E, int S, int top_k, int epilogue) {
-  if (cq_is_w2(W) || kWaves != 8) return false;
+  if (kWaves != 8) return false;
   if (T < 1 || T > 16 || top_k < 1 || T * top_k > 64 || E < 1 || E > 64 || S < 0 || W->G != E + S) return false;
+  // (the 2-bit kernel takes every group of a launch it supports: its workgroups all derive their rows alike)
+  if (cq_is_w2(W)) return cq_gemm_w2_supported(W, CQ_A_INT8_CODES, epilogue);
   const int M_total = T * (top_k + S);
   if (cq_tables_per_row(W) > 1 && !cq_gemm_blockwise_streams(W, M_total, epilogue, T)) return false;
   if (cq_gemm_uses_large_tiles(W, M_total, epilogue, T)) return false;
@@ -1118,7 +1075,7 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     return CQ_ERR_UNSUPPORTED;
   if (cq_is_w2(W))
     return cq_gemm_w2_launch(W, A, a_kind, row_scale, row_gather, group_offsets, M_total, epilogue, out, out_kind,
-                             workspace, s, ksplit_left);
+                             workspace, s, ksplit_left, route);
   if (ksplit_left) *ksplit_left = 1;
   GemmArgs a;
   a.route = route ? *route : cq_route_fuse{nullptr, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr};

@@ -551,19 +551,6 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
   }
 }
 
-template <typename Kernel>
-cq_status configure_lds(Kernel kern, int lds, bool* configured) {
-  if (*configured) return CQ_OK;
-  hipFuncAttributes fa;
-  if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
-  if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
-      hipSuccess)
-    return CQ_ERR_HIP;
-  *configured = true;
-  return CQ_OK;
-}
-
 template <bool F16, int EPI, int OUTK, bool BLK, bool PRE, int C>
 cq_status launch_narrow(const LargeArgs& a, int max128, hipStream_t s) {
   auto kern = gemm_narrow_kernel<F16, EPI, OUTK, BLK, PRE, C>;
@@ -571,8 +558,8 @@ cq_status launch_narrow(const LargeArgs& a, int max128, hipStream_t s) {
   constexpr int lds_loop = 8 * 32 * C * kStepBytes + (BLK ? 8 * kNextTableBytes : 0);
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
   static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
-  static bool configured = false;
-  const cq_status st = configure_lds(kern, lds, &configured);
+  static std::atomic<bool> configured{false};
+  const cq_status st = cq_configure_lds(kern, lds, configured, true);
   if (st != CQ_OK) return st;
   const long grid = (((long)max128 * a.row_tiles + 7) / 8) * 8;
   if (grid <= 0) return CQ_OK;
@@ -597,8 +584,8 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
   auto kern = gemm_large_kernel<F16, EPI, OUTK, BLK, PRE>;
   constexpr int lds_loop = kLdsTileBytes + (BLK ? 8 * kNextTableBytes : 0);
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
-  static bool configured = false;
-  const cq_status st = configure_lds(kern, lds, &configured);
+  static std::atomic<bool> configured{false};
+  const cq_status st = cq_configure_lds(kern, lds, configured, true);
   if (st != CQ_OK) return st;
   // worst case of the kernel's per-XCD shares (a group ends in at most one 128- or 64-token tile, but the
   // two lists round up separately): ceil(n256/8) + ceil(n128/8) + ceil(n64/8) slots on each of 8 XCDs

@@ -158,13 +158,9 @@ __global__ __launch_bounds__(256, 2) void gemm_lut_kernel(const LutArgs p) {
 template <int EPI, int OUTK>
 cq_status launch_lut(const LutArgs& a, int G, hipStream_t s) {
   auto kern = gemm_lut_kernel<EPI, OUTK>;
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kLutLdsBytes) != hipSuccess)
-      return CQ_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<bool> configured{false};
+  const cq_status cst = cq_configure_lds(kern, kLutLdsBytes, configured, false);
+  if (cst != CQ_OK) return cst;
   hipLaunchKernelGGL(kern, dim3(a.N / 64, G), dim3(256), kLutLdsBytes, s, a);
   return cq_check_launch();
 }

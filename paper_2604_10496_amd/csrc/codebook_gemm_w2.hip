@@ -21,6 +21,7 @@
 #include <type_traits>
 
 #include "cq_internal.h"
+#include "cq_route.h"
 #include "cq_stream.h"
 
 namespace {
@@ -41,6 +42,7 @@ struct W2Args {
   const int32_t* group_offsets;
   void* out;
   int out_ld;
+  cq_route_fuse route;      // grouping by expert folded into the launch (cq_route::group_rows_from_ids), else ids == NULL
   int upw;                  // 32-row units per workgroup
   int ksplit;               // K ranges (blockIdx.z); > 1: scaled fp32 partial sums go to `partials`
   float* partials;          // [ksplit][M_total][N]
@@ -71,8 +73,15 @@ __global__ __launch_bounds__(64 * kW2Waves, 1) void gemm_w2_kernel(const W2Args 
   const int r32 = lane & 31, g2 = lane >> 5, i16 = lane & 15, g4 = lane >> 4;
   const int N = p.N, K = p.K;
   const int grp = blockIdx.y;
-  const int m0 = p.group_offsets[grp];
-  const int Me = p.group_offsets[grp + 1] - m0;
+  int m0, Me, row_token = 0;
+  const bool fused = p.route.ids != nullptr;
+  if (fused) {
+    cq_route::group_rows_from_ids(p.route, grp, lane,
+                                  blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && wave == 0, m0, Me, row_token);
+  } else {
+    m0 = p.group_offsets[grp];
+    Me = p.group_offsets[grp + 1] - m0;
+  }
   if (Me <= 0) return;
   const int nUnits = N >> 5;
   const int ustep = gridDim.x, ufirst = blockIdx.x;   // a group's workgroups interleave its units
@@ -137,9 +146,10 @@ __global__ __launch_bounds__(64 * kW2Waves, 1) void gemm_w2_kernel(const W2Args 
     __builtin_amdgcn_sched_barrier(0);
     float sc16 = 1.f;
     size_t arow = 0;
+    const int col_token = __shfl(row_token, 8 * tb + tcol);   // (folded grouping: the token of this lane's column)
     if (tok) {
       const int m = m0 + 8 * tb + tcol;
-      const size_t src = p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
+      const size_t src = fused ? (size_t)col_token : p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
       arow = src * K;
       if (p.row_scale) sc16 = p.row_scale[src];
     }
@@ -295,16 +305,9 @@ __global__ __launch_bounds__(64 * kW2Waves, 1) void gemm_w2_kernel(const W2Args 
 template <int AK, int EPI, int OUTK, int Q>
 cq_status launch_w2(const W2Args& a, int G, hipStream_t s) {
   auto kern = gemm_w2_kernel<AK, EPI, OUTK, Q>;
-  static bool configured = false;
-  if (!configured) {
-    hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
-    if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kW2Lds) != hipSuccess)
-      return CQ_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<bool> configured{false};
+  const cq_status cst = cq_configure_lds(kern, kW2Lds, configured, true);
+  if (cst != CQ_OK) return cst;
   const int n_units = a.N / 32;
   const dim3 grid((n_units + a.upw - 1) / a.upw, G, a.ksplit);
   hipLaunchKernelGGL(kern, grid, dim3(64 * kW2Waves), kW2Lds, s, a);
@@ -359,7 +362,8 @@ bool cq_gemm_w2_supported(const cq_codebook_weights* W, int a_kind, int epilogue
 
 cq_status cq_gemm_w2_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                             const int32_t* row_gather, const int32_t* group_offsets, int M_total, int epilogue,
-                            void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left) {
+                            void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left,
+                            const cq_route_fuse* route) {
   if (ksplit_left) *ksplit_left = 1;
   if (!cq_gemm_w2_supported(W, a_kind, epilogue)) return CQ_ERR_UNSUPPORTED;
   const int steps = cq_gemm_w2_range_steps(W->K);
@@ -373,6 +377,7 @@ cq_status cq_gemm_w2_launch(const cq_codebook_weights* W, const void* A, int a_k
   a.row_scale = row_scale;
   a.row_gather = row_gather;
   a.group_offsets = group_offsets;
+  a.route = route ? *route : cq_route_fuse{nullptr, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr};
   a.out = out;
   a.out_ld = epilogue == CQ_EPI_SWIGLU ? W->N / 2 : W->N;
   a.ksplit = W->K / 128 / steps;

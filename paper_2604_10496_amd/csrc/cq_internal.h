@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "cq.h"
 #include "cq_measure.h"
 
@@ -21,6 +23,24 @@ static inline cq_status cq_check_launch() {
 }
 
 static inline size_t cq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Raises a kernel's dynamic-LDS limit before its first launch.  `done` is the launcher's own flag; threads that
+// meet in a first call may each set the attribute (the same value: harmless), and none launches before it is set.
+// at_zero: the kernel addresses LDS from 0, so it must have no static LDS in front of the dynamic part.
+template <typename Kernel>
+static inline cq_status cq_configure_lds(Kernel kern, int lds_bytes, std::atomic<bool>& done, bool at_zero) {
+  if (done.load(std::memory_order_acquire)) return CQ_OK;
+  if (at_zero) {
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) return CQ_ERR_HIP;
+    if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;
+  }
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          lds_bytes) != hipSuccess)
+    return CQ_ERR_HIP;
+  done.store(true, std::memory_order_release);
+  return CQ_OK;
+}
 
 // centroid tables per weight row: one, or with block-wise tables one per group of group_k weights along K
 static inline int cq_tables_per_row(const cq_codebook_weights* W) {
@@ -108,7 +128,8 @@ bool cq_gemm_w2_supported(const cq_codebook_weights* W, int a_kind, int epilogue
 size_t cq_gemm_w2_partials_bytes(const cq_codebook_weights* W, int M_total);
 cq_status cq_gemm_w2_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                             const int32_t* row_gather, const int32_t* group_offsets, int M_total, int epilogue,
-                            void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left);
+                            void* out, int out_kind, void* workspace, hipStream_t s, int* ksplit_left,
+                            const cq_route_fuse* route = nullptr);
 // weighted combine over `slices` partial copies of O that are `slice_stride` floats apart
 cq_status cq_combine_launch(const float* O, int slices, size_t slice_stride, const float* topk_w,
                             const int32_t* inv_perm, int T, int H, int top_k, int n_shared, float* Y, hipStream_t s);

@@ -86,4 +86,51 @@ __device__ __forceinline__ void wave_topk(const float (&val)[NSLOT], int nslot, 
   __syncthreads();  // the scratch arrays may be reused by the caller's next token
 }
 
+// a5 folded into a product launch for decode-sized batches (cq_route_fuse): the rows of group `grp`, derived by
+// one wavefront from the selected expert ids.  There are at most 64 assignments (token, choice), one per lane,
+// numbered a = token * top_k + choice; the rows of expert e are the assignments that chose e, in ascending a, and
+// the experts' row ranges follow each other in ascending e (the stable grouping of the routing step), so two
+// ballots give the first row m0 and the row count Me, and one lane permutation hands row i's token to lane i
+// (row_token).  Shared experts (grp >= E) take every token, in token order, behind the routed rows.
+// writer: this wavefront also leaves offsets / perm / inv_perm / src_token behind for the launches that follow
+// (exactly one wavefront of the launch must do so).  Called by all 64 lanes.
+__device__ __forceinline__ void group_rows_from_ids(const cq_route_fuse& rt, int grp, int lane, bool writer, int& m0,
+                                                    int& Me, int& row_token) {
+  const int n_assign = rt.T * rt.top_k;
+  const bool va = lane < n_assign;
+  const int id = va ? rt.ids[lane] : 0x7fffffff;
+  const uint64_t lt = lanemask_lt(lane);
+  if (grp < rt.E) {
+    const uint64_t mine = __ballot(va && id == grp);
+    m0 = __popcll(__ballot(va && id < grp));
+    Me = __popcll(mine);
+    const int before = __popcll(mine & lt);
+    // members go to lanes 0 .. Me-1 in order, the others fill the lanes behind them: a permutation
+    const int dest = ((mine >> lane) & 1ull) ? before : Me + lane - before;
+    row_token = __builtin_amdgcn_ds_permute(dest << 2, lane / rt.top_k);
+  } else {
+    m0 = n_assign + (grp - rt.E) * rt.T;
+    Me = rt.T;
+    row_token = lane;
+  }
+  if (writer) {
+    int pos = 0, base = 0, my_off = 0;
+    for (int e = 0; e < rt.E; ++e) {
+      const uint64_t m = __ballot(va && id == e);
+      if (va && id == e) pos = base + __popcll(m & lt);
+      if (lane == e) my_off = base;
+      base += __popcll(m);
+    }
+    if (lane < rt.E) rt.offsets[lane] = my_off;
+    if (lane == 0) rt.offsets[rt.E] = n_assign;
+    for (int sh = lane; sh < rt.S; sh += 64) rt.offsets[rt.E + sh + 1] = n_assign + (sh + 1) * rt.T;
+    if (va) {
+      rt.perm[pos] = lane;
+      rt.inv_perm[lane] = pos;
+      rt.src_token[pos] = lane / rt.top_k;
+    }
+    for (int i = lane; i < rt.S * rt.T; i += 64) rt.src_token[n_assign + i] = i % rt.T;
+  }
+}
+
 }  // namespace cq_route

@@ -174,19 +174,14 @@ cq_status cq_hadamard_quant_launch(const float* Hin, int M, int I, int bits, int
   int m, p, k;
   if (!had_split(I, &m, &p, &k)) return CQ_ERR_SHAPE;
   if (M == 0) return CQ_OK;
-  static bool configured = false;
-  if (!configured) {
-    const int lds = kHadMaxI * 4;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_kernel<1>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_kernel<12>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_kernel<28>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_kernel<44>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+  {
+    static std::atomic<bool> c1{false}, c12{false}, c28{false}, c44{false};
+    constexpr int kMaxLds = kHadMaxI * 4;
+    if (cq_configure_lds(hadamard_quant_kernel<1>, kMaxLds, c1, false) != CQ_OK ||
+        cq_configure_lds(hadamard_quant_kernel<12>, kMaxLds, c12, false) != CQ_OK ||
+        cq_configure_lds(hadamard_quant_kernel<28>, kMaxLds, c28, false) != CQ_OK ||
+        cq_configure_lds(hadamard_quant_kernel<44>, kMaxLds, c44, false) != CQ_OK)
       return CQ_ERR_HIP;
-    configured = true;
   }
   const float qmax = (float)((1 << (bits - 1)) - 1);
   const size_t lds = (size_t)I * 4;

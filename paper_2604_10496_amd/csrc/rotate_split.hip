@@ -370,16 +370,9 @@ size_t cq_rotate_split_workspace_bytes(int T, int H) {
 // X_R = X R from the split R; XR_out [T, H] fp32.  workspace: cq_rotate_split_workspace_bytes(T, H).
 cq_status cq_rotate_split_launch(const float* X, const void* R_split, int T, int H, float* XR_out, void* workspace,
                                  hipStream_t s) {
-  static bool configured = false;
-  if (!configured) {
-    hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(rot_split_kernel)) != hipSuccess) return CQ_ERR_HIP;
-    if (fa.sharedSizeBytes != 0) return CQ_ERR_HIP;  // dynamic LDS must start at address 0
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(rot_split_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kRotLdsBytes) != hipSuccess)
-      return CQ_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<bool> configured{false};
+  const cq_status cst = cq_configure_lds(rot_split_kernel, kRotLdsBytes, configured, true);
+  if (cst != CQ_OK) return cst;
   char* ws = (char*)workspace;
   float* row_pow2 = (float*)ws;
   uint16_t* Xh = (uint16_t*)(ws + cq_align_up((size_t)T * sizeof(float), 256));
