@@ -41,16 +41,51 @@ def _stale(src: str, obj: str) -> bool:
     return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
 
 
+def _split_resource_remarks(lines):
+    """Separates hipcc's kernel-resource-usage remarks ({kernel: {field: value}}) from its other output."""
+    usage, rest, cur, skip = {}, [], None, 0
+    for l in lines:
+        if skip:                      # the two source-excerpt lines clang prints under a remark
+            skip -= 1
+            continue
+        if "[-Rpass-analysis=kernel-resource-usage]" in l:
+            body = l.split("remark:", 1)[1].rsplit("[-Rpass-analysis", 1)[0].strip()
+            if body.startswith("Function Name:"):
+                cur = body.split(":", 1)[1].strip()
+                usage[cur] = {}
+                skip = 2
+            elif cur is not None and ":" in body:
+                k, v = body.rsplit(":", 1)
+                try:
+                    usage[cur][k.strip()] = int(v)
+                except ValueError:
+                    pass
+            continue
+        rest.append(l)
+    return usage, rest
+
+
 def _compile(src: str, force: bool = True) -> str:
     obj = os.path.join(BUILD_DIR, src[:-4] + ".o")
     if not force and not _stale(src, obj):
         return obj
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    lines = [l for l in res.stderr.splitlines() if noise not in l]
+    usage, err = _split_resource_remarks(lines)
+    err = "\n".join(err)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+    # Kernels that issue register loads from inline assembly and wait for them later (cq_async.h) must not spill:
+    # a spill or reload of a register with a load in flight would store or restore a stale value.
+    with open(os.path.join(CSRC, src)) as f:
+        if "cq_async.h" in f.read():
+            bad = [(k, u) for k, u in usage.items() if u.get("VGPRs Spill", 0) or u.get("ScratchSize [bytes/lane]", 0)]
+            if bad:
+                if os.path.exists(obj):
+                    os.remove(obj)
+                raise RuntimeError(f"{src}: kernels with asynchronous register loads spill: {bad}")
     if err.strip():
         print(err, file=sys.stderr)
     return obj

@@ -1124,7 +1124,7 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     // the grid (a grid over all groups would leave most workgroups without work)
     st = cq_gemm_build_lists(W, group_offsets, M_total, small_max,
                              W->G > kListedWorkgroups ? W->G : kListedWorkgroups, large_ws, &a.small_hdr,
-                             &a.small_ids, s);
+                             &a.small_ids, s, cq_gemm_large_tail_split(W, epilogue, out_kind));
     if (st != CQ_OK) return st;
   }
   if (blockwise) {
@@ -1184,7 +1184,7 @@ extern "C" size_t cq_grouped_gemm_workspace_bytes(const cq_codebook_weights* W, 
   for (const int epi : {CQ_EPI_NONE, CQ_EPI_SWIGLU}) {   // the kernel, and with it the need, can depend on the epilogue
     size_t n = cq_gemm_partials_bytes(W, M_total, epi);
     if (cq_gemm_uses_large_tiles(W, M_total, epi))
-      n += cq_gemm_large_workspace_bytes(W->G, M_total, W->K, true);  // worst case over the operand kinds
+      n += cq_gemm_large_workspace_bytes(W->G, M_total, W->K, true, W->N);  // worst case over the operand kinds
     if (n > need) need = n;
   }
   return need;

@@ -57,7 +57,20 @@ struct LargeArgs {
   // out + z * part_stride elements; ksteps covers all of K when there is no split
   int ksteps;
   size_t part_stride;
+  // K split of the narrow tiles of a plain fp32 product with a long K (tail_part != NULL): the builder chooses
+  // S = n_tiles[6] in {1, 2, 4}; split z > 0 of the j-th 128-token (64-token) tile stores its partial sums at
+  // rows j*128 (tail_rows128 + j*64) of slice z-1 of tail_part, [S-1][tail_rows][N] fp32, and tail_sum_kernel
+  // adds them to `out` in the order z = 1, 2, ...
+  float* tail_part;
+  int tail_rows128;   // rows reserved for the 128-token tiles (capacity of that list * 128)
+  int tail_rows;      // rows per slice
 };
+
+#ifndef CQ_TAIL_SPLIT_MAX
+#define CQ_TAIL_SPLIT_MAX 4
+#endif
+constexpr int kTailSplitMax = CQ_TAIL_SPLIT_MAX;   // most K parts a narrow tile is cut into (1: never)
+constexpr int kTailMinSteps = 128;   // K steps (of 64) from which the narrow tiles of a plain product may be split
 
 __device__ __forceinline__ uint32_t f32_to_f16_sat(float x) {
   x = fminf(fmaxf(x, -65504.f), 65504.f);
@@ -91,9 +104,12 @@ constexpr int epilogue_row_stride(int epi, int outk) {
 // pipeline in K steps (a power of two; narrow tiles spend less matrix time per step and need more).
 // BLK: block-wise centroid tables (p.nblk per row, each serving p.gsteps K steps).  PRE: the indices are the
 // prepacked copy (whose nibble arrangement decodes with four operations fewer per 8 weights).
+// kz / kS: this workgroup takes part kz of kS equal parts of K (narrow tiles of a plain fp32 product; 0 / 1
+// otherwise) and, for kz > 0, stores at row tail_row0 of slice kz-1 of p.tail_part instead of p.out.
 template <bool F16, int EPI, int OUTK, int C, int D, bool BLK, bool PRE>
 __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, const int mrow0, const int mcnt,
-                                           const int rt) {
+                                           const int rt, const int kz = 0, const int kS = 1, const int tail_row0 = 0) {
+  constexpr bool kTail = !BLK && EPI == CQ_EPI_NONE && OUTK == CQ_OUT_F32 && C <= 4;
   constexpr int CT = 32 * C;
   constexpr uint32_t kBufBytes = CT * kStepBytes;  // one activation tile: CT tokens x 128 bytes
 
@@ -115,9 +131,16 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
     sstride = 32;
   }
   // this workgroup's K range: steps [sb, sb + nS) (all of K unless the launch splits K)
-  const int sb = BLK ? (int)blockIdx.y * p.ksteps : 0;
-  const int nS = BLK ? min(p.ksteps, K / kStepK - sb) : K / kStepK;
-  if constexpr (BLK) {
+  int sb = BLK ? (int)blockIdx.y * p.ksteps : 0;
+  int nS = BLK ? min(p.ksteps, K / kStepK - sb) : K / kStepK;
+  if constexpr (kTail) {
+    if (kS > 1) {   // equal parts of an even number of steps (the last one takes what is left: at least two)
+      const int per = ((nS + kS - 1) / kS + 1) & ~1;
+      sb = kz * per;
+      nS = min(per, nS - sb);
+    }
+  }
+  if constexpr (BLK || kTail) {
     wp0 += (size_t)sb * sstride;
     wp1 += (size_t)sb * sstride;
   }
@@ -374,6 +397,11 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
         const uint32_t at = (uint32_t)tl * kRowStride + (uint32_t)pc * kPiece;
         char* dst = reinterpret_cast<char*>(p.out) + ((size_t)(mrow0 + tok) * p.out_ld + out_col0) * kEsize + (size_t)pc * kPiece;
         if constexpr (BLK) dst += (size_t)blockIdx.y * p.part_stride * kEsize;
+        if constexpr (kTail) {
+          if (kz > 0)
+            dst = reinterpret_cast<char*>(p.tail_part) +
+                  (((size_t)(kz - 1) * p.tail_rows + tail_row0 + tok) * p.out_ld + out_col0) * kEsize + (size_t)pc * kPiece;
+        }
         if constexpr (kPiece == 16)
           *reinterpret_cast<cq_v4u*>(dst) = *reinterpret_cast<const lds_v4u*>((uintptr_t)at);
         else
@@ -390,7 +418,9 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
 // equal mix on every XCD).  The grid is sized for the worst case; the lists are usually much shorter.
 template <bool F16, int EPI, int OUTK, bool BLK, bool PRE>
 __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
-  const int n256 = p.n_tiles[0] * p.row_tiles, n128 = p.n_tiles[1] * p.row_tiles, n64 = p.n_tiles[5] * p.row_tiles;
+  const int kS = p.tail_part ? p.n_tiles[6] : 1;   // K parts of a narrow tile
+  const int n256 = p.n_tiles[0] * p.row_tiles, n128 = p.n_tiles[1] * p.row_tiles * kS,
+            n64 = p.n_tiles[5] * p.row_tiles * kS;
   const int per256 = (n256 + 7) >> 3, per128 = (n128 + 7) >> 3, per64 = (n64 + 7) >> 3;
   const int xcd = blockIdx.x & 7;
   int slot = blockIdx.x >> 3;
@@ -406,24 +436,69 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   if (slot < per128) {
     const int work = xcd * per128 + slot;
     if (work >= n128) return;
-    const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
+    const int item = work / kS, kz = work - item * kS;
+    const int tile = item / p.row_tiles, rt = item - tile * p.row_tiles;
     const int32_t* t = p.tiles128 + tile * 4;
-    large_tile<F16, EPI, OUTK, 4, 8, BLK, PRE>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 4, 8, BLK, PRE>(p, t[0], t[1], t[2], rt, kz, kS, tile * 128);
     return;
   }
   slot -= per128;
   if (slot < per64) {
     const int work = xcd * per64 + slot;
     if (work >= n64) return;
-    const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
+    const int item = work / kS, kz = work - item * kS;
+    const int tile = item / p.row_tiles, rt = item - tile * p.row_tiles;
     const int32_t* t = p.tiles64 + tile * 4;
-    large_tile<F16, EPI, OUTK, 2, 8, BLK, PRE>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 2, 8, BLK, PRE>(p, t[0], t[1], t[2], rt, kz, kS, p.tail_rows128 + tile * 64);
+  }
+}
+
+// out[row] += slice 0 + slice 1 + ... of the narrow tiles' K parts, in that order (see LargeArgs::tail_part).
+// blockIdx.y: entry of the 128-token list, then of the 64-token list; blockIdx.x: 1024 columns; blockIdx.z: 8 rows.
+constexpr int kTailSumRows = 8;
+__global__ __launch_bounds__(256) void tail_sum_kernel(const LargeArgs p, int cap128) {
+  const int kS = p.n_tiles[6];
+  if (kS <= 1) return;
+  const bool is64 = (int)blockIdx.y >= cap128;
+  const int j = is64 ? (int)blockIdx.y - cap128 : (int)blockIdx.y;
+  if (j >= (is64 ? p.n_tiles[5] : p.n_tiles[1])) return;
+  const int32_t* t = (is64 ? p.tiles64 : p.tiles128) + j * 4;
+  const int mrow0 = t[1], mcnt = t[2];
+  const int row0 = is64 ? p.tail_rows128 + j * 64 : j * 128;
+  const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+  const int r0 = blockIdx.z * kTailSumRows;
+  if (c >= p.N || r0 >= mcnt) return;
+  float* out = reinterpret_cast<float*>(p.out);
+  float4 acc[kTailSumRows], part[kTailSumRows][kTailSplitMax > 1 ? kTailSplitMax - 1 : 1];
+#pragma unroll
+  for (int i = 0; i < kTailSumRows; ++i) {   // all loads first (rows past the tile's end read its last row)
+    const int r = min(r0 + i, mcnt - 1);
+    acc[i] = *reinterpret_cast<const float4*>(out + (size_t)(mrow0 + r) * p.N + c);
+#pragma unroll
+    for (int z = 1; z < kTailSplitMax; ++z)
+      if (z < kS)
+        part[i][z - 1] = *reinterpret_cast<const float4*>(p.tail_part + ((size_t)(z - 1) * p.tail_rows + row0 + r) * p.N + c);
+  }
+#pragma unroll
+  for (int i = 0; i < kTailSumRows; ++i) {
+    if (r0 + i >= mcnt) break;
+#pragma unroll
+    for (int z = 1; z < kTailSplitMax; ++z)
+      if (z < kS) {
+        acc[i].x += part[i][z - 1].x; acc[i].y += part[i][z - 1].y;
+        acc[i].z += part[i][z - 1].z; acc[i].w += part[i][z - 1].w;
+      }
+    *reinterpret_cast<float4*>(out + (size_t)(mrow0 + r0 + i) * p.N + c) = acc[i];
   }
 }
 
 // Narrow tiles alone, for launches in which no group has more than 64 (C = 2) or 32 (C = 1) rows (block-wise
 // tables at decode sizes): few accumulators and at most half the LDS, so two workgroups share a compute
 // unit.  The list of 64-token tiles holds one entry per non-empty group in such a launch.
+// (pipeline depth: 8 steps for 32-token tiles; 4 for 64-token tiles, whose accumulators leave no room for the
+// register ring of 8 -- with 8 the bf16 instantiations spilled one or two registers, which kernels with
+// asynchronous register loads must not do)
+constexpr int narrow_depth(int C) { return C >= 2 ? 4 : 8; }
 template <bool F16, int EPI, int OUTK, bool BLK, bool PRE, int C>
 __global__ __launch_bounds__(256, 2) void gemm_narrow_kernel(const LargeArgs p) {
   const int n64 = p.n_tiles[5] * p.row_tiles;
@@ -434,7 +509,7 @@ __global__ __launch_bounds__(256, 2) void gemm_narrow_kernel(const LargeArgs p) 
   if (work >= n64) return;
   const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
   const int32_t* t = p.tiles64 + tile * 4;
-  large_tile<F16, EPI, OUTK, C, 8, BLK, PRE>(p, t[0], t[1], t[2], rt);
+  large_tile<F16, EPI, OUTK, C, narrow_depth(C), BLK, PRE>(p, t[0], t[1], t[2], rt);
 }
 
 // Pre-pass for activation kinds the main kernel does not read: sorted row m of the result is row
@@ -473,13 +548,13 @@ __global__ __launch_bounds__(256) void convert_rows_kernel(const void* __restric
 // than 128 rows remain), then one of 128 or (up to 64 rows left) 64, in group order (deterministic), and list the non-empty groups with up
 // to `small_max` rows for the streaming kernel, together with a split of their 64-row units over
 // `small_wgs` workgroups.  counts: [0] 256-wide tiles, [1] 128-wide tiles, [2] small groups,
-// [3] units per workgroup, [4] workgroups per small group, [5] 64-wide tiles.
+// [3] units per workgroup, [4] workgroups per small group, [5] 64-wide tiles, [6] K parts of the narrow tiles.
 __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __restrict__ offsets, int G, int small_max,
                                                            int n_units, int small_wgs,
                                                            int32_t* __restrict__ tiles256, int32_t* __restrict__ tiles128,
                                                            int32_t* __restrict__ tiles64,
                                                            int32_t* __restrict__ small_groups,
-                                                           int32_t* __restrict__ counts) {
+                                                           int32_t* __restrict__ counts, int split_max) {
   __shared__ int n256[1024], n128[1024], n64[1024], nsm[1024];
   __shared__ int base256, base128, base64, basesm;
   const int tid = threadIdx.x;
@@ -539,6 +614,15 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
     counts[1] = base128;
     counts[2] = basesm;
     counts[5] = base64;
+    // [6] K parts of the narrow tiles (split_max > 1: a plain fp32 product with a long K).  The narrow tiles
+    // come last; when there are fewer of them than compute units, the tail of the launch runs on a part of the
+    // chip for the length of a whole K loop -- parts of K on more workgroups shorten it.
+    {
+      const int narrow = (base128 + base64) * (n_units / 4);
+      int parts = 1;
+      while (parts < split_max && narrow > 0 && narrow * parts * 2 <= 256) parts *= 2;
+      counts[6] = parts;
+    }
     // fewest units per workgroup such that all small groups fit into small_wgs workgroups
     int upw = 1, chunks = n_units;
     if (basesm > 0) {
@@ -555,7 +639,7 @@ template <bool F16, int EPI, int OUTK, bool BLK, bool PRE, int C>
 cq_status launch_narrow(const LargeArgs& a, int max128, hipStream_t s) {
   auto kern = gemm_narrow_kernel<F16, EPI, OUTK, BLK, PRE, C>;
   constexpr int lds_epi = 64 * epilogue_row_stride(EPI, OUTK);
-  constexpr int lds_loop = 8 * 32 * C * kStepBytes + (BLK ? 8 * kNextTableBytes : 0);
+  constexpr int lds_loop = narrow_depth(C) * 32 * C * kStepBytes + (BLK ? 8 * kNextTableBytes : 0);
   constexpr int lds = lds_loop > lds_epi ? lds_loop : lds_epi;
   static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
   static std::atomic<bool> configured{false};
@@ -589,7 +673,8 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
   if (st != CQ_OK) return st;
   // worst case of the kernel's per-XCD shares (a group ends in at most one 128- or 64-token tile, but the
   // two lists round up separately): ceil(n256/8) + ceil(n128/8) + ceil(n64/8) slots on each of 8 XCDs
-  const long w256 = (long)max256 * a.row_tiles, w128 = (long)max128 * a.row_tiles;
+  const long w256 = (long)max256 * a.row_tiles,
+             w128 = (long)max128 * a.row_tiles * (a.tail_part ? kTailSplitMax : 1);   // (narrow tiles may come in K parts)
   const long grid = ((w256 + 7) / 8 + (w128 + 7) / 8 + 1) * 8;
   if (grid <= 0) return CQ_OK;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, a);
@@ -641,9 +726,26 @@ void cq_large_tile_caps(int G, int M_total, int* cap256, int* cap128) {
   if (*cap128 < 1) *cap128 = 1;
 }
 
-// tile lists, plus (with_conversion) room for the activations as 16-bit rows [M_total, K]
-size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion) {
+// Narrow tiles of a plain fp32 product with a long K may be cut into K parts (LargeArgs::tail_part).
+bool cq_gemm_large_tail_split(const cq_codebook_weights* W, int epilogue, int out_kind) {
+  return epilogue == CQ_EPI_NONE && out_kind == CQ_OUT_F32 && cq_tables_per_row(W) == 1 &&
+         W->K / kStepK >= kTailMinSteps;
+}
+
+namespace {
+// partial sums of those K parts: [kTailSplitMax - 1][cap128 * (128 + 64)][N] fp32
+size_t tail_part_bytes(int G, int M_total, int N) {
+  int c256, c128;
+  cq_large_tile_caps(G, M_total, &c256, &c128);
+  return cq_align_up((size_t)(kTailSplitMax - 1) * c128 * 192 * N * sizeof(float), 256);
+}
+}  // namespace
+
+// tile lists, plus (tail_N > 0: a plain fp32 product of N columns whose K is long enough) the partial sums of
+// the narrow tiles' K parts, plus (with_conversion) room for the activations as 16-bit rows [M_total, K]
+size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion, int tail_N) {
   size_t n = tile_list_bytes(G, M_total);
+  if (tail_N > 0 && K / kStepK >= kTailMinSteps) n += tail_part_bytes(G, M_total, tail_N);
   if (with_conversion) n += cq_align_up((size_t)M_total * K * sizeof(uint16_t), 256);
   return n;
 }
@@ -661,7 +763,7 @@ bool cq_gemm_large_supported(const cq_codebook_weights* W) {
 // unused} followed by the group ids... as two pointers: *small_hdr -> counts + 2, *small_ids -> ids.
 cq_status cq_gemm_build_lists(const cq_codebook_weights* W, const int32_t* group_offsets, int M_total, int small_max,
                               int small_wgs, void* workspace, const int32_t** small_hdr, const int32_t** small_ids,
-                              hipStream_t s) {
+                              hipStream_t s, bool tail_split) {
   int cap256, cap128;
   cq_large_tile_caps(W->G, M_total, &cap256, &cap128);
   int32_t* counts = (int32_t*)workspace;
@@ -670,7 +772,7 @@ cq_status cq_gemm_build_lists(const cq_codebook_weights* W, const int32_t* group
   int32_t* t64 = t128 + (size_t)cap128 * 4;
   int32_t* small = t64 + (size_t)cap128 * 4;
   hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, s, group_offsets, W->G, small_max, W->N / 64, small_wgs,
-                     t256, t128, t64, small, counts);
+                     t256, t128, t64, small, counts, tail_split ? kTailSplitMax : 1);
   *small_hdr = counts + 2;
   *small_ids = small;
   return cq_check_launch();
@@ -709,9 +811,20 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
     cq_gemm_split_plan(W, M_total, epilogue, &ksplit, &a.ksteps);  // a split is planned for 64-token launches only
     a.part_stride = ksplit > 1 ? (size_t)M_total * W->N : 0;
   }
+  // workspace: tile lists, then the partial sums of the narrow tiles' K parts (if the launch may split them:
+  // the builder was told so with the same rule), then the 16-bit copy of the rows
+  size_t ws_off = tile_list_bytes(W->G, M_total);
+  const bool tail = cq_gemm_large_tail_split(W, epilogue, out_kind);
+  a.tail_part = nullptr;
+  a.tail_rows128 = cap128 * 128;
+  a.tail_rows = cap128 * 192;
+  if (tail) {
+    a.tail_part = (float*)((char*)workspace + ws_off);
+    ws_off += tail_part_bytes(W->G, M_total, W->N);
+  }
   if (a_kind == CQ_A_INT8_CODES || a_kind == CQ_A_F32) {
     // 16-bit copy of the rows in sorted order (the gather is applied here)
-    uint16_t* A16 = (uint16_t*)((char*)workspace + tile_list_bytes(W->G, M_total));
+    uint16_t* A16 = (uint16_t*)((char*)workspace + ws_off);
     const size_t chunks = (size_t)M_total * (W->K / 8);
     const unsigned blocks = (unsigned)((chunks + 255) / 256);
     if (a_kind == CQ_A_INT8_CODES)
@@ -726,6 +839,13 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
   const bool f16 = a_kind == CQ_A_F16 || a_kind == CQ_A_F32;
   // with so few rows in all, every group has at most that many: one narrow tile each
   const int narrow = M_total <= 32 ? 32 : M_total <= 64 ? 64 : 0;
-  return f16 ? dispatch_large<true>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, narrow, s)
-             : dispatch_large<false>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, narrow, s);
+  const cq_status st = f16 ? dispatch_large<true>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, narrow, s)
+                           : dispatch_large<false>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, narrow, s);
+  if (st != CQ_OK || !tail) return st;
+  // (a launch of a few dozen workgroups that return at once when the builder chose not to split)
+  a.tiles128 = t128;
+  a.tiles64 = t128 + (size_t)cap128 * 4;
+  a.n_tiles = counts;
+  hipLaunchKernelGGL(tail_sum_kernel, dim3((W->N / 4 + 255) / 256, 2 * cap128, 128 / kTailSumRows), dim3(256), 0, s, a, cap128);
+  return cq_check_launch();
 }

@@ -142,12 +142,14 @@ bool cq_gemm_uses_large_tiles(const cq_codebook_weights* W, int M_total, int epi
                               int max_group_rows = 0);
 // with_conversion: include room for a 16-bit copy of the activation rows (needed for CQ_A_INT8_CODES
 // and CQ_A_F32 operands; bf16 / f16 operands are read in place)
-size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion);
+size_t cq_gemm_large_workspace_bytes(int G, int M_total, int K, bool with_conversion, int tail_N = 0);
+// narrow tiles of a plain fp32 product with a long K are cut into K parts (their partial sums live in the workspace)
+bool cq_gemm_large_tail_split(const cq_codebook_weights* W, int epilogue, int out_kind);
 // work lists of a launch that uses both kernels (device-built: group sizes are device data); small_hdr:
 // {number of small groups, 64-row units per workgroup, workgroups per small group}, small_ids: their ids
 cq_status cq_gemm_build_lists(const cq_codebook_weights* W, const int32_t* group_offsets, int M_total, int small_max,
                               int small_wgs, void* workspace, const int32_t** small_hdr, const int32_t** small_ids,
-                              hipStream_t s);
+                              hipStream_t s, bool tail_split = false);
 cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int a_kind, const float* row_scale,
                                const int32_t* row_gather, const int32_t* group_offsets, int M_total, int small_max,
                                int epilogue, void* out, int out_kind, void* workspace, hipStream_t s);

@@ -103,7 +103,7 @@ void make_layout(const cq_layer* L, int T, cq_moe_layout* o) {
   {
     size_t g2 = cq_gemm_partials_bytes(&L->down, (int)M, CQ_EPI_NONE, T);   // (a group has at most T rows)
     if (cq_gemm_uses_large_tiles(&L->down, (int)M, CQ_EPI_NONE, T))  // (16-bit operands in either variant: f16 h or bf16 codes)
-      g2 += cq_gemm_large_workspace_bytes(L->down.G, (int)M, L->down.K, false);
+      g2 += cq_gemm_large_workspace_bytes(L->down.G, (int)M, L->down.K, false, L->down.N);
     if (g2 > scratch) scratch = g2;
   }
   o->scratch = take(scratch);

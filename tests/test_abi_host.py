@@ -152,3 +152,28 @@ def test_prepack_layout_documented_in_header_matches_numpy_model():
             assert got == want
     assert sorted(np.concatenate([packed & 15, packed >> 4]).tolist()) == \
         sorted(np.concatenate([idx.reshape(-1) & 15, idx.reshape(-1) >> 4]).tolist())
+
+
+def test_build_reads_spill_counts_from_the_compiler_remarks():
+    """build.py refuses kernels with asynchronous register loads that spill; its reader of hipcc's resource
+    remarks is checked on a sample of that output."""
+    from paper_2604_10496_amd import build
+    tag = "[-Rpass-analysis=kernel-resource-usage]"
+    sample = [
+        f"a.hip:12:1: remark: Function Name: kern_a {tag}",
+        "   12 | __global__ void kern_a() {",
+        "      | ^",
+        f"a.hip:12:1: remark:     VGPRs: 34 {tag}",
+        f"a.hip:12:1: remark:     ScratchSize [bytes/lane]: 0 {tag}",
+        f"a.hip:12:1: remark:     VGPRs Spill: 0 {tag}",
+        "a.hip:40:3: warning: something else",
+        f"a.hip:50:1: remark: Function Name: kern_b {tag}",
+        "   50 | __global__ void kern_b() {",
+        "      | ^",
+        f"a.hip:50:1: remark:     ScratchSize [bytes/lane]: 8 {tag}",
+        f"a.hip:50:1: remark:     VGPRs Spill: 2 {tag}",
+    ]
+    usage, rest = build._split_resource_remarks(sample)
+    assert usage == {"kern_a": {"VGPRs": 34, "ScratchSize [bytes/lane]": 0, "VGPRs Spill": 0},
+                     "kern_b": {"ScratchSize [bytes/lane]": 8, "VGPRs Spill": 2}}
+    assert rest == ["a.hip:40:3: warning: something else"]

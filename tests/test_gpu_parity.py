@@ -266,7 +266,12 @@ def _rand_weights(rng, G, N, K, cent=None):
                                         # long K with few rows: K is split over workgroups and the partial
                                         # sums are added afterwards (also next to large-tile groups, and
                                         # with a token block of 17..32 rows that restages inside its range)
-                                        (64, 8192, [3, 0, 9]), (128, 14336, [5, 17, 33]), (256, 8192, [40, 7])])
+                                        (64, 8192, [3, 0, 9]), (128, 14336, [5, 17, 33]), (256, 8192, [40, 7]),
+                                        # long K on the large-tile kernel: the 128- and 64-token tiles at the
+                                        # end of the groups are cut into K parts whose partial sums are added
+                                        # afterwards (4, 2 or 1 parts, chosen on the device from the tile counts)
+                                        (512, 14336, [150, 300, 70, 31]), (256, 8192, [200, 64, 129, 0, 90]),
+                                        (2048, 8192, [100, 50, 520]), (256, 9088, [77])])
 def test_gemm_integer_centroids_exact(B, N, K, counts, prepacked):
     """Centroids k-8 and integer codes: every partial sum is an integer below 2^24, so the result must
     equal the exact integer product whatever the summation order."""
