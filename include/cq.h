@@ -268,7 +268,7 @@ cq_status cq_moe_forward(const cq_layer* L, const float* X, int T, float* Y,
  * the library itself holds in the device memory of every GPU it has run on (until the process ends).  The
  * call allocates and frees nothing and does not synchronise the host.
  *   A batch whose cq_moe_workspace_bytes(L, T) exceeds CQ_STATIC_SCRATCH_BYTES returns CQ_ERR_WORKSPACE
- *   and launches nothing (the Mixtral-8x7B shape fits up to T = 128 tokens).
+ *   and launches nothing (the Mixtral-8x7B shape fits up to T = 96 tokens).
  *   All calls on one GPU share the array, which keeps the previous call's contents (no kernel of the layer
  *   needs it cleared): calls that overlap on one GPU -- two streams, two threads -- race; serialise them.
  */

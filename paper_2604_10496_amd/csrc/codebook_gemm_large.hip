@@ -59,11 +59,13 @@ struct LargeArgs {
   size_t part_stride;
   // K split of the narrow tiles of a plain fp32 product with a long K (tail_part != NULL): the builder chooses
   // S = n_tiles[6] in {1, 2, 4}; split z > 0 of the j-th 128-token (64-token) tile stores its partial sums at
-  // rows j*128 (tail_rows128 + j*64) of slice z-1 of tail_part, [S-1][tail_rows][N] fp32, and tail_sum_kernel
-  // adds them to `out` in the order z = 1, 2, ...
+  // rows j*128 (tail_rows128 + j*64) of slice z-1 of tail_part, [S-1][tail_rows][N] fp32 -- or, when the launch
+  // has fewer rows than such slots (tail_abs), at the tile's own sorted rows -- and tail_sum_kernel adds them to
+  // `out` in the order z = 1, 2, ...
   float* tail_part;
   int tail_rows128;   // rows reserved for the 128-token tiles (capacity of that list * 128)
   int tail_rows;      // rows per slice
+  int tail_abs;       // 1: a slice has M_total rows and a tile stores at its own sorted rows (fewer rows than slots)
 };
 
 #ifndef CQ_TAIL_SPLIT_MAX
@@ -439,7 +441,7 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     const int item = work / kS, kz = work - item * kS;
     const int tile = item / p.row_tiles, rt = item - tile * p.row_tiles;
     const int32_t* t = p.tiles128 + tile * 4;
-    large_tile<F16, EPI, OUTK, 4, 8, BLK, PRE>(p, t[0], t[1], t[2], rt, kz, kS, tile * 128);
+    large_tile<F16, EPI, OUTK, 4, 8, BLK, PRE>(p, t[0], t[1], t[2], rt, kz, kS, p.tail_abs ? t[1] : tile * 128);
     return;
   }
   slot -= per128;
@@ -449,7 +451,8 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
     const int item = work / kS, kz = work - item * kS;
     const int tile = item / p.row_tiles, rt = item - tile * p.row_tiles;
     const int32_t* t = p.tiles64 + tile * 4;
-    large_tile<F16, EPI, OUTK, 2, 8, BLK, PRE>(p, t[0], t[1], t[2], rt, kz, kS, p.tail_rows128 + tile * 64);
+    large_tile<F16, EPI, OUTK, 2, 8, BLK, PRE>(p, t[0], t[1], t[2], rt, kz, kS,
+                                               p.tail_abs ? t[1] : p.tail_rows128 + tile * 64);
   }
 }
 
@@ -464,7 +467,7 @@ __global__ __launch_bounds__(256) void tail_sum_kernel(const LargeArgs p, int ca
   if (j >= (is64 ? p.n_tiles[5] : p.n_tiles[1])) return;
   const int32_t* t = (is64 ? p.tiles64 : p.tiles128) + j * 4;
   const int mrow0 = t[1], mcnt = t[2];
-  const int row0 = is64 ? p.tail_rows128 + j * 64 : j * 128;
+  const int row0 = p.tail_abs ? mrow0 : is64 ? p.tail_rows128 + j * 64 : j * 128;
   const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
   const int r0 = blockIdx.z * kTailSumRows;
   if (c >= p.N || r0 >= mcnt) return;
@@ -733,11 +736,19 @@ bool cq_gemm_large_tail_split(const cq_codebook_weights* W, int epilogue, int ou
 }
 
 namespace {
-// partial sums of those K parts: [kTailSplitMax - 1][cap128 * (128 + 64)][N] fp32
-size_t tail_part_bytes(int G, int M_total, int N) {
+// rows of a slice of partial sums: a slot per possible narrow tile (128 + 64 rows per group), or the launch's own
+// rows when those are fewer
+int tail_slice_rows(int G, int M_total, bool* absolute) {
   int c256, c128;
   cq_large_tile_caps(G, M_total, &c256, &c128);
-  return cq_align_up((size_t)(kTailSplitMax - 1) * c128 * 192 * N * sizeof(float), 256);
+  *absolute = M_total < c128 * 192;
+  return *absolute ? M_total : c128 * 192;
+}
+// partial sums of those K parts: [kTailSplitMax - 1][rows of a slice][N] fp32
+size_t tail_part_bytes(int G, int M_total, int N) {
+  bool absolute;
+  const int rows = tail_slice_rows(G, M_total, &absolute);
+  return cq_align_up((size_t)(kTailSplitMax - 1) * rows * N * sizeof(float), 256);
 }
 }  // namespace
 
@@ -817,7 +828,11 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
   const bool tail = cq_gemm_large_tail_split(W, epilogue, out_kind);
   a.tail_part = nullptr;
   a.tail_rows128 = cap128 * 128;
-  a.tail_rows = cap128 * 192;
+  {
+    bool absolute;
+    a.tail_rows = tail_slice_rows(W->G, M_total, &absolute);
+    a.tail_abs = absolute ? 1 : 0;
+  }
   if (tail) {
     a.tail_part = (float*)((char*)workspace + ws_off);
     ws_off += tail_part_bytes(W->G, M_total, W->N);
