@@ -1098,8 +1098,13 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     a.part_stride = (size_t)M_total * W->N;
     // (a whole number of workgroups per (group, K range), at most 256 in all: 56 pairs take 4 each, not 5 --
     // 280 workgroups would run as a full round and a nearly empty one)
+    // Groups of more than 16 rows take the plain unit loop, which is about twice as slow per unit: when such
+    // groups are possible the launch gets twice the workgroups, so that the compute units the fast groups leave
+    // early pick up the rest of the slow ones.
+    const int row_bound = max_group_rows > 0 && max_group_rows < M_total ? max_group_rows : M_total;
+    const long target = row_bound > 16 ? 512 : 256;
     const long pairs = (long)W->G * a.ksplit;
-    const long per_pair = pairs < 256 ? 256 / pairs : 1;
+    const long per_pair = pairs < target ? target / pairs : 1;
     long upw = (W->N / 64 + per_pair - 1) / per_pair;
     if (upw < 1) upw = 1;
     a.upw = (int)upw;
@@ -1175,6 +1180,8 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
 
 bool cq_gemm_uses_large_tiles(const cq_codebook_weights* W, int M_total, int epilogue, int max_group_rows) {
   if (cq_tables_per_row(W) > 1 && cq_gemm_blockwise_streams(W, M_total, epilogue, max_group_rows)) return false;
+  // no group can have more rows than the streaming kernel takes: nothing for the large tiles to do
+  if (cq_tables_per_row(W) == 1 && max_group_rows > 0 && max_group_rows <= kSmallMaxRows) return false;
   return !cq_is_w2(W) && cq_gemm_large_supported(W) && (M_total > kSmallMaxRows || cq_tables_per_row(W) > 1);
 }
 

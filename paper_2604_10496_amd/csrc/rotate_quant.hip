@@ -227,7 +227,7 @@ cq_gemm_f32_plan cq_gemm_f32_make_plan(int T, int N, int K) {
   const int tm = p.mb == 4 ? 128 : 16;
   const int tn = p.mb == 4 ? 128 : 256;
   const long wgs = (long)((N + tn - 1) / tn) * ((T + tm - 1) / tm);
-  int ks = (int)((256 + wgs - 1) / wgs);
+  int ks = (int)(256 / wgs);   // K chunks such that one round of workgroups covers the launch (96 tiles: 2, not 3)
   if (ks > 16) ks = 16;
   if (ks > K / 64) ks = K / 64;
   if (ks < 1) ks = 1;

@@ -1056,6 +1056,11 @@ def test_layer_tiny(B):
     ("mixtral_prefill", dict(H=256, I=512, T=300)),
     ("dsv2lite", dict(H=256, I=192, T=100, E=16)),
     ("qwen3_zipf", dict(H=256, I=128, T=260, E=32)),
+    # 17..32 tokens: more than 32 rows in all, but no group can have more than the streaming kernel takes
+    ("mixtral_decode", dict(H=512, I=1024, T=17)),
+    ("mixtral_decode", dict(H=512, I=4352, T=32, E=4)),      # groups of 9..32 rows, K-split down product
+    ("mixtral_decode", dict(H=4096, I=256, T=24)),
+    ("mixtral_decode", dict(H=1024, I=512, T=48)),           # rotation in 5 K chunks
 ])
 def test_layer_reduced_shapes(B, name, over):
     cfg = synth.small_variant(synth.CONFIGS[name], **over)
