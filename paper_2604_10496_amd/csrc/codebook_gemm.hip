@@ -86,6 +86,7 @@ struct GemmArgs {
   int max_rows;             // groups with more rows are left to the large-tile kernel
   int ksteps;               // K steps (of 64) per K split; blockIdx.z selects the split
   int ksplit;               // number of K splits; > 1: scaled fp32 partial sums go to `partials`
+  int halves;               // 1, or 2: gridDim.z = ksplit * 2 (see the kernel)
   float* partials;          // [ksplit][M_total][N]
   size_t part_stride;       // M_total * N
   // device-built work list (launches that also use the large-tile kernel), else NULL: blockIdx.y is
@@ -109,7 +110,7 @@ __device__ __forceinline__ cq_v16f mfma32(const cq_v4u a, const uint4 b, cq_v16f
 }
 
 
-// QS > 0: a workgroup whose group has at most 16 rows and whose wavefronts have exactly QS K steps per unit
+// QS > 0: a workgroup whose group has at most 32 rows and whose wavefronts have exactly QS K steps per unit
 // runs the pipelined unit loop (run_units_pipe below); 0: that path is left out of the instantiation.
 // QT > 0: block-wise centroid tables, one per 512 * QT weights of a row (QT K steps per wavefront and table; QT
 // divides QS); the instantiation then holds nothing but the pipelined loop.  0: one table per row.
@@ -144,6 +145,10 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   }
   // Rows of this group: from the grouped layout, or -- a5 folded into this launch -- from the selected expert
   // ids themselves (cq_route::group_rows_from_ids).
+  // blockIdx.z = K range + ksplit * half: half 1 exists in launches in which groups of 17..32 rows are possible and
+  // takes rows 16.. of such a group in the pipelined unit loop
+  const int kz = p.halves > 1 ? (int)blockIdx.z % p.ksplit : (int)blockIdx.z;
+  const int half = p.halves > 1 ? (int)blockIdx.z / p.ksplit : 0;
   int m0, Me, row_token = 0;
   bool fused = false;
   if constexpr (QS > 0) fused = p.route.ids != nullptr;
@@ -155,6 +160,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     Me = p.group_offsets[grp + 1] - m0;
   }
   if (Me <= 0 || Me > p.max_rows) return;
+  if (half > 0 && (Me <= 16 || Me > 32)) return;   // (second halves exist for groups of 17..32 rows only)
   const int u1 = min(nUnits, u0 + upw);
   if (u0 >= u1) return;
   const size_t rowbytes = (size_t)K >> 1;
@@ -171,7 +177,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     lane_off1 = (size_t)(32 + r32) * rowbytes + g2 * 16;
     sstride = 32;
   }
-  const int sb = blockIdx.z * p.ksteps;             // first K step (of 64) of this workgroup's K range
+  const int sb = kz * p.ksteps;                     // first K step (of 64) of this workgroup's K range
   const int nS = min(p.ksteps, (K >> 6) - sb);      // its number of steps
   if (nS <= 0) return;
   const int Kl = nS << 6;
@@ -182,6 +188,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   const uint32_t lanebase0 = (uint32_t)(r32 * 4);
   const uint32_t lanebase1 = (uint32_t)((32 + r32) * 4);
   const int n_tb = (Me + 31) >> 5;
+  if (half > 0 && !(QS > 0 && nS == QS * NW)) return;   // (no pipelined loop here: the first half's workgroup takes all rows)
 
   // ---- up to 16 tokens, K range of exactly QS steps per wavefront: the unit loop as a pipeline ----
   // (described for up to 8 tokens; the form for 9..16 differs where WIDE says so)
@@ -194,6 +201,11 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   // before the barrier that ends unit u-1.
   // Ring slot hs % HD serves half step hs = 2q + row block (one 16-byte load per lane) and is refilled with
   // half step hs + HD, of this unit or of the next one, as soon as step q's lookups are issued.
+  // (a group of 17..32 rows is shared by two workgroups per run of units, 16 rows and the rest -- `half` above: it
+  // streams its indices twice, which is still faster than the plain loop below, whose 32-token slab holds a quarter
+  // of K and is restaged four times per unit)
+  const int pass_row0 = 16 * half;
+  const int pass_rows = min(16, Me - pass_row0);   // this workgroup's rows: m0 + pass_row0 .. + pass_rows - 1
   auto run_units_pipe = [&](auto wide_tag) {
     constexpr bool WIDE = decltype(wide_tag)::value;   // 9..16 tokens: see below
     constexpr int Q = QS > 0 ? QS : 1;
@@ -207,7 +219,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     constexpr int TB0 = QL / 2;
     const int i16 = lane & 15, g4 = lane >> 4;
     const int tcol = WIDE ? i16 : (i16 & 7);   // token column whose activations this lane holds
-    const bool tok = tcol < Me;             // ... a real token
+    const bool tok = tcol < pass_rows;      // ... a real token (of this pass's block of up to 16 rows)
     const bool grouped = p.prepacked != 0;
     constexpr uint32_t kRed = 2 * kTableBytes;   // partial buffers: [2][wave][16 registers][32 columns] floats
     const uint32_t slot = WIDE ? (uint32_t)lane : (uint32_t)(g4 * 8 + (i16 & 7));
@@ -269,9 +281,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
     __builtin_amdgcn_sched_barrier(0);
     float sc16 = 1.f;
     size_t arow = 0;
-    const int col_token = __shfl(row_token, tcol);   // (folded grouping: the token of this lane's column)
+    const int col_token = __shfl(row_token, pass_row0 + tcol);   // (folded grouping: the token of this lane's column)
     if (tok) {
-      const int m = m0 + tcol;
+      const int m = m0 + pass_row0 + tcol;
       const size_t src = fused ? (size_t)col_token : p.row_gather ? (size_t)p.row_gather[m] : (size_t)m;
       arow = src * K;
       if (p.row_scale) sc16 = p.row_scale[src];
@@ -318,13 +330,13 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
             sum += __uint_as_float(lds_read_u32(rb0 + (uint32_t)w * kWaveStride + (uint32_t)i * kRegStride));
           val[i] = sum;
         }
-        if (i16 < Me) {
-          const int m = m0 + i16;
+        if (i16 < pass_rows) {
+          const int m = m0 + pass_row0 + i16;
           const int r = 2 * wave;
           const int row = uu * 64 + (r >> 3) * 32 + ((r >> 2) & 1) * 16 + g4 * 4 + (r & 3);
           const float x0 = sc16 * val[0], x1 = sc16 * val[1];
           if (p.ksplit > 1) {  // partial sum of this K range (CQ_EPI_NONE only)
-            float* dst = p.partials + (size_t)blockIdx.z * p.part_stride + (size_t)m * N + row;
+            float* dst = p.partials + (size_t)kz * p.part_stride + (size_t)m * N + row;
             *reinterpret_cast<float2*>(dst) = make_float2(x0, x1);
           } else if constexpr (EPI == CQ_EPI_SWIGLU) {
             const float h0 = x0 / (1.f + __expf(-x0)) * x1;
@@ -463,8 +475,8 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
   };
 #ifndef CQ_NO_PIPE
   if constexpr (QS > 0) {
-    if (Me <= 16 && nS == QS * NW) {   // every wavefront has exactly QS real steps
-      if (Me <= 8) run_units_pipe(std::false_type{});
+    if (Me <= 16 * p.halves && nS == QS * NW) {   // every wavefront has exactly QS real steps
+      if (pass_rows <= 8) run_units_pipe(std::false_type{});
       else run_units_pipe(std::true_type{});
       return;
     }
@@ -708,7 +720,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
             const float x0 = sc * val[4 * h], x1 = sc * val[4 * h + 1], x2 = sc * val[4 * h + 2],
                         x3 = sc * val[4 * h + 3];
             if (p.ksplit > 1) {  // partial sum of this K range (the launcher allows this for CQ_EPI_NONE only)
-              float* dst = p.partials + (size_t)blockIdx.z * p.part_stride + (size_t)m * N + row;
+              float* dst = p.partials + (size_t)kz * p.part_stride + (size_t)m * N + row;
               *reinterpret_cast<float4*>(dst) = make_float4(x0, x1, x2, x3);
               continue;
             }
@@ -899,7 +911,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void gemm_small_kernel(const GemmAr
           const int row = u * 64 + (r >> 3) * 32 + ((r >> 2) & 1) * 16 + g4 * 4 + (r & 3);
           const float x0 = sc16 * val[0], x1 = sc16 * val[1];
           if (p.ksplit > 1) {  // partial sum of this K range (CQ_EPI_NONE only)
-            float* dst = p.partials + (size_t)blockIdx.z * p.part_stride + (size_t)m * N + row;
+            float* dst = p.partials + (size_t)kz * p.part_stride + (size_t)m * N + row;
             *reinterpret_cast<float2*>(dst) = make_float2(x0, x1);
           } else if constexpr (EPI == CQ_EPI_SWIGLU) {
             const float h0 = x0 / (1.f + __expf(-x0)) * x1;
@@ -938,8 +950,8 @@ cq_status launch_small_ring(const GemmArgs& a, int G, hipStream_t s) {
   const cq_status cst = cq_configure_lds(kern, kTableBytes + kSlabBytes + kRedBytes, configured, true);
   if (cst != CQ_OK) return cst;
   const int n_units = a.N / 64;
-  const dim3 grid = a.small_hdr ? dim3(G > kListedWorkgroups ? G : kListedWorkgroups, 1, a.ksplit)
-                                : dim3((n_units + a.upw - 1) / a.upw, G, a.ksplit);
+  const dim3 grid = a.small_hdr ? dim3(G > kListedWorkgroups ? G : kListedWorkgroups, 1, a.ksplit * a.halves)
+                                : dim3((n_units + a.upw - 1) / a.upw, G, a.ksplit * a.halves);
   hipLaunchKernelGGL(kern, grid, dim3(64 * kWaves), kTableBytes + kSlabBytes + kRedBytes, s, a);
   return cq_check_launch();
 }
@@ -1003,12 +1015,12 @@ cq_status dispatch_epi(const GemmArgs& a, int G, int qt, int epilogue, int out_k
 // into ranges of at most 4096 that different workgroups stream, and their partial sums are added in a
 // fixed order afterwards.  Plain products only (a nonlinear epilogue needs the whole sum).
 // Block-wise tables on the streaming kernel's pipelined loop: tables of 1024 weights (two K steps per wavefront
-// and table), groups of at most 16 rows (the loop's limit), and K ranges of whole tables that give every wavefront
+// and table), groups of at most 32 rows (the loop's limit: two passes of 16), and K ranges of whole tables that give every wavefront
 // exactly 8 steps (4096 weights) or 4 (2048); a nonlinear epilogue needs all of K in one range.
 bool cq_gemm_blockwise_streams(const cq_codebook_weights* W, int M_total, int epilogue, int max_group_rows) {
   if (kWaves != 8 || cq_is_w2(W) || W->group_k != 1024 || W->K % 2048 != 0) return false;
   const int bound = max_group_rows > 0 && max_group_rows < M_total ? max_group_rows : M_total;
-  if (bound > 16) return false;
+  if (bound > 32) return false;
   return epilogue == CQ_EPI_NONE || W->K == 4096;
 }
 
@@ -1052,11 +1064,11 @@ size_t cq_gemm_partials_bytes(const cq_codebook_weights* W, int M_total, int epi
 }
 
 // The grouping by expert can be folded into a launch when every workgroup of it runs the pipelined unit loop
-// (at most 16 rows per group, a K range of exactly 8 or 7 steps per wavefront) and one lane per assignment
-// suffices: at most 16 tokens (a group has at most one row per token), at most 64 assignments and experts.
+// (at most 32 rows per group, a K range of exactly 8 or 7 steps per wavefront) and one lane per assignment
+// suffices: at most 32 tokens (a group has at most one row per token), at most 64 assignments and experts.
 bool cq_gemm_can_fuse_route(const cq_codebook_weights* W, int T, int E, int S, int top_k, int epilogue) {
   if (kWaves != 8) return false;
-  if (T < 1 || T > 16 || top_k < 1 || T * top_k > 64 || E < 1 || E > 64 || S < 0 || W->G != E + S) return false;
+  if (T < 1 || T > 32 || top_k < 1 || T * top_k > 64 || E < 1 || E > 64 || S < 0 || W->G != E + S) return false;
   // (the 2-bit kernel takes every group of a launch it supports: its workgroups all derive their rows alike)
   if (cq_is_w2(W)) return cq_gemm_w2_supported(W, CQ_A_INT8_CODES, epilogue);
   const int M_total = T * (top_k + S);
@@ -1098,13 +1110,12 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     a.part_stride = (size_t)M_total * W->N;
     // (a whole number of workgroups per (group, K range), at most 256 in all: 56 pairs take 4 each, not 5 --
     // 280 workgroups would run as a full round and a nearly empty one)
-    // Groups of more than 16 rows take the plain unit loop, which is about twice as slow per unit: when such
-    // groups are possible the launch gets twice the workgroups, so that the compute units the fast groups leave
-    // early pick up the rest of the slow ones.
+    // The pipelined unit loop takes 16 rows at a time: when groups of 17..32 rows are possible the launch gets a
+    // second set of workgroups for rows 16.. of such groups (they return at once for the other groups).
     const int row_bound = max_group_rows > 0 && max_group_rows < M_total ? max_group_rows : M_total;
-    const long target = row_bound > 16 ? 512 : 256;
+    a.halves = row_bound > 16 ? 2 : 1;
     const long pairs = (long)W->G * a.ksplit;
-    const long per_pair = pairs < target ? target / pairs : 1;
+    const long per_pair = pairs < 256 ? 256 / pairs : 1;
     long upw = (W->N / 64 + per_pair - 1) / per_pair;
     if (upw < 1) upw = 1;
     a.upw = (int)upw;

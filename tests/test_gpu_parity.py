@@ -471,15 +471,19 @@ def test_gemm_instantiation_matrix(B, a_kind, epi, out_kind, blockwise, prepacke
         assert err.max() < (1e-3 if out_kind == "f16" else 2e-5), f"row {int(err.argmax())}: {err.max():.3e}"
 
 
+@pytest.mark.parametrize("counts,n_extra", [
+    ([8, 12, 0, 5, 16, 1, 9, 7], 0),         # up to 8 tokens and 9..16 tokens: the two forms of the pipelined loop
+    ([17, 32, 3, 20, 0, 25, 16, 9], 0),      # 17..32 rows: two workgroups per run of units (device-built group list)
+    ([24, 2, 31, 16, 17, 0, 8, 32], 64),     # ... with a launch grid over all groups (no 256-row tiles for N + 64)
+])
 @pytest.mark.parametrize("shape", ["gate_up", "down"])
-def test_gemm_streaming_pipeline_many_units(B, shape):
+def test_gemm_streaming_pipeline_many_units(B, shape, counts, n_extra):
     """The pipelined streaming loop with several 64-row units per workgroup (more units than compute units):
     gate/up-shaped (K = 4096: 8 K steps per wavefront, SiLU-gated, f16 output) and down-shaped (K = 14336 cut
     into four ranges of 7 steps per wavefront, f16 rows, partial sums added afterwards).  Exact integers."""
     rng = np.random.default_rng(77)
-    counts = [8, 12, 0, 5, 16, 1, 9, 7]      # up to 8 tokens and 9..16 tokens: the two forms of the pipelined loop
     G, M = len(counts), sum(counts)
-    N, K = (6144, 4096) if shape == "gate_up" else (1024, 14336)
+    N, K = (6144 + n_extra, 4096) if shape == "gate_up" else (1024 + n_extra, 14336)
     idx = rng.integers(0, 256, size=(G, N, K // 2), dtype=np.uint8)
     cent = _integer_block_tables(rng, G, N, 1)[:, :, 0, :].copy()
     acts = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
@@ -1075,6 +1079,9 @@ def test_layer_reduced_shapes(B, name, over):
     ("mixtral_decode", dict(H=4096, I=192, T=16, E=16, top_k=4, S=1)),     # 64 assignments, a shared expert
     ("mixtral_decode", dict(H=3584, I=128, T=13, E=4, top_k=2)),           # 7 K steps per wavefront, 9..13-row groups
     ("mixtral_decode", dict(H=3584, I=192, T=7, E=8, top_k=3, S=2)),
+    ("mixtral_decode", dict(H=4096, I=128, T=32, E=2, top_k=2)),           # 32-row groups: both halves of every group
+    ("mixtral_decode", dict(H=4096, I=256, T=29, E=4, top_k=2)),           # groups around 16 rows
+    ("mixtral_decode", dict(H=4096, I=192, T=21, E=8, top_k=3, S=1)),      # 63 assignments, a shared expert of 21 rows
 ])
 def test_layer_grouping_folded_into_gate_up(B, name, over):
     """Decode-sized batches whose gate/up product has K = 4096 or 3584: the front launch selects the experts and
