@@ -1138,8 +1138,9 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
   if (large) {
     // the host does not know which groups are small: a device-built list spreads exactly those over
     // the grid (a grid over all groups would leave most workgroups without work)
-    st = cq_gemm_build_lists(W, group_offsets, M_total, small_max,
-                             W->G > kListedWorkgroups ? W->G : kListedWorkgroups, large_ws, &a.small_hdr,
+    // (the listed workgroups exist once per K range: a K-split launch lists fewer per range)
+    const int listed = kListedWorkgroups / a.ksplit;
+    st = cq_gemm_build_lists(W, group_offsets, M_total, small_max, W->G > listed ? W->G : listed, large_ws, &a.small_hdr,
                              &a.small_ids, s, cq_gemm_large_tail_split(W, epilogue, out_kind));
     if (st != CQ_OK) return st;
   }

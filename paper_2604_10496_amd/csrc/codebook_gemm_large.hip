@@ -111,7 +111,7 @@ constexpr int epilogue_row_stride(int epi, int outk) {
 template <bool F16, int EPI, int OUTK, int C, int D, bool BLK, bool PRE>
 __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, const int mrow0, const int mcnt,
                                            const int rt, const int kz = 0, const int kS = 1, const int tail_row0 = 0) {
-  constexpr bool kTail = !BLK && EPI == CQ_EPI_NONE && OUTK == CQ_OUT_F32 && C <= 4;
+  constexpr bool kTail = !BLK && EPI == CQ_EPI_NONE && OUTK == CQ_OUT_F32;
   constexpr int CT = 32 * C;
   constexpr uint32_t kBufBytes = CT * kStepBytes;  // one activation tile: CT tokens x 128 bytes
 
@@ -421,7 +421,8 @@ __device__ __forceinline__ void large_tile(const LargeArgs& p, const int grp, co
 template <bool F16, int EPI, int OUTK, bool BLK, bool PRE>
 __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   const int kS = p.tail_part ? p.n_tiles[6] : 1;   // K parts of a narrow tile
-  const int n256 = p.n_tiles[0] * p.row_tiles, n128 = p.n_tiles[1] * p.row_tiles * kS,
+  const int kS256 = p.tail_part && p.tail_abs ? p.n_tiles[7] : 1;   // ... of a 256-token tile (launches of few tiles)
+  const int n256 = p.n_tiles[0] * p.row_tiles * kS256, n128 = p.n_tiles[1] * p.row_tiles * kS,
             n64 = p.n_tiles[5] * p.row_tiles * kS;
   const int per256 = (n256 + 7) >> 3, per128 = (n128 + 7) >> 3, per64 = (n64 + 7) >> 3;
   const int xcd = blockIdx.x & 7;
@@ -429,9 +430,10 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
   if (slot < per256) {
     const int work = xcd * per256 + slot;
     if (work >= n256) return;
-    const int tile = work / p.row_tiles, rt = work - tile * p.row_tiles;
+    const int item = work / kS256, kz = work - item * kS256;
+    const int tile = item / p.row_tiles, rt = item - tile * p.row_tiles;
     const int32_t* t = p.tiles + tile * 4;
-    large_tile<F16, EPI, OUTK, 8, 4, BLK, PRE>(p, t[0], t[1], t[2], rt);
+    large_tile<F16, EPI, OUTK, 8, 4, BLK, PRE>(p, t[0], t[1], t[2], rt, kz, kS256, t[1]);
     return;
   }
   slot -= per256;
@@ -460,14 +462,15 @@ __global__ __launch_bounds__(256, 1) void gemm_large_kernel(const LargeArgs p) {
 // blockIdx.y: entry of the 128-token list, then of the 64-token list; blockIdx.x: 1024 columns; blockIdx.z: 8 rows.
 constexpr int kTailSumRows = 8;
 __global__ __launch_bounds__(256) void tail_sum_kernel(const LargeArgs p, int cap128) {
-  const int kS = p.n_tiles[6];
+  // blockIdx.y: entries of the 128-token list, of the 64-token list, then (launches of few tiles) of the 256-token list
+  const int list = (int)blockIdx.y < cap128 ? 0 : (int)blockIdx.y < 2 * cap128 ? 1 : 2;
+  const int j = (int)blockIdx.y - list * cap128;
+  const int kS = list == 2 ? p.n_tiles[7] : p.n_tiles[6];
   if (kS <= 1) return;
-  const bool is64 = (int)blockIdx.y >= cap128;
-  const int j = is64 ? (int)blockIdx.y - cap128 : (int)blockIdx.y;
-  if (j >= (is64 ? p.n_tiles[5] : p.n_tiles[1])) return;
-  const int32_t* t = (is64 ? p.tiles64 : p.tiles128) + j * 4;
+  if (j >= (list == 0 ? p.n_tiles[1] : list == 1 ? p.n_tiles[5] : p.n_tiles[0])) return;
+  const int32_t* t = (list == 0 ? p.tiles128 : list == 1 ? p.tiles64 : p.tiles) + j * 4;
   const int mrow0 = t[1], mcnt = t[2];
-  const int row0 = p.tail_abs ? mrow0 : is64 ? p.tail_rows128 + j * 64 : j * 128;
+  const int row0 = p.tail_abs ? mrow0 : list == 1 ? p.tail_rows128 + j * 64 : j * 128;
   const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
   const int r0 = blockIdx.z * kTailSumRows;
   if (c >= p.N || r0 >= mcnt) return;
@@ -551,13 +554,14 @@ __global__ __launch_bounds__(256) void convert_rows_kernel(const void* __restric
 // than 128 rows remain), then one of 128 or (up to 64 rows left) 64, in group order (deterministic), and list the non-empty groups with up
 // to `small_max` rows for the streaming kernel, together with a split of their 64-row units over
 // `small_wgs` workgroups.  counts: [0] 256-wide tiles, [1] 128-wide tiles, [2] small groups,
-// [3] units per workgroup, [4] workgroups per small group, [5] 64-wide tiles, [6] K parts of the narrow tiles.
+// [3] units per workgroup, [4] workgroups per small group, [5] 64-wide tiles, [6] K parts of the narrow tiles,
+// [7] K parts of the 256-wide tiles.
 __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __restrict__ offsets, int G, int small_max,
                                                            int n_units, int small_wgs,
                                                            int32_t* __restrict__ tiles256, int32_t* __restrict__ tiles128,
                                                            int32_t* __restrict__ tiles64,
                                                            int32_t* __restrict__ small_groups,
-                                                           int32_t* __restrict__ counts, int split_max) {
+                                                           int32_t* __restrict__ counts, int split_max, int split_all) {
   __shared__ int n256[1024], n128[1024], n64[1024], nsm[1024];
   __shared__ int base256, base128, base64, basesm;
   const int tid = threadIdx.x;
@@ -625,6 +629,12 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
       int parts = 1;
       while (parts < split_max && narrow > 0 && narrow * parts * 2 <= 256) parts *= 2;
       counts[6] = parts;
+      // [7] K parts of the 256-token tiles: a launch of few tiles in all (split_all: its partial sums are kept by
+      // sorted row, so any tile can have them) leaves most of the chip idle for a whole K loop otherwise
+      const int all = narrow + base256 * (n_units / 4);
+      parts = 1;
+      while (split_all && parts < split_max && base256 > 0 && all * parts * 2 <= 256) parts *= 2;
+      counts[7] = parts;
     }
     // fewest units per workgroup such that all small groups fit into small_wgs workgroups
     int upw = 1, chunks = n_units;
@@ -676,7 +686,7 @@ cq_status launch_both(LargeArgs a, const int32_t* t256, const int32_t* t128, con
   if (st != CQ_OK) return st;
   // worst case of the kernel's per-XCD shares (a group ends in at most one 128- or 64-token tile, but the
   // two lists round up separately): ceil(n256/8) + ceil(n128/8) + ceil(n64/8) slots on each of 8 XCDs
-  const long w256 = (long)max256 * a.row_tiles,
+  const long w256 = (long)max256 * a.row_tiles * (a.tail_part && a.tail_abs ? kTailSplitMax : 1),
              w128 = (long)max128 * a.row_tiles * (a.tail_part ? kTailSplitMax : 1);   // (narrow tiles may come in K parts)
   const long grid = ((w256 + 7) / 8 + (w128 + 7) / 8 + 1) * 8;
   if (grid <= 0) return CQ_OK;
@@ -777,13 +787,15 @@ cq_status cq_gemm_build_lists(const cq_codebook_weights* W, const int32_t* group
                               hipStream_t s, bool tail_split) {
   int cap256, cap128;
   cq_large_tile_caps(W->G, M_total, &cap256, &cap128);
+  bool split_all = false;
+  if (tail_split) (void)tail_slice_rows(W->G, M_total, &split_all);   // partial sums by sorted row: any tile may split
   int32_t* counts = (int32_t*)workspace;
   int32_t* t256 = counts + 64;
   int32_t* t128 = t256 + (size_t)cap256 * 4;
   int32_t* t64 = t128 + (size_t)cap128 * 4;
   int32_t* small = t64 + (size_t)cap128 * 4;
   hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, s, group_offsets, W->G, small_max, W->N / 64, small_wgs,
-                     t256, t128, t64, small, counts, tail_split ? kTailSplitMax : 1);
+                     t256, t128, t64, small, counts, tail_split ? kTailSplitMax : 1, split_all ? 1 : 0);
   *small_hdr = counts + 2;
   *small_ids = small;
   return cq_check_launch();
@@ -858,9 +870,11 @@ cq_status cq_gemm_large_launch(const cq_codebook_weights* W, const void* A, int 
                            : dispatch_large<false>(a, epilogue, out_kind, t256, t128, counts, cap256, cap128, narrow, s);
   if (st != CQ_OK || !tail) return st;
   // (a launch of a few dozen workgroups that return at once when the builder chose not to split)
+  a.tiles = t256;
   a.tiles128 = t128;
   a.tiles64 = t128 + (size_t)cap128 * 4;
   a.n_tiles = counts;
-  hipLaunchKernelGGL(tail_sum_kernel, dim3((W->N / 4 + 255) / 256, 2 * cap128, 128 / kTailSumRows), dim3(256), 0, s, a, cap128);
+  hipLaunchKernelGGL(tail_sum_kernel, dim3((W->N / 4 + 255) / 256, 2 * cap128 + (a.tail_abs ? cap256 : 0), (a.tail_abs ? 256 : 128) / kTailSumRows),
+                     dim3(256), 0, s, a, cap128);
   return cq_check_launch();
 }

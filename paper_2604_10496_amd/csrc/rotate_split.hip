@@ -329,7 +329,7 @@ bool cq_rotate_split_supported(int T, int H) {
 // The tile grid must be able to fill a good part of the chip: below that the fp32 kernel, which splits K
 // over workgroups, is faster (measured: T = 512, H = 2048 -> 32 tiles: 72 us against 53 us).
 bool cq_rotate_split_preferred(int T, int H) {
-  return cq_rotate_split_supported(T, H) && (long)((T + kTok - 1) / kTok) * (H / kCols) >= 96;
+  return cq_rotate_split_supported(T, H) && (long)((T + kTok - 1) / kTok) * (H / kCols) >= 48;
 }
 
 extern "C" size_t cq_rotate_quant_split_workspace_bytes(int T, int H) {
