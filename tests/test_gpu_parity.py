@@ -1149,9 +1149,10 @@ def test_layer_blockwise(B, name, over):
     _check_layer(B, cfg, label=f"{name} block-wise {over}")
 
 
-def test_layer_w2_budget(B):
+@pytest.mark.parametrize("T,E", [(12, 4), (27, 4), (40, 8)])   # grouping folded into the launch up to 32 tokens
+def test_layer_w2_budget(B, T, E):
     """A whole layer on W2 weights streamed as stored (gate/up K = 4096 in one range, down K = 7168 in one range)."""
-    cfg = synth.small_variant(synth.CONFIGS["mixtral_decode_w2"], H=4096, I=7168, E=4, T=12)
+    cfg = synth.small_variant(synth.CONFIGS["mixtral_decode_w2"], H=4096, I=7168, E=E, T=T)
     _check_layer(B, cfg, label="mixtral_decode_w2-reduced")
 
 
