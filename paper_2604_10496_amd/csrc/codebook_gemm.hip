@@ -1114,8 +1114,11 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     // second set of workgroups for rows 16.. of such groups (they return at once for the other groups).
     const int row_bound = max_group_rows > 0 && max_group_rows < M_total ? max_group_rows : M_total;
     a.halves = row_bound > 16 ? 2 : 1;
+    // (when groups above 16 rows are likely -- 8 rows per group on average -- the workgroups are half as long, so
+    // that the second halves, which start when a compute unit comes free, do not add a whole round)
+    const long target = a.halves == 2 && (long)M_total >= 8L * W->G ? 512 : 256;
     const long pairs = (long)W->G * a.ksplit;
-    const long per_pair = pairs < 256 ? 256 / pairs : 1;
+    const long per_pair = pairs < target ? target / pairs : 1;
     long upw = (W->N / 64 + per_pair - 1) / per_pair;
     if (upw < 1) upw = 1;
     a.upw = (int)upw;
