@@ -43,11 +43,17 @@ def _stale(src: str, obj: str) -> bool:
 
 def _split_resource_remarks(lines):
     """Separates hipcc's kernel-resource-usage remarks ({kernel: {field: value}}) from its other output."""
-    usage, rest, cur, skip = {}, [], None, 0
+    usage, rest, cur, skip, held = {}, [], None, 0, []
     for l in lines:
         if skip:                      # the two source-excerpt lines clang prints under a remark
             skip -= 1
             continue
+        if l.startswith("In file included from"):   # belongs to the diagnostic that follows
+            held.append(l)
+            continue
+        if "[-Rpass-analysis=kernel-resource-usage]" not in l:
+            rest.extend(held)
+        held = []
         if "[-Rpass-analysis=kernel-resource-usage]" in l:
             body = l.split("remark:", 1)[1].rsplit("[-Rpass-analysis", 1)[0].strip()
             if body.startswith("Function Name:"):
@@ -94,7 +100,7 @@ def _compile(src: str, force: bool = True) -> str:
 def build_library(verbose: bool = True, force: bool = True) -> str:
     """force=False recompiles only sources older than their object (development); the default compiles all."""
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as pool:
+    with ThreadPoolExecutor(max_workers=8) as pool:
         objs = list(pool.map(lambda s: _compile(s, force), sources()))
     # no rpath to a particular ROCm: when torch is imported first its HIP runtime (same soname) is
     # already mapped and is the one this library binds to, so streams and pointers are shared.

@@ -3,7 +3,7 @@
 // centroid x 4-bit activation value is precomputed, and a (weight index, activation code) pair then selects
 // one product, which is accumulated -- no multiplication in the inner loop.
 //
-// This is the comparison path for the matrix-core kernels (codebook_gemm.hip, codebook_gemm_large.hip), built
+// This is the comparison path for the matrix-core kernels (codebook_gemm_small.h, codebook_gemm_large.hip), built
 // to measure what the paper's scheme costs on gfx950 without its hardware changes: every multiply-accumulate
 // becomes one LDS read plus one addition, so the kernel is bound by the LDS read rate (64 lanes every two
 // clocks per compute unit), far below the matrix cores.

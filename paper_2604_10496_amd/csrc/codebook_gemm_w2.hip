@@ -8,7 +8,7 @@
 // ds_read_b64 returns four MFMA operands: half the instructions per weight of the pair table of the 4-bit
 // kernel, which is what lets the kernel follow the halved byte stream.  A wavefront's lookups hit different
 // banks whatever the indices are (the bank depends on the row slot only).
-// Structure as in the pipelined loop of the 4-bit kernel (codebook_gemm.hip): 8 wavefronts split K (one step =
+// Structure as in the pipelined loop of the 4-bit kernel (codebook_gemm_small.h): 8 wavefronts split K (one step =
 // 128 weights of 32 rows = one 16-byte load per lane; lane (r, g) holds row r, weights [128 s + 64 g, +64));
 // the activations of a wavefront's own K steps stay in registers; LDS holds two tables (2 x 64 KiB) and two
 // buffers of K partials; while unit u is looked up, the table of unit u+1 is written and unit u-1 is finished;
