@@ -75,3 +75,39 @@ def test_static_scratch_refuses_a_batch_that_does_not_fit(B):
     with pytest.raises(B.CqError) as e:
         B.cq_moe_forward_static(layer, X, Y)
     assert e.value.status == 4   # CQ_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("name,over", [
+    ("tiny", dict()),
+    ("mixtral_decode", dict(H=4096, I=256, T=16)),     # five launches, the grouping folded into the gate/up launch
+    ("mixtral_decode", dict(H=512, I=4352, T=24)),     # K-split down product, second halves of the streaming launch
+])
+def test_static_entry_point_replayed_from_a_captured_graph(B, name, over):
+    """The entry point that allocates nothing is meant for callers under HIP graph capture: capture one call,
+    replay it several times with the program's own eager work and synchronisations in between and with new
+    contents in the input buffer, and compare every replay with an eager call on the same input, bit for bit."""
+    import torch
+    cfg = synth.small_variant(synth.CONFIGS[name], **over) if over else synth.CONFIGS[name]
+    L = Hp.make_inputs(cfg)
+    layer = B.device_layer_from_inputs(L)
+    X = torch.from_numpy(L.X).to("cuda")
+    Xg = X.clone()
+    Yg = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device="cuda")
+    B.cq_moe_forward_static(layer, Xg, Yg)      # first call outside the capture: one-time set-up happens here
+    torch.cuda.synchronize()
+    print(f"graph capture: {name} {over}", flush=True)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.cq_moe_forward_static(layer, Xg, Yg)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for rep in range(4):
+        if rep:   # new input in the captured buffer: rows permuted and rescaled
+            perm = torch.from_numpy(rng.permutation(cfg.T)).to("cuda")
+            Xg.copy_(X[perm] * float(1.0 + 0.25 * rep))
+        want = B.cq_moe_forward(layer, Xg).clone()     # eager work between the replays, on its own workspace
+        torch.cuda.synchronize()
+        Yg.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(Yg.cpu().numpy(), want.cpu().numpy()), f"replay {rep}"
