@@ -102,9 +102,8 @@ def cpu_baseline(L, budget_s):
 
 
 def yardsticks(B, torch, info):
-    """Measured ceilings next to the nominal peaks (run first: they also bring the clocks up before the timed
-    steps): a streaming read shaped like the product's index stream, the bare matrix-core loop, and the plain
-    copy of known size that the HBM counters of a profiled run are scaled by."""
+    """Measured ceilings next to the nominal peaks: a streaming read shaped like the product's index stream, the
+    bare matrix-core loop, and the plain copy of known size that the HBM counters of a profiled run are scaled by."""
     probe = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     probe.random_(0, 255)
     for _ in range(3):
