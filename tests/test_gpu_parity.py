@@ -1091,6 +1091,37 @@ def test_layer_grouping_folded_into_gate_up(B, name, over):
     _check_layer(B, cfg, label=f"{name}-folded")
 
 
+@pytest.mark.parametrize("T", [16, 27])
+def test_layer_folded_grouping_with_exactly_tied_experts(B, T):
+    """Two experts with the same router row have bit-identical logits for every token (on the GPU as in the
+    oracle): the decode front end's own top-k must order them by expert id and, when only one place is left,
+    admit the lower id -- ids, weights and the grouping derived from them are compared exactly."""
+    import torch
+    cfg = synth.small_variant(synth.CONFIGS["mixtral_decode"], H=4096, I=128, T=T)
+    L = Hp.make_inputs(cfg)
+    L.Wr[5] = L.Wr[2]
+    if L.bias is not None:
+        L.bias[5] = L.bias[2]
+    ref = Hp.oracle_forward(L)
+    both = int(np.sum(np.any(ref["ids"] == 2, axis=1) & np.any(ref["ids"] == 5, axis=1)))
+    only2 = int(np.sum(np.any(ref["ids"] == 2, axis=1) & ~np.any(ref["ids"] == 5, axis=1)))
+    _say(f"tied experts 2 and 5, T={T}: {both} tokens take both, {only2} tokens take expert 2 at the last place")
+    assert both + only2 > 0 and not np.any(np.any(ref["ids"] == 5, axis=1) & ~np.any(ref["ids"] == 2, axis=1))
+    layer = B.device_layer_from_inputs(L)
+    Y = B.cq_moe_forward(layer, _dev(L.X))
+    torch.cuda.synchronize()
+    mid = B.moe_intermediates(layer, cfg.T)
+    assert np.array_equal(mid["ids"].cpu().numpy(), ref["ids"])
+    assert np.allclose(mid["w"].cpu().numpy(), ref["w"], rtol=W_RTOL, atol=1e-7)
+    assert np.array_equal(mid["offsets"].cpu().numpy()[:cfg.E + 1], ref["offsets"])
+    assert np.array_equal(mid["perm"].cpu().numpy(), ref["perm"])
+    assert np.array_equal(mid["inv_perm"].cpu().numpy(), ref["inv_perm"])
+    q_gpu = mid["Q"].cpu().numpy()
+    clean = np.array([t for t in range(cfg.T) if np.array_equal(q_gpu[t], ref["q"][t])])
+    assert clean.size >= cfg.T // 2    # (tokens with a code at a rounding tie are left to the other layer tests)
+    assert Hp.row_rel_l2(Y.cpu().numpy()[clean], ref["Y"][clean]).max() <= OUT_TOL
+
+
 @pytest.mark.parametrize("name,over", [
     ("tiny", dict(h_bits=8)),                                              # I = 512: a power of two
     ("mixtral_decode", dict(H=512, I=1792, T=16, h_bits=8)),               # I = 28 * 64
