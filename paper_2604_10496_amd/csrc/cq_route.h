@@ -86,6 +86,45 @@ __device__ __forceinline__ void wave_topk(const float (&val)[NSLOT], int nslot, 
   __syncthreads();  // the scratch arrays may be reused by the caller's next token
 }
 
+// Top-k of one token by one wavefront on its own, for at most 64 experts: lane e holds the logit of expert e.  No
+// LDS and no barrier (only this wavefront's lanes take part): the k-th largest key by the same bitwise descent,
+// ties admitted in ascending expert id, the selected lanes ranked by (logit descending, id ascending) against each
+// other through lane reads, and one lane permutation that brings the pair of rank r to lane r.  Results as
+// wave_topk writes them: ids in rank order and the softmax over the selected logits.  Called by all 64 lanes.
+__device__ __forceinline__ void wave_topk_regs(float val, int E, int k, int lane, int32_t* ids_out, float* w_out) {
+  const uint64_t lt = lanemask_lt(lane);
+  const bool valid = lane < E;
+  const uint32_t key = valid ? order_key(val) : 0u;
+  uint32_t kth = 0u;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = kth | (1u << bit);
+    if (__popcll(__ballot(valid && key >= cand)) >= k) kth = cand;
+  }
+  const int need = k - __popcll(__ballot(valid && key > kth));   // how many of the keys equal to kth are admitted
+  const uint64_t m_eq = __ballot(valid && key == kth);
+  const bool sel = valid && (key > kth || (key == kth && __popcll(m_eq & lt) < need));
+  const uint64_t m_sel = __ballot(sel);
+  int rank = 0;
+  for (uint64_t m = m_sel; m; m &= m - 1) {
+    const int j = __ffsll((long long)m) - 1;
+    const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)key, j);
+    rank += (kj > key || (kj == key && j < lane)) ? 1 : 0;
+  }
+  // selected lanes go to lane `rank`, the others fill the lanes from k on in order: a permutation
+  const int dest = sel ? rank : k + __popcll(~m_sel & lt);
+  const int id_sorted = __builtin_amdgcn_ds_permute(dest << 2, lane);
+  const float v_sorted = __int_as_float(__builtin_amdgcn_ds_permute(dest << 2, __float_as_int(val)));
+  const float top = __shfl(v_sorted, 0);
+  const float ex = lane < k ? expf(v_sorted - top) : 0.f;
+  float sum = ex;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+  if (lane < k) {
+    ids_out[lane] = id_sorted;
+    w_out[lane] = ex / sum;
+  }
+}
+
 // a5 folded into a product launch for decode-sized batches (cq_route_fuse): the rows of group `grp`, derived by
 // one wavefront from the selected expert ids.  There are at most 64 assignments (token, choice), one per lane,
 // numbered a = token * top_k + choice; the rows of expert e are the assignments that chose e, in ascending a, and

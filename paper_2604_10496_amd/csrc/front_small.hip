@@ -32,10 +32,6 @@ __global__ __launch_bounds__(kFrontThreads) void front_small_kernel(
     float* __restrict__ topk_w) {
   __shared__ float red[16];
   __shared__ float lred[16][kFrontMaxE];
-  __shared__ float s_logit[64];
-  __shared__ uint32_t s_key[64];
-  __shared__ int s_id[64];
-  __shared__ float s_val[64], s_sorted[64];
   const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
   float4 v[NC];
@@ -95,20 +91,19 @@ __global__ __launch_bounds__(kFrontThreads) void front_small_kernel(
   for (int i = 1; i < 16; ++i) amax = fmaxf(amax, red[i]);
   const float s = amax == 0.f ? 1.f : amax / qmax;
   if (tid == 0) scale[t] = s;
-  if (tid < E) {
-    float x = lred[0][tid];
+  {
+    float x = 0.f;
+    if (tid < E) {
+      x = lred[0][tid];
 #pragma unroll
-    for (int i = 1; i < 16; ++i) x += lred[i][tid];
-    if (bias) x += bias[tid];
-    logits[(size_t)t * E + tid] = x;
-    s_logit[tid] = x;
-  }
-  if (topk_ids) {  // (uniform) a4 for this token: wavefront 0 selects, the others only keep the barriers company
-    __syncthreads();
-    const bool sel = wave == 0;
-    const float val[1] = {(sel && lane < E) ? s_logit[lane] : 0.f};
-    cq_route::wave_topk<1>(val, 1, E, top_k, sel, lane, s_key, s_id, s_val, s_sorted, topk_ids + (size_t)t * top_k,
-                           topk_w + (size_t)t * top_k, nullptr);
+      for (int i = 1; i < 16; ++i) x += lred[i][tid];
+      if (bias) x += bias[tid];
+      logits[(size_t)t * E + tid] = x;
+    }
+    // a4 for this token: the logits are in the lanes of wavefront 0, which selects on its own (no LDS, no
+    // barrier) while the other wavefronts go on to the codes
+    if (topk_ids && wave == 0)   // (uniform per wavefront)
+      cq_route::wave_topk_regs(x, E, top_k, lane, topk_ids + (size_t)t * top_k, topk_w + (size_t)t * top_k);
   }
 
   // ---- integer codes: round to nearest, ties to even (v_rndne_f32) ----
