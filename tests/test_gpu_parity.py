@@ -271,7 +271,10 @@ def _rand_weights(rng, G, N, K, cent=None):
                                         # end of the groups are cut into K parts whose partial sums are added
                                         # afterwards (4, 2 or 1 parts, chosen on the device from the tile counts)
                                         (512, 14336, [150, 300, 70, 31]), (256, 8192, [200, 64, 129, 0, 90]),
-                                        (2048, 8192, [100, 50, 520]), (256, 9088, [77])])
+                                        (2048, 8192, [100, 50, 520]), (256, 9088, [77]),
+                                        # K = 2048: four steps per wavefront, the plain unit loop (launch grid over all
+                                        # groups, and the device-built group list next to large tiles)
+                                        (192, 2048, [5, 16, 0, 9, 30]), (256, 2048, [40, 7, 20, 32])])
 def test_gemm_integer_centroids_exact(B, N, K, counts, prepacked):
     """Centroids k-8 and integer codes: every partial sum is an integer below 2^24, so the result must
     equal the exact integer product whatever the summation order."""
@@ -1082,6 +1085,7 @@ def test_layer_reduced_shapes(B, name, over):
     ("mixtral_decode", dict(H=4096, I=128, T=32, E=2, top_k=2)),           # 32-row groups: both halves of every group
     ("mixtral_decode", dict(H=4096, I=256, T=29, E=4, top_k=2)),           # groups around 16 rows
     ("mixtral_decode", dict(H=4096, I=192, T=21, E=8, top_k=3, S=1)),      # 63 assignments, a shared expert of 21 rows
+    ("dsv2lite", dict(H=2048, I=192, T=10, E=16, top_k=6)),                # K = 2048: not folded (plain unit loop); 2 shared experts
 ])
 def test_layer_grouping_folded_into_gate_up(B, name, over):
     """Decode-sized batches whose gate/up product has K = 4096 or 3584: the front launch selects the experts and
