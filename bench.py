@@ -55,6 +55,10 @@ def parse_args():
                     help="default workload only: skip the Mixtral-shaped prefill leg of the metric")
     ap.add_argument("--prefill-steps", type=int, default=10)
     ap.add_argument("--prefill-warmup", type=int, default=3)
+    ap.add_argument("--sweep-tokens", default="",
+                    help="comma-separated batch sizes: instead of the benchmark line, print the step time of the "
+                         "workload's layer at each of them (its first T tokens; looks for cliffs between the "
+                         "decode and the prefill regime)")
     ap.add_argument("--compare-lut", action="store_true",
                     help="A4 workloads: also time the gate/up product in the lookup formulation (product tables)")
     return ap.parse_args()
@@ -141,6 +145,37 @@ def prime(B, torch, info, seconds=0.3):
     while time.perf_counter() - t0 < seconds:
         B.cq_mfma_loop(info["cu_count"] * 8, 200)
         torch.cuda.synchronize()
+
+
+def sweep_tokens(B, torch, synth, info, name, sizes):
+    """Step time of the named workload's layer on its first T tokens, for every T in `sizes` (back-to-back steps
+    between two host synchronisations, stage times from the event-timed entry point)."""
+    cfg = synth.CONFIGS[name]
+    L = synth.make_layer(cfg)
+    layer = B.device_layer_from_inputs(L)
+    Xall = torch.from_numpy(L.X).to("cuda")
+    prime(B, torch, info)
+    rows = []
+    for T in sizes:
+        T = min(int(T), cfg.T)
+        X = Xall[:T].contiguous()
+        Y = torch.empty((T, cfg.H), dtype=torch.float32, device="cuda")
+        for _ in range(10):
+            B.cq_moe_forward(layer, X, Y)
+        torch.cuda.synchronize()
+        n = 100 if T <= 512 else 20
+        t0 = time.perf_counter()
+        for _ in range(n):
+            B.cq_moe_forward(layer, X, Y)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / n
+        acc = np.zeros(len(B.STAGES))
+        for _ in range(20):
+            _, ms = B.cq_moe_forward_timed(layer, X, Y)
+            acc += [ms[k] for k in B.STAGES]
+        rows.append({"tokens": T, "us_per_layer": dt * 1e6, "tokens_per_s": T / dt,
+                     "stage_us": dict(zip(B.STAGES, (acc / 20 * 1e3).tolist()))})
+    return rows
 
 
 def measure(B, torch, synth, info, name, steps, warmup, n_stage):
@@ -263,6 +298,10 @@ def main():
     B.load_library()
     torch.cuda.set_device(0)
     info = B.cq_device_info()
+    if args.sweep_tokens:
+        sizes = [int(v) for v in args.sweep_tokens.split(",") if v.strip()]
+        print(json.dumps({"workload": args.workload, "sweep": sweep_tokens(B, torch, synth, info, args.workload, sizes)}))
+        return
     read_gbps, mfma_tflops = yardsticks(B, torch, info)
 
     n_stage = 100 if synth.CONFIGS[args.workload].T <= 1024 else 20
