@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restri
   if (Me <= 0 || Me > max_rows) return;
   const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (c >= N) return;
-  for (int m = m0; m < m0 + Me; ++m) {
+  for (int m = m0 + blockIdx.z; m < m0 + Me; m += gridDim.z) {   // (blockIdx.z: rows of the group in parallel)
     const size_t at = (size_t)m * N + c;
     float4 acc = *reinterpret_cast<const float4*>(partials + at);
     for (int q = 1; q < ksplit; ++q) {
@@ -180,7 +180,7 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
       *ksplit_left = a.ksplit;  // the caller adds the partial sums itself
       return st;
     }
-    const dim3 grid((W->N / 4 + 255) / 256, W->G);
+    const dim3 grid((W->N / 4 + 255) / 256, W->G, 16);   // (z: up to 16 rows of a group at a time)
     if (out_kind == CQ_OUT_F16)
       hipLaunchKernelGGL(sum_partials_kernel<CQ_OUT_F16>, grid, dim3(256), 0, s, a.partials, a.part_stride, a.ksplit,
                          group_offsets, 0x7fffffff, W->N, out);
@@ -200,7 +200,7 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     if (ksplit_left && !large) {
       *ksplit_left = a.ksplit;  // the caller adds the partial sums itself (they are all there is)
     } else {
-      const dim3 grid((W->N / 4 + 255) / 256, W->G);
+      const dim3 grid((W->N / 4 + 255) / 256, W->G, 16);   // (z: up to 16 rows of a group at a time)
       if (out_kind == CQ_OUT_F16)
         hipLaunchKernelGGL(sum_partials_kernel<CQ_OUT_F16>, grid, dim3(256), 0, s, a.partials, a.part_stride, a.ksplit,
                            group_offsets, a.max_rows, W->N, out);

@@ -88,6 +88,11 @@ bool cq_hadamard_supported(int I);
 cq_status cq_hadamard_quant_launch(const float* Hin, int M, int I, int bits, int8_t* Q, uint16_t* Q16, float* scale,
                                    float* HR, hipStream_t s);
 
+// a5 alone (one workgroup) for decode-sized batches whose experts the front launch has selected
+bool cq_group_small_supported(int T, int E, int top_k);
+cq_status cq_group_small_launch(int32_t* topk_ids, float* topk_w, int T, int E, int top_k, int n_shared,
+                                int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm, int32_t* src_token,
+                                hipStream_t s);
 cq_status cq_topk_launch(const float* logit_partials, int ksplit, const float* bias, int T, int E, int top_k,
                          float* logits_out, int32_t* topk_ids, float* topk_w, hipStream_t s);
 size_t cq_permute_workspace_bytes(int T, int E, int top_k);

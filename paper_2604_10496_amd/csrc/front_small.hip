@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kFrontThreads) void front_small_kernel(
 bool cq_front_small_supported(int T, int H, int E, int top_k) {
   // the limits of the one-workgroup routing kernel that follows, and of this kernel's registers
   return (long)T * top_k <= 1024 && E <= kFrontMaxE && H <= 2 * 4 * kFrontThreads && H % 4 == 0 &&
-         (long)T * E * H <= (1L << 22);
+         (long)T * E * H <= (1L << 23);
 }
 
 cq_status cq_front_small_launch(const float* partials, int ksplit, int T, int H, int act_bits, const float* Wr,

@@ -181,12 +181,15 @@ cq_status run_layer(const cq_layer* L, const float* X, int T, float* Y, void* wo
     // when the gate/up launch can do the grouping itself, the front launch also selects the experts and
     // the routing launch falls away
     fuse_route = cq_gemm_can_fuse_route(&L->gate_up, T, L->E, L->S, L->top_k, CQ_EPI_SWIGLU);
+    // (the front launch selects the experts whenever a launch that only groups can follow it)
+    const bool front_topk = fuse_route || cq_group_small_supported(T, L->E, L->top_k);
     st = cq_front_small_launch(part, p.ksplit, T, L->H, L->act_bits, L->Wr, L->bias, L->E, XR, Q, Q16, scale, logits,
-                               L->top_k, fuse_route ? ids : nullptr, fuse_route ? tw : nullptr, hs);
+                               L->top_k, front_topk ? ids : nullptr, front_topk ? tw : nullptr, hs);
     if (st != CQ_OK) return st;
     if (!fuse_route) {
-      st = cq_route_permute(nullptr, nullptr, nullptr, logits, T, L->H, L->E, L->top_k, L->S, logits, ids, tw,
-                            offsets, perm, inv_perm, src_token, scratch, scratch_bytes, stream);
+      st = front_topk ? cq_group_small_launch(ids, tw, T, L->E, L->top_k, L->S, offsets, perm, inv_perm, src_token, hs)
+                      : cq_route_permute(nullptr, nullptr, nullptr, logits, T, L->H, L->E, L->top_k, L->S, logits, ids,
+                                         tw, offsets, perm, inv_perm, src_token, scratch, scratch_bytes, stream);
       if (st != CQ_OK) return st;
     }
     if (!mark(2)) return CQ_ERR_HIP;

@@ -104,7 +104,7 @@ __global__ __launch_bounds__(1024) void route_fused_kernel(const float* logits_i
                                                            int32_t* __restrict__ ids, float* __restrict__ w,
                                                            int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
                                                            int32_t* __restrict__ inv_perm,
-                                                           int32_t* __restrict__ src_token) {
+                                                           int32_t* __restrict__ src_token, int ids_given) {
   __shared__ uint32_t s_key[16][64];
   __shared__ int s_id[16][64];
   __shared__ float s_val[16][64];
@@ -114,7 +114,10 @@ __global__ __launch_bounds__(1024) void route_fused_kernel(const float* logits_i
   __shared__ int s_off[kFusedMaxE + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nslot = (E + 63) / 64;
-  for (int t0 = 0; t0 < T; t0 += 16) {
+  // ids_given: the experts were selected already (ids and w hold them): only the grouping is left
+  if (ids_given)
+    for (int a = tid; a < T * k; a += 1024) s_ids[a] = ids[a];
+  for (int t0 = 0; t0 < (ids_given ? 0 : T); t0 += 16) {
     const int t = t0 + wave;
     const bool active = t < T;
     float val[2] = {0.f, 0.f};
@@ -318,7 +321,7 @@ extern "C" cq_status cq_route_permute(const float* XR, const float* Wr, const fl
     }
     hipLaunchKernelGGL(route_fused_kernel, dim3(1), dim3(1024), 0, s, lg, T, E, top_k, n_shared,
                        XR ? (float*)nullptr : logits_out, topk_ids, topk_w, expert_offsets, perm, inv_perm,
-                       src_token);
+                       src_token, 0);
     return cq_check_launch();
   }
   if (XR) {
@@ -331,4 +334,17 @@ extern "C" cq_status cq_route_permute(const float* XR, const float* Wr, const fl
   if (st != CQ_OK) return st;
   return cq_permute_launch(topk_ids, T, E, top_k, n_shared, expert_offsets, perm, inv_perm, src_token,
                            (char*)workspace + part_bytes, s);
+}
+
+// a5 alone for decode-sized batches whose experts were selected by the front launch: the one-workgroup kernel
+// without its top-k loop.  Requires T * top_k <= 1024 and E <= 128 (cq_group_small_supported).
+bool cq_group_small_supported(int T, int E, int top_k) {
+  return (long)T * top_k <= kFusedMaxAssign && E <= kFusedMaxE;
+}
+cq_status cq_group_small_launch(int32_t* topk_ids, float* topk_w, int T, int E, int top_k, int n_shared,
+                                int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm, int32_t* src_token,
+                                hipStream_t s) {
+  hipLaunchKernelGGL(route_fused_kernel, dim3(1), dim3(1024), 0, s, (const float*)nullptr, T, E, top_k, n_shared,
+                     (float*)nullptr, topk_ids, topk_w, expert_offsets, perm, inv_perm, src_token, 1);
+  return cq_check_launch();
 }

@@ -1068,6 +1068,10 @@ def test_layer_tiny(B):
     ("mixtral_decode", dict(H=512, I=4352, T=32, E=4)),      # groups of 9..32 rows, K-split down product
     ("mixtral_decode", dict(H=4096, I=256, T=24)),
     ("mixtral_decode", dict(H=1024, I=512, T=48)),           # rotation in 5 K chunks
+    # the largest batches that take the decode front end (one workgroup per token, its own top-k) and the
+    # one-workgroup grouping launch behind it
+    ("mixtral_decode", dict(H=4096, I=128, T=200)),
+    ("dsv2lite", dict(H=512, I=192, T=160, E=16)),           # 960 assignments, shared experts
 ])
 def test_layer_reduced_shapes(B, name, over):
     cfg = synth.small_variant(synth.CONFIGS[name], **over)
