@@ -332,6 +332,12 @@ extern "C" cq_status cq_route_permute(const float* XR, const float* Wr, const fl
     st = cq_topk_launch(logits_in, 1, nullptr, T, E, top_k, logits_out, topk_ids, topk_w, s);
   }
   if (st != CQ_OK) return st;
+  // (up to 1024 assignments: one workgroup groups them in one launch instead of the three counting-sort passes)
+  if ((long)T * top_k <= kFusedMaxAssign && E <= kFusedMaxE) {
+    hipLaunchKernelGGL(route_fused_kernel, dim3(1), dim3(1024), 0, s, (const float*)nullptr, T, E, top_k, n_shared,
+                       (float*)nullptr, topk_ids, topk_w, expert_offsets, perm, inv_perm, src_token, 1);
+    return cq_check_launch();
+  }
   return cq_permute_launch(topk_ids, T, E, top_k, n_shared, expert_offsets, perm, inv_perm, src_token,
                            (char*)workspace + part_bytes, s);
 }
