@@ -140,7 +140,11 @@ cq_status cq_gemm_codebook_launch(const cq_codebook_weights* W, const void* A, i
     a.halves = row_bound > 16 ? 2 : 1;
     // (when groups above 16 rows are likely -- 8 rows per group on average -- the workgroups are half as long, so
     // that the second halves, which start when a compute unit comes free, do not add a whole round)
-    const long target = a.halves == 2 && (long)M_total >= 8L * W->G ? 512 : 256;
+    // Where the pipelined loop is not available (other K), a group of 17..32 rows runs the plain loop on one
+    // set of workgroups, several times slower per unit than the small groups around it: many short workgroups
+    // then, so that the compute units the small groups leave early take the rest of the big ones.
+    const bool piped = a.ksteps == 8 * kWaves || (a.ksteps == 7 * kWaves && cq_tables_per_row(W) == 1);
+    const long target = a.halves == 1 ? 256 : !piped ? 1024 : (long)M_total >= 8L * W->G ? 512 : 256;
     const long pairs = (long)W->G * a.ksplit;
     const long per_pair = pairs < target ? target / pairs : 1;
     long upw = (W->N / 64 + per_pair - 1) / per_pair;
