@@ -90,8 +90,10 @@ __device__ __forceinline__ void wave_topk(const float (&val)[NSLOT], int nslot, 
 // LDS and no barrier (only this wavefront's lanes take part): the k-th largest key by the same bitwise descent,
 // ties admitted in ascending expert id, the selected lanes ranked by (logit descending, id ascending) against each
 // other through lane reads, and one lane permutation that brings the pair of rank r to lane r.  Results as
-// wave_topk writes them: ids in rank order and the softmax over the selected logits.  Called by all 64 lanes.
-__device__ __forceinline__ void wave_topk_regs(float val, int E, int k, int lane, int32_t* ids_out, float* w_out) {
+// wave_topk writes them: ids in rank order (also to lds_ids, if given) and the softmax over the selected logits.
+// Called by all 64 lanes.
+__device__ __forceinline__ void wave_topk_regs(float val, int E, int k, int lane, int32_t* ids_out, float* w_out,
+                                               int* lds_ids = nullptr) {
   const uint64_t lt = lanemask_lt(lane);
   const bool valid = lane < E;
   const uint32_t key = valid ? order_key(val) : 0u;
@@ -121,6 +123,7 @@ __device__ __forceinline__ void wave_topk_regs(float val, int E, int k, int lane
   for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
   if (lane < k) {
     ids_out[lane] = id_sorted;
+    if (lds_ids) lds_ids[lane] = id_sorted;
     w_out[lane] = ex / sum;
   }
 }

@@ -117,7 +117,14 @@ __global__ __launch_bounds__(1024) void route_fused_kernel(const float* logits_i
   // ids_given: the experts were selected already (ids and w hold them): only the grouping is left
   if (ids_given)
     for (int a = tid; a < T * k; a += 1024) s_ids[a] = ids[a];
-  for (int t0 = 0; t0 < (ids_given ? 0 : T); t0 += 16) {
+  // at most 64 experts: every wavefront takes its tokens through the register top-k on its own, no barriers
+  if (!ids_given && nslot == 1)
+    for (int t = wave; t < T; t += 16) {
+      const float v = lane < E ? logits_in[(size_t)t * E + lane] : 0.f;
+      if (logits_out && logits_out != logits_in && lane < E) logits_out[(size_t)t * E + lane] = v;
+      wave_topk_regs(v, E, k, lane, ids + (size_t)t * k, w + (size_t)t * k, s_ids + t * k);
+    }
+  for (int t0 = 0; t0 < (ids_given || nslot == 1 ? 0 : T); t0 += 16) {
     const int t = t0 + wave;
     const bool active = t < T;
     float val[2] = {0.f, 0.f};
